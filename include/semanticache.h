@@ -1,0 +1,171 @@
+/*
+ * libsemanticache — C ABI of the SemantiCache compress-then-attend path for AMD MI355X (gfx950).
+ *
+ * Three operations, each a hand-written HIP kernel pipeline behind a plain C call:
+ *
+ *   sc_segment      Sec. 2.2, Eq. 1        delimiter mask            -> chunk offsets
+ *   sc_gsc_merge    Sec. 2.3, Alg. 1/Eq. 2 keys/values + offsets     -> merged keys/values (semantic
+ *                   Sec. 2.4, Eq. 3                                     cores), cluster sizes, lengths
+ *   sc_decode_attn  Sec. 2.4, Eq. 4        query vs. merged cache with the log-size bias
+ *
+ * Conventions shared by all entry points
+ *   - Every data pointer is DEVICE memory owned by the caller; the library neither allocates
+ *     nor frees device memory.  Scratch memory is passed in as `ws` (size from the matching
+ *     *_workspace_bytes query; 256-byte aligned).  `ws` contents are undefined afterwards.
+ *   - Calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL = default stream).
+ *     No call synchronises with the host.  Calls that share a workspace must be stream-ordered.
+ *   - Return value: SC_OK, or an error detected on the host BEFORE anything is launched
+ *     (nothing is written in that case).  Conditions only the device can see (an output
+ *     capacity that turns out too small) are reported in the outputs themselves: the affected
+ *     length entry is set to -1 and no row is written out of bounds.
+ *   - Shapes are row-major; "[B, H, N, d]" means d is the fastest dimension.
+ *   - A "sequence" b has seq_lens[b] <= N_max tokens; positions beyond are never read.
+ *   - Supported head dims: 64 and 128.  Supported element types: fp32 and bf16.
+ */
+#ifndef SEMANTICACHE_H
+#define SEMANTICACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SC_OK = 0,
+    SC_ERR_INVALID_ARG = 1,   /* null pointer, non-positive size, misaligned pointer or stride */
+    SC_ERR_UNSUPPORTED = 2,   /* head dim / dtype / head grouping the kernels do not cover */
+    SC_ERR_CAPACITY = 3,      /* an output capacity that can never hold the result */
+    SC_ERR_WORKSPACE = 4,     /* ws is NULL or smaller than *_workspace_bytes */
+    SC_ERR_RUNTIME = 5        /* the HIP runtime refused a launch; see sc_last_runtime_error */
+} sc_status;
+
+typedef enum { SC_F32 = 0, SC_BF16 = 1 } sc_dtype;
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char *sc_status_string(sc_status status);
+
+/* Text of the last HIP runtime error seen by this thread inside the library ("" if none). */
+const char *sc_last_runtime_error(void);
+
+/* Library version, "major.minor.patch". */
+const char *sc_version(void);
+
+/* ------------------------------------------------------------------------------------------------
+ * sc_segment — semantic chunking (Sec. 2.2, Eq. 1).
+ *
+ * A sequence of n tokens with delimiters at positions p_1 < ... < p_{M-1} becomes the alternating
+ * series (C_1, d_1, C_2, ..., d_{M-1}, C_M): M = (#delimiters + 1) possibly empty chunks separated
+ * by single delimiters.  Encoding per sequence b (row b of `offsets`):
+ *     offsets[0] = 0,  offsets[m] = p_m + 1 (1 <= m < M),  offsets[M] = n + 1,
+ * so chunk m (0-based) covers positions [offsets[m], offsets[m+1] - 1) and the delimiter that closes
+ * it, if any, is position offsets[m+1] - 1 (< n).  num_chunks[b] = M.
+ *
+ *   mask           device u8 [B, N_max] (row stride mask_stride_b bytes); nonzero = delimiter
+ *   seq_lens       device i32 [B], or NULL meaning every sequence has N_max tokens
+ *   offsets        device i32 [B, offsets_cap] (row stride offsets_stride_b elements); needs
+ *                  offsets_cap >= M + 1; N_max + 2 always suffices
+ *   num_chunks     device i32 [B]; set to -1 for a sequence whose M + 1 exceeds offsets_cap
+ *                  (its offsets row is then unspecified but never overrun)
+ *   ws, ws_bytes   unused by the current kernels (sc_segment_workspace_bytes returns 0); may be NULL
+ *
+ * Integer work: results are exact.  Host errors: NULL mask/offsets/num_chunks, B <= 0, N_max <= 0,
+ * offsets_cap < 2, strides smaller than the row.
+ */
+size_t sc_segment_workspace_bytes(int B, int N_max);
+sc_status sc_segment(const uint8_t *mask, int64_t mask_stride_b, const int32_t *seq_lens,
+                     int B, int N_max,
+                     int32_t *offsets, int64_t offsets_stride_b, int offsets_cap,
+                     int32_t *num_chunks,
+                     void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * sc_gsc_merge — Greedy Seed-Based Clustering inside every chunk (Sec. 2.3, Alg. 1 with the cosine
+ * similarity of Eq. 2 on keys only) followed by clustered merging (Sec. 2.4, Eq. 3), independently
+ * for every (sequence, KV head).
+ *
+ * Clustering: in each chunk the first unassigned token becomes a seed and absorbs every later
+ * unassigned token whose key has cosine similarity to the SEED's key strictly greater than tau;
+ * repeat until every token is assigned.  A similarity that is not a number (zero-norm key) never
+ * exceeds tau.  Decisions are taken in fp32 and re-evaluated in fp64 whenever the fp32 value lies
+ * within 1e-4 of tau, so they equal an fp64 evaluation except for similarities within ~1e-13 of tau.
+ *
+ * Merging: each cluster S_t becomes one row (mean of its keys, mean of its values, size |S_t|),
+ * accumulated in fp32.  Output rows of a (sequence, head), in order: for each chunk, its clusters in
+ * order of their seeds, then the chunk's closing delimiter copied bit-for-bit with size 1.  Rows of
+ * size 1 are bit-for-bit copies of their input row (widened exactly if out_dtype is wider).
+ *
+ *   K, V            device [B, Hkv, N_max, d] of in_dtype, addressed as
+ *                   base + b*stride_b + h*stride_h + n*stride_n (+ e), strides in ELEMENTS;
+ *                   the last dimension is contiguous; rows must be 16-byte aligned
+ *   seq_lens        device i32 [B] or NULL (= N_max)
+ *   offsets, num_chunks   as produced by sc_segment (shared by all heads); sequences with
+ *                   num_chunks[b] < 0 are skipped and get comp_lens = -1
+ *   tau             similarity threshold (any real value; the paper uses 0.5..0.9)
+ *   Kc, Vc          device [B, Hkv, cap, d] of out_dtype, contiguous
+ *   counts          device i32 [B, Hkv, cap]; cluster sizes (1 for delimiters)
+ *   comp_lens       device i32 [B, Hkv]; number of rows produced N'(b,h), or -1 if N' > cap
+ *                   (then only the first cap rows are written)
+ *   cluster_id      device i32 [B, Hkv, N_max] or NULL; receives for every token the index of its
+ *                   cluster inside its chunk (-1 for delimiters); positions >= seq_lens[b] untouched
+ *   cap             rows available per (b, h); cap = N_max always suffices
+ *
+ * Host errors: NULL required pointer, B/Hkv/N_max/cap <= 0, d not in {64,128}, bad dtype,
+ * misaligned base pointers or strides not multiples of 16 bytes, workspace too small.
+ */
+size_t sc_gsc_merge_workspace_bytes(int B, int Hkv, int N_max, int d);
+sc_status sc_gsc_merge(const void *K, const void *V, sc_dtype in_dtype,
+                       int64_t stride_b, int64_t stride_h, int64_t stride_n,
+                       const int32_t *seq_lens,
+                       const int32_t *offsets, int64_t offsets_stride_b, const int32_t *num_chunks,
+                       int B, int Hkv, int N_max, int d, float tau,
+                       void *Kc, void *Vc, sc_dtype out_dtype, int cap,
+                       int32_t *counts, int32_t *comp_lens, int32_t *cluster_id,
+                       void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * sc_decode_attn — Proportional Attention for one decode step (Sec. 2.4, Eq. 4):
+ *     O[b,hq] = softmax_t( Q[b,hq] . Kc[b,h,t] * scale + ln(counts[b,h,t]) ) Vc[b,h,t],
+ *     t in [0, comp_lens[b,h]),  h = hq / (Hq / Hkv)   (consecutive query heads share a KV head).
+ * No mask: the query sees every row of the merged cache.  fp32 softmax and accumulation.
+ *
+ *   Q               device [B, Hq, d] of q_dtype, contiguous
+ *   Kc, Vc, counts  device, layout as written by sc_gsc_merge ([B, Hkv, cap, d] of kv_dtype, [B, Hkv, cap])
+ *   comp_lens       device i32 [B, Hkv]; entries <= 0 give O = 0 and lse = -inf for that head group
+ *   scale           logit scale; 0 selects 1/sqrt(d)
+ *   O               device [B, Hq, d] of o_dtype, contiguous
+ *   lse             device f32 [B, Hq] or NULL; natural-log-sum-exp of the biased logits
+ *
+ *   ws              workspace of sc_decode_attn_workspace_bytes; unlike the other workspaces it carries
+ *                   state: its first bytes are split-K arrival counters that must be ZERO when a call
+ *                   starts.  Zero them once with sc_decode_attn_init_workspace (or any memset) after
+ *                   allocating; every call leaves them zero again, so the workspace can be reused
+ *                   by stream-ordered calls without further care.  Two calls that overlap in time
+ *                   need two workspaces.
+ *
+ * Host errors: NULL required pointer, sizes <= 0, Hq not a multiple of Hkv or Hq/Hkv > 8,
+ * d not in {64,128}, bad dtype, workspace too small.
+ */
+size_t sc_decode_attn_workspace_bytes(int B, int Hq, int Hkv, int cap, int d);
+sc_status sc_decode_attn_init_workspace(void *ws, size_t ws_bytes, int B, int Hkv, void *stream);
+sc_status sc_decode_attn(const void *Q, sc_dtype q_dtype,
+                         const void *Kc, const void *Vc, sc_dtype kv_dtype, int cap,
+                         const int32_t *counts, const int32_t *comp_lens,
+                         int B, int Hq, int Hkv, int d, float scale,
+                         void *O, sc_dtype o_dtype, float *lse,
+                         void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Launch-shape knobs for experiments (process-wide, not thread-safe; results never depend on them
+ * beyond floating-point summation order in sc_decode_attn).  Keys: "decode_max_splits",
+ * "decode_min_rows", "gsc_chunks_per_item", "gsc_grid_x".  Return 0 / the value, or -1 for an
+ * unknown key.
+ */
+int sc_tune_set(const char *key, int value);
+int sc_tune_get(const char *key);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SEMANTICACHE_H */

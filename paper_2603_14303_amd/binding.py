@@ -1,0 +1,222 @@
+"""Thin Python binding of libsemanticache (see include/semanticache.h).
+
+Argument marshalling only: torch supplies device memory and the current stream, every step of the
+path runs in the library's HIP kernels.  There is no CPU fallback: if the shared library is missing
+or a call is refused, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsemanticache.so")
+
+SC_OK = 0
+SC_F32, SC_BF16 = 0, 1
+
+_lib = None
+
+
+class SemantiCacheError(RuntimeError):
+    pass
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libsemanticache.so built in-tree (python -m paper_2603_14303_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise SemantiCacheError(
+            "libsemanticache.so is not built; run `python -m paper_2603_14303_amd.build` (needs hipcc)")
+    lib = ctypes.CDLL(LIB_PATH)
+    c = ctypes
+    vp, i32, i64, sz, f32 = c.c_void_p, c.c_int, c.c_int64, c.c_size_t, c.c_float
+    lib.sc_status_string.restype = c.c_char_p
+    lib.sc_status_string.argtypes = [i32]
+    lib.sc_last_runtime_error.restype = c.c_char_p
+    lib.sc_last_runtime_error.argtypes = []
+    lib.sc_version.restype = c.c_char_p
+    lib.sc_version.argtypes = []
+    lib.sc_tune_set.restype = i32
+    lib.sc_tune_set.argtypes = [c.c_char_p, i32]
+    lib.sc_tune_get.restype = i32
+    lib.sc_tune_get.argtypes = [c.c_char_p]
+    lib.sc_segment_workspace_bytes.restype = sz
+    lib.sc_segment_workspace_bytes.argtypes = [i32, i32]
+    lib.sc_segment.restype = i32
+    lib.sc_segment.argtypes = [vp, i64, vp, i32, i32, vp, i64, i32, vp, vp, sz, vp]
+    lib.sc_gsc_merge_workspace_bytes.restype = sz
+    lib.sc_gsc_merge_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    lib.sc_gsc_merge.restype = i32
+    lib.sc_gsc_merge.argtypes = [vp, vp, i32, i64, i64, i64, vp, vp, i64, vp, i32, i32, i32, i32, f32,
+                                 vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.sc_decode_attn_workspace_bytes.restype = sz
+    lib.sc_decode_attn_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+    lib.sc_decode_attn_init_workspace.restype = i32
+    lib.sc_decode_attn_init_workspace.argtypes = [vp, sz, i32, i32, vp]
+    lib.sc_decode_attn.restype = i32
+    lib.sc_decode_attn.argtypes = [vp, i32, vp, vp, i32, i32, vp, vp, i32, i32, i32, i32, f32,
+                                   vp, i32, vp, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+EXPORTED = [
+    "sc_status_string", "sc_last_runtime_error", "sc_version", "sc_tune_set", "sc_tune_get",
+    "sc_segment_workspace_bytes", "sc_segment",
+    "sc_gsc_merge_workspace_bytes", "sc_gsc_merge",
+    "sc_decode_attn_workspace_bytes", "sc_decode_attn_init_workspace", "sc_decode_attn",
+]
+
+
+def _check(status: int, what: str) -> None:
+    if status != SC_OK:
+        lib = load_library()
+        msg = lib.sc_status_string(status).decode()
+        extra = lib.sc_last_runtime_error().decode() if status == 5 else ""
+        raise SemantiCacheError("%s failed: %s %s" % (what, msg, extra))
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _dtype_code(t) -> int:
+    torch = _torch()
+    if t.dtype == torch.float32:
+        return SC_F32
+    if t.dtype == torch.bfloat16:
+        return SC_BF16
+    raise SemantiCacheError("unsupported dtype %s" % t.dtype)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    return _torch().cuda.current_stream().cuda_stream
+
+
+def _require_cuda(*tensors) -> None:
+    for t in tensors:
+        if t is not None and not t.is_cuda:
+            raise SemantiCacheError("all tensors must live on the GPU")
+
+
+def tune_set(key: str, value: int) -> None:
+    if load_library().sc_tune_set(key.encode(), int(value)) != 0:
+        raise SemantiCacheError("unknown tuning key %r" % key)
+
+
+def tune_get(key: str) -> int:
+    return int(load_library().sc_tune_get(key.encode()))
+
+
+# ------------------------------------------------------------------------------------------------
+def sc_segment(mask, seq_lens=None, offsets=None, num_chunks=None):
+    """mask u8 [B, N_max] (device) -> (offsets i32 [B, N_max + 2], num_chunks i32 [B])."""
+    torch = _torch()
+    lib = load_library()
+    _require_cuda(mask, seq_lens, offsets, num_chunks)
+    if mask.dtype != torch.uint8 or mask.dim() != 2 or mask.stride(1) != 1:
+        raise SemantiCacheError("mask must be uint8 [B, N_max] with contiguous rows")
+    B, N = mask.shape
+    if offsets is None:
+        offsets = torch.empty((B, N + 2), dtype=torch.int32, device=mask.device)
+    if num_chunks is None:
+        num_chunks = torch.empty((B,), dtype=torch.int32, device=mask.device)
+    st = lib.sc_segment(_ptr(mask), mask.stride(0), _ptr(seq_lens), B, N, _ptr(offsets), offsets.stride(0),
+                        offsets.shape[1], _ptr(num_chunks), None, 0, _stream())
+    _check(st, "sc_segment")
+    return offsets, num_chunks
+
+
+class Workspace:
+    """Device scratch for one entry point; allocated once through torch, reused across calls."""
+
+    def __init__(self, nbytes: int, device, zero_prefix: int = 0):
+        torch = _torch()
+        self.nbytes = int(nbytes)
+        # torch's caching allocator returns 512-byte aligned blocks
+        self.buf = torch.empty((max(self.nbytes, 256),), dtype=torch.uint8, device=device)
+        assert self.buf.data_ptr() % 256 == 0
+
+    @property
+    def ptr(self) -> int:
+        return self.buf.data_ptr()
+
+
+def gsc_merge_workspace(B: int, Hkv: int, N_max: int, d: int, device) -> Workspace:
+    return Workspace(load_library().sc_gsc_merge_workspace_bytes(B, Hkv, N_max, d), device)
+
+
+def sc_gsc_merge(K, V, offsets, num_chunks, tau: float, seq_lens=None, cap: Optional[int] = None,
+                 out_dtype=None, Kc=None, Vc=None, counts=None, comp_lens=None, cluster_id=None,
+                 want_cluster_id: bool = False, workspace: Optional[Workspace] = None):
+    """K, V [B, Hkv, N_max, d] (device, last dim contiguous) -> (Kc, Vc, counts, comp_lens, cluster_id)."""
+    torch = _torch()
+    lib = load_library()
+    _require_cuda(K, V, offsets, num_chunks, seq_lens, Kc, Vc, counts, comp_lens, cluster_id)
+    if K.dim() != 4 or K.shape != V.shape or K.stride() != V.stride() or K.stride(3) != 1 or K.dtype != V.dtype:
+        raise SemantiCacheError("K and V must be [B, Hkv, N_max, d] with identical strides and dtype")
+    B, H, N, d = K.shape
+    cap = N if cap is None else int(cap)
+    out_dtype = K.dtype if out_dtype is None else out_dtype
+    dev = K.device
+    if Kc is None:
+        Kc = torch.empty((B, H, cap, d), dtype=out_dtype, device=dev)
+    if Vc is None:
+        Vc = torch.empty((B, H, cap, d), dtype=out_dtype, device=dev)
+    if counts is None:
+        counts = torch.empty((B, H, cap), dtype=torch.int32, device=dev)
+    if comp_lens is None:
+        comp_lens = torch.empty((B, H), dtype=torch.int32, device=dev)
+    if cluster_id is None and want_cluster_id:
+        cluster_id = torch.full((B, H, N), -9, dtype=torch.int32, device=dev)
+    if workspace is None:
+        workspace = gsc_merge_workspace(B, H, N, d, dev)
+    for t in (Kc, Vc, counts, comp_lens):
+        if not t.is_contiguous():
+            raise SemantiCacheError("outputs must be contiguous")
+    st = lib.sc_gsc_merge(_ptr(K), _ptr(V), _dtype_code(K), K.stride(0), K.stride(1), K.stride(2),
+                          _ptr(seq_lens), _ptr(offsets), offsets.stride(0), _ptr(num_chunks),
+                          B, H, N, d, float(tau), _ptr(Kc), _ptr(Vc), _dtype_code(Kc), cap,
+                          _ptr(counts), _ptr(comp_lens), _ptr(cluster_id), workspace.ptr, workspace.nbytes, _stream())
+    _check(st, "sc_gsc_merge")
+    return Kc, Vc, counts, comp_lens, cluster_id
+
+
+def decode_attn_workspace(B: int, Hq: int, Hkv: int, cap: int, d: int, device) -> Workspace:
+    lib = load_library()
+    ws = Workspace(lib.sc_decode_attn_workspace_bytes(B, Hq, Hkv, cap, d), device)
+    _check(lib.sc_decode_attn_init_workspace(ws.ptr, ws.nbytes, B, Hkv, _stream()), "sc_decode_attn_init_workspace")
+    return ws
+
+
+def sc_decode_attn(Q, Kc, Vc, counts, comp_lens, scale: float = 0.0, O=None, lse=None, want_lse: bool = False,
+                   workspace: Optional[Workspace] = None):
+    """Q [B, Hq, d]; Kc, Vc [B, Hkv, cap, d]; counts [B, Hkv, cap]; comp_lens [B, Hkv] -> (O [B, Hq, d], lse)."""
+    torch = _torch()
+    lib = load_library()
+    _require_cuda(Q, Kc, Vc, counts, comp_lens, O, lse)
+    B, Hq, d = Q.shape
+    _, Hkv, cap, _ = Kc.shape
+    for t in (Q, Kc, Vc, counts, comp_lens):
+        if not t.is_contiguous():
+            raise SemantiCacheError("inputs must be contiguous")
+    if O is None:
+        O = torch.empty((B, Hq, d), dtype=Q.dtype, device=Q.device)
+    if lse is None and want_lse:
+        lse = torch.empty((B, Hq), dtype=torch.float32, device=Q.device)
+    if workspace is None:
+        workspace = decode_attn_workspace(B, Hq, Hkv, cap, d, Q.device)
+    st = lib.sc_decode_attn(_ptr(Q), _dtype_code(Q), _ptr(Kc), _ptr(Vc), _dtype_code(Kc), cap, _ptr(counts),
+                            _ptr(comp_lens), B, Hq, Hkv, d, float(scale), _ptr(O), _dtype_code(O), _ptr(lse),
+                            workspace.ptr, workspace.nbytes, _stream())
+    _check(st, "sc_decode_attn")
+    return O, lse

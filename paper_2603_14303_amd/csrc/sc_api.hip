@@ -1,0 +1,170 @@
+// C ABI of libsemanticache: argument validation on the host, then the kernel launchers.
+// Everything that can be rejected without touching the device is rejected before any HIP call.
+#include "../../include/semanticache.h"
+
+#include <string.h>
+
+#include "sc_host.h"
+
+namespace sc {
+
+Tuning &tuning() {
+    static Tuning t;
+    return t;
+}
+
+static thread_local char g_last_error[256] = "";
+
+static sc_status runtime_status(hipError_t e) {
+    if (e == hipSuccess) return SC_OK;
+    strncpy(g_last_error, hipGetErrorString(e), sizeof(g_last_error) - 1);
+    g_last_error[sizeof(g_last_error) - 1] = 0;
+    return SC_ERR_RUNTIME;
+}
+
+static bool dtype_ok(int t) { return t == SC_F32 || t == SC_BF16; }
+static size_t elem_size(int t) { return t == SC_BF16 ? 2 : 4; }
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
+
+}  // namespace sc
+
+using namespace sc;
+
+extern "C" {
+
+const char *sc_status_string(sc_status status) {
+    switch (status) {
+        case SC_OK: return "SC_OK";
+        case SC_ERR_INVALID_ARG: return "SC_ERR_INVALID_ARG";
+        case SC_ERR_UNSUPPORTED: return "SC_ERR_UNSUPPORTED";
+        case SC_ERR_CAPACITY: return "SC_ERR_CAPACITY";
+        case SC_ERR_WORKSPACE: return "SC_ERR_WORKSPACE";
+        case SC_ERR_RUNTIME: return "SC_ERR_RUNTIME";
+    }
+    return "SC_ERR_UNKNOWN";
+}
+
+const char *sc_last_runtime_error(void) { return g_last_error; }
+
+const char *sc_version(void) { return "0.1.0"; }
+
+int sc_tune_set(const char *key, int value) {
+    if (!key) return -1;
+    Tuning &t = tuning();
+    if (!strcmp(key, "decode_max_splits")) t.decode_max_splits = value;
+    else if (!strcmp(key, "decode_min_rows")) t.decode_min_rows = value;
+    else if (!strcmp(key, "gsc_chunks_per_item")) t.gsc_chunks_per_item = value;
+    else if (!strcmp(key, "gsc_grid_x")) t.gsc_grid_x = value;
+    else return -1;
+    return 0;
+}
+
+int sc_tune_get(const char *key) {
+    if (!key) return -1;
+    const Tuning &t = tuning();
+    if (!strcmp(key, "decode_max_splits")) return t.decode_max_splits;
+    if (!strcmp(key, "decode_min_rows")) return t.decode_min_rows;
+    if (!strcmp(key, "gsc_chunks_per_item")) return t.gsc_chunks_per_item;
+    if (!strcmp(key, "gsc_grid_x")) return t.gsc_grid_x;
+    return -1;
+}
+
+// ------------------------------------------------------------------------------------------------
+size_t sc_segment_workspace_bytes(int B, int N_max) {
+    (void)B; (void)N_max;
+    return 0;
+}
+
+sc_status sc_segment(const uint8_t *mask, int64_t mask_stride_b, const int32_t *seq_lens, int B, int N_max,
+                     int32_t *offsets, int64_t offsets_stride_b, int offsets_cap, int32_t *num_chunks,
+                     void *ws, size_t ws_bytes, void *stream) {
+    (void)ws; (void)ws_bytes;
+    if (!mask || !offsets || !num_chunks) return SC_ERR_INVALID_ARG;
+    if (B <= 0 || N_max <= 0) return SC_ERR_INVALID_ARG;
+    if (offsets_cap < 2) return SC_ERR_CAPACITY;
+    if (mask_stride_b < N_max || offsets_stride_b < offsets_cap) return SC_ERR_INVALID_ARG;
+    if (!aligned4(offsets) || !aligned4(num_chunks) || (seq_lens && !aligned4(seq_lens))) return SC_ERR_INVALID_ARG;
+    if (B > 65535 * 32) return SC_ERR_UNSUPPORTED;
+    return runtime_status(launch_segment(mask, mask_stride_b, seq_lens, B, N_max, offsets, offsets_stride_b,
+                                         offsets_cap, num_chunks, static_cast<hipStream_t>(stream)));
+}
+
+// ------------------------------------------------------------------------------------------------
+size_t sc_gsc_merge_workspace_bytes(int B, int Hkv, int N_max, int d) {
+    if (B <= 0 || Hkv <= 0 || N_max <= 0) return 0;
+    return gsc_merge_workspace_bytes(B, Hkv, N_max, d);
+}
+
+sc_status sc_gsc_merge(const void *K, const void *V, sc_dtype in_dtype, int64_t stride_b, int64_t stride_h,
+                       int64_t stride_n, const int32_t *seq_lens, const int32_t *offsets, int64_t offsets_stride_b,
+                       const int32_t *num_chunks, int B, int Hkv, int N_max, int d, float tau, void *Kc, void *Vc,
+                       sc_dtype out_dtype, int cap, int32_t *counts, int32_t *comp_lens, int32_t *cluster_id,
+                       void *ws, size_t ws_bytes, void *stream) {
+    if (!K || !V || !offsets || !num_chunks || !Kc || !Vc || !counts || !comp_lens) return SC_ERR_INVALID_ARG;
+    if (B <= 0 || Hkv <= 0 || N_max <= 0) return SC_ERR_INVALID_ARG;
+    if (cap <= 0) return SC_ERR_CAPACITY;
+    if (!dtype_ok(in_dtype) || !dtype_ok(out_dtype)) return SC_ERR_UNSUPPORTED;
+    if (d != 64 && d != 128) return SC_ERR_UNSUPPORTED;
+    if (Hkv > 65535 || B > 65535) return SC_ERR_UNSUPPORTED;
+    const size_t es = elem_size(in_dtype);
+    if (stride_n < d || stride_h < 0 || stride_b < 0) return SC_ERR_INVALID_ARG;
+    if ((stride_n * es) % 16 || (stride_h * es) % 16 || (stride_b * es) % 16) return SC_ERR_INVALID_ARG;
+    if (!aligned16(K) || !aligned16(V) || !aligned16(Kc) || !aligned16(Vc)) return SC_ERR_INVALID_ARG;
+    if (!aligned4(counts) || !aligned4(comp_lens) || !aligned4(offsets) || !aligned4(num_chunks)) return SC_ERR_INVALID_ARG;
+    if (offsets_stride_b < 2) return SC_ERR_INVALID_ARG;
+    if (tau != tau) return SC_ERR_INVALID_ARG;
+    const size_t need = gsc_merge_workspace_bytes(B, Hkv, N_max, d);
+    if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SC_ERR_WORKSPACE;
+
+    GscMergeArgs a;
+    a.K = K; a.V = V; a.in_dtype = static_cast<DType>(in_dtype);
+    a.stride_b = stride_b; a.stride_h = stride_h; a.stride_n = stride_n;
+    a.seq_lens = seq_lens; a.offsets = offsets; a.offsets_stride_b = offsets_stride_b; a.num_chunks = num_chunks;
+    a.B = B; a.Hkv = Hkv; a.N_max = N_max; a.d = d; a.tau = tau;
+    a.Kc = Kc; a.Vc = Vc; a.out_dtype = static_cast<DType>(out_dtype); a.cap = cap;
+    a.counts = counts; a.comp_lens = comp_lens; a.cluster_id = cluster_id; a.ws = ws;
+    return runtime_status(launch_gsc_merge(a, static_cast<hipStream_t>(stream)));
+}
+
+// ------------------------------------------------------------------------------------------------
+size_t sc_decode_attn_workspace_bytes(int B, int Hq, int Hkv, int cap, int d) {
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || cap <= 0 || Hq % Hkv) return 0;
+    return decode_workspace_bytes(B, Hq, Hkv, cap, d);
+}
+
+sc_status sc_decode_attn_init_workspace(void *ws, size_t ws_bytes, int B, int Hkv, void *stream) {
+    if (B <= 0 || Hkv <= 0) return SC_ERR_INVALID_ARG;
+    const size_t state = decode_workspace_state_bytes(B, Hkv);
+    if (!ws || ws_bytes < state || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SC_ERR_WORKSPACE;
+    return runtime_status(launch_decode_init_workspace(ws, state, static_cast<hipStream_t>(stream)));
+}
+
+sc_status sc_decode_attn(const void *Q, sc_dtype q_dtype, const void *Kc, const void *Vc, sc_dtype kv_dtype, int cap,
+                         const int32_t *counts, const int32_t *comp_lens, int B, int Hq, int Hkv, int d, float scale,
+                         void *O, sc_dtype o_dtype, float *lse, void *ws, size_t ws_bytes, void *stream) {
+    if (!Q || !Kc || !Vc || !counts || !comp_lens || !O) return SC_ERR_INVALID_ARG;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0) return SC_ERR_INVALID_ARG;
+    if (cap <= 0) return SC_ERR_CAPACITY;
+    if (!dtype_ok(q_dtype) || !dtype_ok(kv_dtype) || !dtype_ok(o_dtype)) return SC_ERR_UNSUPPORTED;
+    if (d != 64 && d != 128) return SC_ERR_UNSUPPORTED;
+    if (Hq % Hkv) return SC_ERR_UNSUPPORTED;
+    if (Hq / Hkv > 8) return SC_ERR_UNSUPPORTED;
+    if (Hkv > 65535 || B > 65535) return SC_ERR_UNSUPPORTED;
+    if (!aligned16(Q) || !aligned16(Kc) || !aligned16(Vc) || !aligned4(O)) return SC_ERR_INVALID_ARG;
+    if (!aligned4(counts) || !aligned4(comp_lens) || (lse && !aligned4(lse))) return SC_ERR_INVALID_ARG;
+    if (scale != scale) return SC_ERR_INVALID_ARG;
+    const size_t need = decode_workspace_bytes(B, Hq, Hkv, cap, d);
+    if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SC_ERR_WORKSPACE;
+
+    DecodeArgs a;
+    a.Q = Q; a.q_dtype = static_cast<DType>(q_dtype);
+    a.Kc = Kc; a.Vc = Vc; a.kv_dtype = static_cast<DType>(kv_dtype); a.cap = cap;
+    a.counts = counts; a.comp_lens = comp_lens;
+    a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.d = d;
+    a.scale = (scale == 0.f) ? 1.0f / sqrtf((float)d) : scale;
+    a.O = O; a.o_dtype = static_cast<DType>(o_dtype); a.lse = lse; a.ws = ws;
+    return runtime_status(launch_decode(a, static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

@@ -1,0 +1,141 @@
+// Device-side building blocks shared by the SemantiCache kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sc {
+
+// Storage tag for bf16 elements (the kernels only ever look at the bits).
+struct bf16_t { uint16_t bits; };
+
+constexpr int kWave = 64;
+
+// ------------------------------------------------------------------ bf16 <-> fp32
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// ------------------------------------------------------------------ 8-element row pieces
+// Every kernel gives a lane 8 consecutive elements of a row (16 B of bf16, 32 B of fp32), so a row
+// of d elements is covered by d/8 neighbouring lanes with fully coalesced 16-byte accesses.
+__device__ __forceinline__ void load8(const bf16_t *p, float (&x)[8]) {
+    const uint4 v = *reinterpret_cast<const uint4 *>(p);
+    x[0] = bf16_lo(v.x); x[1] = bf16_hi(v.x); x[2] = bf16_lo(v.y); x[3] = bf16_hi(v.y);
+    x[4] = bf16_lo(v.z); x[5] = bf16_hi(v.z); x[6] = bf16_lo(v.w); x[7] = bf16_hi(v.w);
+}
+__device__ __forceinline__ void load8(const float *p, float (&x)[8]) {
+    const float4 a = *reinterpret_cast<const float4 *>(p);
+    const float4 b = *reinterpret_cast<const float4 *>(p + 4);
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+}
+__device__ __forceinline__ void store8(bf16_t *p, const float (&x)[8]) {
+    uint4 v;
+    v.x = f32_to_bf16(x[0]) | (f32_to_bf16(x[1]) << 16);
+    v.y = f32_to_bf16(x[2]) | (f32_to_bf16(x[3]) << 16);
+    v.z = f32_to_bf16(x[4]) | (f32_to_bf16(x[5]) << 16);
+    v.w = f32_to_bf16(x[6]) | (f32_to_bf16(x[7]) << 16);
+    *reinterpret_cast<uint4 *>(p) = v;
+}
+__device__ __forceinline__ void store8(float *p, const float (&x)[8]) {
+    *reinterpret_cast<float4 *>(p) = make_float4(x[0], x[1], x[2], x[3]);
+    *reinterpret_cast<float4 *>(p + 4) = make_float4(x[4], x[5], x[6], x[7]);
+}
+__device__ __forceinline__ double load1_f64(const bf16_t *p) { return (double)__uint_as_float((uint32_t)p->bits << 16); }
+__device__ __forceinline__ double load1_f64(const float *p) { return (double)*p; }
+
+// ------------------------------------------------------------------ cross-lane moves (DPP)
+// Symmetric lane pairings inside a row of 16 lanes; all lanes of the wave must be active.
+constexpr int kDppQuadXor1 = 0xB1;      // quad_perm [1,0,3,2]
+constexpr int kDppQuadXor2 = 0x4E;      // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;   // lane i <-> 7 - i inside each 8 lanes
+constexpr int kDppMirror = 0x140;       // lane i <-> 15 - i inside each 16 lanes
+constexpr int kDppRor4 = 0x124;         // rotate by 4 inside each 16 lanes
+constexpr int kDppRor8 = 0x128;         // rotate by 8 inside each 16 lanes
+
+template <int CTRL>
+__device__ __forceinline__ float dpp(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp(int x) {
+    return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xf, 0xf, true);
+}
+
+// Sum over the LPR (8 or 16) neighbouring lanes that share a row; every lane gets the total.
+template <int LPR>
+__device__ __forceinline__ float row_allreduce_sum(float x) {
+    x += dpp<kDppQuadXor1>(x);
+    x += dpp<kDppQuadXor2>(x);
+    x += dpp<kDppHalfMirror>(x);
+    if (LPR == 16) x += dpp<kDppMirror>(x);
+    return x;
+}
+template <int LPR>
+__device__ __forceinline__ float row_allreduce_max(float x) {
+    x = fmaxf(x, dpp<kDppQuadXor1>(x));
+    x = fmaxf(x, dpp<kDppQuadXor2>(x));
+    x = fmaxf(x, dpp<kDppHalfMirror>(x));
+    if (LPR == 16) x = fmaxf(x, dpp<kDppMirror>(x));
+    return x;
+}
+
+// "Transposed" reduction: every lane holds LPR partial sums p[0..LPR); lane c of each LPR-lane
+// group ends up with the group-wide total of p[c].  Costs ~2*LPR adds instead of LPR*log2(LPR).
+template <int LPR>
+__device__ __forceinline__ float row_transpose_reduce(const float (&p)[LPR], int c) {
+    float q8[8];
+    if constexpr (LPR == 16) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const float lo = p[t] + dpp<kDppMirror>(p[t]);
+            const float hi = p[(t + 8) % LPR] + dpp<kDppMirror>(p[(t + 8) % LPR]);
+            q8[t] = (c & 8) ? hi : lo;
+        }
+    } else {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) q8[t] = p[t];
+    }
+    float q4[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const float lo = q8[t] + dpp<kDppHalfMirror>(q8[t]);
+        const float hi = q8[t + 4] + dpp<kDppHalfMirror>(q8[t + 4]);
+        q4[t] = (c & 4) ? hi : lo;
+    }
+    float q2[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const float lo = q4[t] + dpp<kDppQuadXor2>(q4[t]);
+        const float hi = q4[t + 2] + dpp<kDppQuadXor2>(q4[t + 2]);
+        q2[t] = (c & 2) ? hi : lo;
+    }
+    const float lo = q2[0] + dpp<kDppQuadXor1>(q2[0]);
+    const float hi = q2[1] + dpp<kDppQuadXor1>(q2[1]);
+    return (c & 1) ? hi : lo;
+}
+
+// Arbitrary lane gather through the LDS crossbar (no LDS memory is touched).
+__device__ __forceinline__ float lane_gather(float x, int src_lane) {
+    return __int_as_float(__builtin_amdgcn_ds_bpermute(src_lane << 2, __float_as_int(x)));
+}
+__device__ __forceinline__ int lane_gather(int x, int src_lane) {
+    return __builtin_amdgcn_ds_bpermute(src_lane << 2, x);
+}
+
+__device__ __forceinline__ uint64_t ballot64(bool pred) { return __ballot(pred); }
+__device__ __forceinline__ int first_bit(uint64_t m) { return __ffsll((unsigned long long)m) - 1; }
+
+__device__ __forceinline__ double wave_allreduce_sum(double x) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
+    return x;
+}
+
+}  // namespace sc

@@ -1,0 +1,66 @@
+// Host-side launcher declarations (internal; the public boundary is include/semanticache.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace sc {
+
+enum class DType : int { F32 = 0, BF16 = 1 };
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- sc_segment
+hipError_t launch_segment(const uint8_t *mask, int64_t mask_stride_b, const int32_t *seq_lens, int B, int n_max,
+                          int32_t *offsets, int64_t offsets_stride_b, int offsets_cap, int32_t *num_chunks,
+                          hipStream_t stream);
+
+// ---- sc_gsc_merge
+struct GscMergeArgs {
+    const void *K, *V;
+    DType in_dtype;
+    int64_t stride_b, stride_h, stride_n;   // elements
+    const int32_t *seq_lens, *offsets;
+    int64_t offsets_stride_b;
+    const int32_t *num_chunks;
+    int B, Hkv, N_max, d;
+    float tau;
+    void *Kc, *Vc;
+    DType out_dtype;
+    int cap;
+    int32_t *counts, *comp_lens, *cluster_id;
+    void *ws;
+};
+size_t gsc_merge_workspace_bytes(int B, int Hkv, int N_max, int d);
+hipError_t launch_gsc_merge(const GscMergeArgs &a, hipStream_t stream);
+
+// ---- sc_decode_attn
+struct DecodeArgs {
+    const void *Q;
+    DType q_dtype;
+    const void *Kc, *Vc;
+    DType kv_dtype;
+    int cap;
+    const int32_t *counts, *comp_lens;
+    int B, Hq, Hkv, d;
+    float scale;
+    void *O;
+    DType o_dtype;
+    float *lse;
+    void *ws;
+};
+size_t decode_workspace_bytes(int B, int Hq, int Hkv, int cap, int d);
+size_t decode_workspace_state_bytes(int B, int Hkv);
+hipError_t launch_decode_init_workspace(void *ws, size_t state_bytes, hipStream_t stream);
+hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream);
+
+// tuning knobs (read by the launchers; set through sc_tune_set)
+struct Tuning {
+    int decode_max_splits = 64;     // upper bound on split-K workgroups per (sequence, KV head)
+    int decode_min_rows = 128;      // rows of the merged cache a split should at least get
+    int gsc_chunks_per_item = 16;   // chunks handled by one workgroup work item
+    int gsc_grid_x = 128;           // persistent workgroups per (sequence, KV head)
+};
+Tuning &tuning();
+
+}  // namespace sc
