@@ -58,7 +58,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecParams p) {
     __shared__ int s_last;
 
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // scalar: keeps the row loop wave-uniform
     const int g = lane / LPR, c = lane % LPR;
     const int64_t bh = (int64_t)b * p.Hkv + h;
     const int rows_total = min(max(p.comp_lens[bh], 0), p.cap);

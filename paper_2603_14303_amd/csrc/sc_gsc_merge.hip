@@ -173,9 +173,11 @@ __device__ int gsc_chunk(const T *__restrict__ Kbh, int64_t stride_n, int start,
 template <typename T, int D>
 __global__ __launch_bounds__(kGscThreads) void gsc_assign_kernel(GscParams p) {
     __shared__ int s_off[kMaxChunksPerItem + 1];
-    __shared__ int s_next;
     const int b = blockIdx.z, h = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    // wave index as a scalar: everything derived from it (chunk bounds, loop trip counts) stays
+    // wave-uniform for the compiler, so the cross-lane operations below always see all 64 lanes
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int M = p.num_chunks[b];
     if (M <= 0) return;
     int n = p.seq_lens ? p.seq_lens[b] : p.N_max;
@@ -194,15 +196,10 @@ __global__ __launch_bounds__(kGscThreads) void gsc_assign_kernel(GscParams p) {
         const int nch = min(C, M - m0);
         __syncthreads();
         if (tid <= nch) s_off[tid] = off[m0 + tid];
-        if (tid == 0) s_next = 0;
         __syncthreads();
-        while (true) {
-            int idx = 0;
-            if (lane == 0) idx = atomicAdd(&s_next, 1);
-            idx = __builtin_amdgcn_readfirstlane(idx);
-            if (idx >= nch) break;
-            const int start = s_off[idx];
-            const int l = s_off[idx + 1] - 1 - start;
+        for (int idx = wave; idx < nch; idx += kGscThreads / kWave) {
+            const int start = __builtin_amdgcn_readfirstlane(s_off[idx]);
+            const int l = __builtin_amdgcn_readfirstlane(s_off[idx + 1]) - 1 - start;
             int pc = 0;
             if (l > 0) pc = gsc_chunk<T, D>(Kbh, p.stride_n, start, l, p.tau, cid_bh, seed_bh, lane);
             if (lane == 0) {
@@ -279,13 +276,15 @@ __device__ __forceinline__ void store_row8(void *base, int64_t elem_off, const f
 template <typename T, int D>
 __global__ __launch_bounds__(kGscThreads) void gsc_merge_kernel(GscParams p) {
     constexpr int LPR = D / 8;
-    constexpr int kGroups = kGscThreads / LPR;
+    constexpr int RPW = kWave / LPR;            // output rows a wave works on at once
+    constexpr int kGroups = kGscThreads / LPR;  // output rows a workgroup works on at once
     __shared__ int s_off[kMaxChunksPerItem + 1];
     __shared__ int s_base[kMaxChunksPerItem + 1];
     const int b = blockIdx.z, h = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
-    const int group = tid / LPR, c = tid % LPR;
-    const int gsh = (lane / LPR) * LPR;   // position of this group's bits inside a wave ballot
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int g = lane / LPR, c = lane % LPR;
+    const int gsh = g * LPR;   // position of this group's bits inside a wave ballot
     const uint64_t gmask = (LPR == 16) ? 0xffffull : 0xffull;
     const int M = p.num_chunks[b];
     if (M <= 0) return;
@@ -310,9 +309,12 @@ __global__ __launch_bounds__(kGscThreads) void gsc_merge_kernel(GscParams p) {
             s_base[tid] = rowbase_bh[m0 + tid];
         }
         __syncthreads();
-        const int R0 = s_base[0], R1 = s_base[nch];
-        for (int R = R0 + group; R < R1; R += kGroups) {
-            if (R >= p.cap) break;
+        const int R0 = __builtin_amdgcn_readfirstlane(s_base[0]);
+        const int R1 = min(__builtin_amdgcn_readfirstlane(s_base[nch]), p.cap);
+        // all loops below have wave-uniform trip counts; per-group differences are predicates
+        for (int Rw = R0 + wave * RPW; Rw < R1; Rw += kGroups) {
+            const int R = Rw + g;
+            const bool valid = R < R1;
             // chunk of this output row: last idx with s_base[idx] <= R
             int idx = 0;
             for (int k = 1; k < nch; ++k) idx = (s_base[k] <= R) ? k : idx;
@@ -321,67 +323,74 @@ __global__ __launch_bounds__(kGscThreads) void gsc_merge_kernel(GscParams p) {
             const int cl = R - s_base[idx];
             const bool closed = (start + l) < n;   // chunk is followed by a delimiter
             const int pc = s_base[idx + 1] - s_base[idx] - (closed ? 1 : 0);
+            const bool is_delim = valid && cl >= pc;
+            const int lscan = (valid && !is_delim) ? l : 0;
+            int lmax = 0;
+#pragma unroll
+            for (int gg = 0; gg < RPW; ++gg) lmax = max(lmax, __builtin_amdgcn_readlane(lscan, gg * LPR));
+
             float ka[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, va[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             int size = 0;
-            if (cl >= pc) {
+            if (is_delim) {
                 // the delimiter that closes the chunk: copied unchanged, size 1
                 const int64_t src = (int64_t)(start + l) * p.stride_n + 8 * c;
                 load8(Kbh + src, ka);
                 load8(Vbh + src, va);
                 size = 1;
-            } else {
-                for (int j0 = 0; j0 < l; j0 += LPR) {
-                    const int j = j0 + c;
-                    const bool match = (j < l) && (cid_bh[start + j] == cl);
-                    uint32_t mbits = (uint32_t)((ballot64(match) >> gsh) & gmask);
-                    while (mbits) {
-                        int jj[4];
-                        bool ok[4];
-                        float kk[4][8], vv[4][8];
+            }
+            for (int j0 = 0; j0 < lmax; j0 += LPR) {
+                const int j = j0 + c;
+                const bool match = (j < lscan) && (cid_bh[start + j] == cl);
+                uint32_t mbits = (uint32_t)((ballot64(match) >> gsh) & gmask);
+                while (ballot64(mbits != 0u) != 0ull) {
+                    int jj[4];
+                    bool ok[4];
+                    float kk[4][8], vv[4][8];
 #pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            ok[u] = mbits != 0;
-                            jj[u] = ok[u] ? (__ffs(mbits) - 1) : 0;
-                            mbits &= mbits - 1;
+                    for (int u = 0; u < 4; ++u) {
+                        ok[u] = mbits != 0u;
+                        jj[u] = ok[u] ? (__ffs(mbits) - 1) : 0;
+                        mbits &= mbits - 1u;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        if (ok[u]) {
+                            const int64_t src = (int64_t)(start + j0 + jj[u]) * p.stride_n + 8 * c;
+                            load8(Kbh + src, kk[u]);
+                            load8(Vbh + src, vv[u]);
                         }
+                    }
 #pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            if (ok[u]) {
-                                const int64_t src = (int64_t)(start + j0 + jj[u]) * p.stride_n + 8 * c;
-                                load8(Kbh + src, kk[u]);
-                                load8(Vbh + src, vv[u]);
+                    for (int u = 0; u < 4; ++u) {
+                        if (ok[u]) {
+                            if (size == 0) {
+#pragma unroll
+                                for (int e = 0; e < 8; ++e) { ka[e] = kk[u][e]; va[e] = vv[u][e]; }
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 8; ++e) { ka[e] += kk[u][e]; va[e] += vv[u][e]; }
                             }
-                        }
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            if (ok[u]) {
-                                if (size == 0) {
-#pragma unroll
-                                    for (int e = 0; e < 8; ++e) { ka[e] = kk[u][e]; va[e] = vv[u][e]; }
-                                } else {
-#pragma unroll
-                                    for (int e = 0; e < 8; ++e) { ka[e] += kk[u][e]; va[e] += vv[u][e]; }
-                                }
-                                size += 1;
-                            }
+                            size += 1;
                         }
                     }
                 }
-                if (size > 1) {
-                    const float fs = (float)size;
+            }
+            if (size > 1) {
+                const float fs = (float)size;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) { ka[e] = ka[e] / fs; va[e] = va[e] / fs; }
+                for (int e = 0; e < 8; ++e) { ka[e] = ka[e] / fs; va[e] = va[e] / fs; }
+            }
+            if (valid) {
+                const int64_t dst = ((int64_t)bh * p.cap + R) * D + 8 * c;
+                if (p.out_is_bf16) {
+                    store_row8<bf16_t>(p.Kc, dst, ka);
+                    store_row8<bf16_t>(p.Vc, dst, va);
+                } else {
+                    store_row8<float>(p.Kc, dst, ka);
+                    store_row8<float>(p.Vc, dst, va);
                 }
+                if (c == 0) counts_bh[R] = size;
             }
-            const int64_t dst = ((int64_t)bh * p.cap + R) * D + 8 * c;
-            if (p.out_is_bf16) {
-                store_row8<bf16_t>(p.Kc, dst, ka);
-                store_row8<bf16_t>(p.Vc, dst, va);
-            } else {
-                store_row8<float>(p.Kc, dst, ka);
-                store_row8<float>(p.Vc, dst, va);
-            }
-            if (c == 0) counts_bh[R] = size;
         }
     }
 }
