@@ -1,14 +1,22 @@
 // sc_decode_attn: Proportional Attention for one decode step (paper Sec. 2.4, Eq. 4):
 //     O = softmax(q K_c^T * scale + ln s) V_c   per (sequence, query head), GQA-grouped.
 //
-// Split-K: the rows of one (sequence, KV head) are cut into S contiguous ranges, one workgroup each;
-// the G query heads that share the KV head are handled together so K_c/V_c are read once.  Inside a
-// workgroup a row is spread over d/8 neighbouring lanes (16-byte pieces, fully coalesced); a wave
-// loads 4 x (64/(d/8)) rows per step, forms the G dot products per row with a DPP all-reduce, and
-// keeps an online softmax (running max, running sum, fp32 accumulator) per lane group.  Partials are
-// merged through LDS, written to the workspace, and the workgroup that arrives last (ticket counter)
-// folds the S partials into O.  The ticket is reset by that workgroup, so a workspace that was
-// zeroed once stays ready for the next call.
+// Split-K.  The rows of one (sequence, KV head) are cut into S contiguous ranges, one workgroup of
+// four wavefronts each; the G query heads that share the KV head are handled together so K_c/V_c
+// are read once.  A row is spread over d/8 neighbouring lanes (16-byte pieces, fully coalesced), a
+// wave-wide load covers 64/(d/8) rows, and one "step" of a wave is U such loads of K_c and of V_c,
+// double-buffered in registers so the next step's loads are in flight while this one is computed.
+//
+// Fast kernel (bf16 cache and query, d = 128).  Per step and lane: U*GP partial dot products
+// (GP = G padded to 1/2/4/8; bf16 pairs go through v_dot2_f32_bf16), a transposed DPP reduction that
+// leaves ONE (row, head) score per lane, the online-softmax update done once per score by its owner
+// lane (exp2 domain, log2(size) bias), and a ds_swizzle broadcast of the 16 probabilities back to
+// the lanes that hold the value pieces.  Partials (running max, sum, fp32 accumulator) are folded
+// across lane groups and waves, written to the workspace, and the workgroup that arrives last
+// (ticket counter) folds the S partials into O with all 256 threads.  The ticket is reset by that
+// workgroup, so a workspace that was zeroed once stays ready for the next call.
+//
+// Generic kernel (d = 64, fp32 caches or queries): same split-K scheme, plain DPP all-reduce.
 #include "sc_device.h"
 #include "sc_host.h"
 
@@ -16,12 +24,17 @@ namespace sc {
 
 constexpr int kDecThreads = 256;
 constexpr int kDecWaves = kDecThreads / kWave;
-constexpr int kDecUnroll = 4;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr int kDecMaxSplits = 256;
+constexpr int kDecUnroll = 4;   // loads per step of the generic kernel
+
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
+}
 
 struct DecParams {
     const void *Q;
@@ -35,7 +48,7 @@ struct DecParams {
     int o_is_bf16;
     float *lse;
     int32_t *tickets;     // [B*Hkv], zero between calls
-    float *part;          // [B*Hkv][S][G][D + 2]
+    float *part;          // [B*Hkv][max_splits][G][D + 2]
     int max_splits, min_rows;
 };
 
@@ -44,8 +57,295 @@ __device__ __forceinline__ int splits_for(int rows, int max_splits, int min_rows
     return s < 1 ? 1 : (s > max_splits ? max_splits : s);
 }
 
+template <int SH> __device__ __forceinline__ float ror_max(float x) { return fmaxf(x, dpp<0x120 + SH>(x)); }
+template <int SH> __device__ __forceinline__ float ror_add(float x) { return x + dpp<0x120 + SH>(x); }
+// reduce over the lanes of a 16-lane row that share (lane % GP): rotations by GP, 2GP, ... < 16
+template <int GP> __device__ __forceinline__ float orbit_max(float x) {
+    if constexpr (GP <= 1) x = ror_max<1>(x);
+    if constexpr (GP <= 2) x = ror_max<2>(x);
+    if constexpr (GP <= 4) x = ror_max<4>(x);
+    if constexpr (GP <= 8) x = ror_max<8>(x);
+    return x;
+}
+template <int GP> __device__ __forceinline__ float orbit_sum(float x) {
+    if constexpr (GP <= 1) x = ror_add<1>(x);
+    if constexpr (GP <= 2) x = ror_add<2>(x);
+    if constexpr (GP <= 4) x = ror_add<4>(x);
+    if constexpr (GP <= 8) x = ror_add<8>(x);
+    return x;
+}
+// value of lane SRC of the own 16-lane row (ds_swizzle bit-mask mode: keep lane bit 4, force the low bits)
+template <int SRC> __device__ __forceinline__ float row_bcast(float x) {
+    return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(x), 0x10 | (SRC << 5)));
+}
+template <int N, int I = 0> struct BcastAll {
+    static __device__ __forceinline__ void run(float x, float (&out)[N]) {
+        out[I] = row_bcast<I>(x);
+        if constexpr (I + 1 < N) BcastAll<N, I + 1>::run(x, out);
+    }
+};
+
+template <int D, int G>
+__global__ __launch_bounds__(kDecThreads) void decode_bf16_kernel(DecParams p) {
+    static_assert(D == 128, "16 lanes per row");
+    constexpr int LPR = 16;
+    constexpr int RPW = kWave / LPR;                       // 4 rows per wave-wide load
+    constexpr int GP = G <= 1 ? 1 : (G <= 2 ? 2 : (G <= 4 ? 4 : 8));
+    constexpr int U = GP == 8 ? 4 : 16 / GP;               // loads per step
+    constexpr int NT = U * GP / 16;                        // transposed reductions per step (2 for GP = 8)
+    constexpr int UH = U / NT;                             // loads covered by one reduction
+    constexpr int kRowsPerWaveStep = RPW * U;
+    constexpr int kRowsPerBlockStep = kRowsPerWaveStep * kDecWaves;
+    constexpr int kStride = D + 2;   // floats per (split, head) partial: acc[D], m, l
+
+    __shared__ float s_acc[kDecWaves][G][D];
+    __shared__ float s_m[kDecWaves][G];
+    __shared__ float s_l[kDecWaves][G];
+    __shared__ float s_w[kDecMaxSplits];
+    __shared__ float s_red[2][D];
+    __shared__ float s_tot[2];
+    __shared__ int s_last;
+
+    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // scalar: keeps the row loop wave-uniform
+    const int g = lane / LPR, c = lane % LPR;
+    const int64_t bh = (int64_t)b * p.Hkv + h;
+    const int rows_total = min(max(p.comp_lens[bh], 0), p.cap);
+    const int S = splits_for(rows_total, p.max_splits, p.min_rows);
+    if (split >= S) return;
+    // contiguous row range of this split, a multiple of the block step except for the last one
+    int per = (rows_total + S - 1) / S;
+    per = (per + kRowsPerBlockStep - 1) / kRowsPerBlockStep * kRowsPerBlockStep;
+    const int r0 = min(split * per, rows_total), r1 = min(r0 + per, rows_total);
+
+    const bf16_t *Kbh = reinterpret_cast<const bf16_t *>(p.Kc) + bh * (int64_t)p.cap * D + 8 * c;
+    const bf16_t *Vbh = reinterpret_cast<const bf16_t *>(p.Vc) + bh * (int64_t)p.cap * D + 8 * c;
+    const int32_t *cnt_bh = p.counts + bh * (int64_t)p.cap;
+
+    uint4 k0[U], v0[U], k1[U], v1[U];
+    int c0[U], c1[U];
+    auto issue = [&](uint4 (&kb)[U], uint4 (&vb)[U], int (&cb)[U], int base) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int row = base + u * RPW + g;
+            if (row < r1) {
+                kb[u] = *reinterpret_cast<const uint4 *>(Kbh + (int64_t)row * D);
+                vb[u] = *reinterpret_cast<const uint4 *>(Vbh + (int64_t)row * D);
+                cb[u] = cnt_bh[row];
+            } else {
+                kb[u] = make_uint4(0, 0, 0, 0);
+                vb[u] = make_uint4(0, 0, 0, 0);
+                cb[u] = 0;      // "no row": its score becomes -inf
+            }
+        }
+    };
+    int base = r0 + wave * kRowsPerWaveStep;
+    issue(k0, v0, c0, base);
+
+    uint4 q[GP];
+#pragma unroll
+    for (int hh = 0; hh < GP; ++hh) {
+        const int64_t qoff = ((int64_t)b * p.Hq + (int64_t)h * G + (hh < G ? hh : 0)) * D + 8 * c;
+        q[hh] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const bf16_t *>(p.Q) + qoff);
+    }
+
+    // owner-lane state: lane c of a row owns head (c % GP); replicated over the 16/GP lanes of its orbit
+    float m_run = -INFINITY, l_run = 0.f;
+    float acc[GP][8];
+#pragma unroll
+    for (int hh = 0; hh < GP; ++hh)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[hh][e] = 0.f;
+
+    auto compute = [&](const uint4 (&kb)[U], const uint4 (&vb)[U], const int (&cb)[U]) {
+#pragma unroll
+        for (int half = 0; half < NT; ++half) {
+            // ---- scores: UH loads x GP heads = 16 partials -> one full dot product per lane
+            float part[16];
+#pragma unroll
+            for (int uu = 0; uu < UH; ++uu) {
+                const uint4 kk = kb[half * UH + uu];
+#pragma unroll
+                for (int hh = 0; hh < GP; ++hh) {
+                    float s = dot2_bf16(kk.x, q[hh].x, 0.f);
+                    s = dot2_bf16(kk.y, q[hh].y, s);
+                    s = dot2_bf16(kk.z, q[hh].z, s);
+                    part[uu * GP + hh] = dot2_bf16(kk.w, q[hh].w, s);
+                }
+            }
+            float s = row_transpose_reduce<16>(part, c);
+            // lane c owns (load uu = c / GP, head c % GP)
+            int cnt = 0;
+#pragma unroll
+            for (int uu = 0; uu < UH; ++uu) cnt = (c / GP == uu) ? cb[half * UH + uu] : cnt;
+            s = (cnt > 0) ? fmaf(s, p.scale_log2, __log2f((float)cnt)) : -INFINITY;
+            const float m_new = orbit_max<GP>(fmaxf(s, m_run));
+            const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = fast_exp2(m_run - m_safe);
+            const float pw = fast_exp2(s - m_safe);
+            l_run = fmaf(l_run, alpha, orbit_sum<GP>(pw));
+            m_run = m_new;
+            // ---- rescale (skipped when no running max moved) and accumulate P V
+            if (ballot64(alpha != 1.0f) != 0ull) {
+                float al[GP];
+                BcastAll<GP>::run(alpha, al);
+#pragma unroll
+                for (int hh = 0; hh < GP; ++hh)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[hh][e] *= al[hh];
+            }
+            float pb[16];
+            BcastAll<16>::run(pw, pb);
+#pragma unroll
+            for (int uu = 0; uu < UH; ++uu) {
+                const uint4 vv = vb[half * UH + uu];
+                const float x[8] = {bf16_lo(vv.x), bf16_hi(vv.x), bf16_lo(vv.y), bf16_hi(vv.y),
+                                    bf16_lo(vv.z), bf16_hi(vv.z), bf16_lo(vv.w), bf16_hi(vv.w)};
+#pragma unroll
+                for (int hh = 0; hh < GP; ++hh)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[hh][e] = fmaf(pb[uu * GP + hh], x[e], acc[hh][e]);
+            }
+        }
+    };
+
+    // two register sets alternate: while one step is computed the next step's loads are in flight
+    while (base < r1) {
+        if (base + kRowsPerBlockStep < r1) issue(k1, v1, c1, base + kRowsPerBlockStep);
+        compute(k0, v0, c0);
+        base += kRowsPerBlockStep;
+        if (base >= r1) break;
+        if (base + kRowsPerBlockStep < r1) issue(k0, v0, c0, base + kRowsPerBlockStep);
+        compute(k1, v1, c1);
+        base += kRowsPerBlockStep;
+    }
+
+    // ---- fold the RPW lane groups of the wave (each saw different rows), then park in LDS
+    {
+        float mw = m_run;
+#pragma unroll
+        for (int off = LPR; off < kWave; off <<= 1) mw = fmaxf(mw, __shfl_xor(mw, off, kWave));
+        const float m_safe = (mw == -INFINITY) ? 0.f : mw;
+        const float f = fast_exp2(m_run - m_safe);    // this lane group's factor for head c % GP
+        float lw = l_run * f;
+#pragma unroll
+        for (int off = LPR; off < kWave; off <<= 1) lw += __shfl_xor(lw, off, kWave);
+        float fh[GP];
+        BcastAll<GP>::run(f, fh);
+#pragma unroll
+        for (int hh = 0; hh < GP; ++hh) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float a = acc[hh][e] * fh[hh];
+#pragma unroll
+                for (int off = LPR; off < kWave; off <<= 1) a += __shfl_xor(a, off, kWave);
+                acc[hh][e] = a;
+            }
+            if (hh < G && g == 0) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s_acc[wave][hh][8 * c + e] = acc[hh][e];
+            }
+        }
+        if (g == 0 && c < G) { s_m[wave][c] = mw; s_l[wave][c] = lw; }
+    }
+    __syncthreads();
+
+    // ---- fold the waves, write this split's partial
+    float *part_bh = p.part + bh * (int64_t)p.max_splits * G * kStride;
+    for (int i = tid; i < G * D; i += kDecThreads) {
+        const int hh = i / D, e = i % D;
+        float mw = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kDecWaves; ++w) mw = fmaxf(mw, s_m[w][hh]);
+        const float m_safe = (mw == -INFINITY) ? 0.f : mw;
+        float a = 0.f, l = 0.f;
+#pragma unroll
+        for (int w = 0; w < kDecWaves; ++w) {
+            const float f = fast_exp2(s_m[w][hh] - m_safe);
+            a = fmaf(s_acc[w][hh][e], f, a);
+            l = fmaf(s_l[w][hh], f, l);
+        }
+        float *dst = part_bh + ((int64_t)split * G + hh) * kStride;
+        dst[e] = a;
+        if (e == 0) { dst[D] = mw; dst[D + 1] = l; }
+    }
+
+    // ---- the workgroup that arrives last combines all splits
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        const int ticket = atomicAdd(p.tickets + bh, 1);
+        s_last = (ticket == S - 1);
+        if (ticket == S - 1) p.tickets[bh] = 0;   // ready for the next call
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    for (int hh = 0; hh < G; ++hh) {
+        // weights of the S partials of this head, w_s = 2^(m_s - max m), by wave 0
+        if (wave == 0) {
+            float mx = -INFINITY;
+            for (int s0 = 0; s0 < S; s0 += kWave) {
+                const int s = s0 + lane;
+                if (s < S) {
+                    const float ms = __builtin_nontemporal_load(part_bh + ((int64_t)s * G + hh) * kStride + D);
+                    s_w[s] = ms;
+                    mx = fmaxf(mx, ms);
+                }
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+            const float m_safe = (mx == -INFINITY) ? 0.f : mx;
+            float lt = 0.f;
+            for (int s0 = 0; s0 < S; s0 += kWave) {
+                const int s = s0 + lane;
+                if (s < S) {
+                    const float wgt = fast_exp2(s_w[s] - m_safe);
+                    s_w[s] = wgt;
+                    lt = fmaf(__builtin_nontemporal_load(part_bh + ((int64_t)s * G + hh) * kStride + D + 1), wgt, lt);
+                }
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) lt += __shfl_xor(lt, off, kWave);
+            if (lane == 0) { s_tot[0] = mx; s_tot[1] = lt; }
+        }
+        __syncthreads();
+        // 256 threads: element e = tid % D, split parity tid / D; independent loads, 4 in flight
+        const int e = tid % D, par = tid / D;
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+        const float *src = part_bh + (int64_t)hh * kStride + e;
+        const int64_t sstep = (int64_t)G * kStride;
+        int s = par;
+        for (; s + 6 < S; s += 8) {
+            const float x0 = __builtin_nontemporal_load(src + (s + 0) * sstep);
+            const float x1 = __builtin_nontemporal_load(src + (s + 2) * sstep);
+            const float x2 = __builtin_nontemporal_load(src + (s + 4) * sstep);
+            const float x3 = __builtin_nontemporal_load(src + (s + 6) * sstep);
+            a0 = fmaf(x0, s_w[s], a0); a1 = fmaf(x1, s_w[s + 2], a1);
+            a2 = fmaf(x2, s_w[s + 4], a2); a3 = fmaf(x3, s_w[s + 6], a3);
+        }
+        for (; s < S; s += 2) a0 = fmaf(__builtin_nontemporal_load(src + s * sstep), s_w[s], a0);
+        s_red[par][e] = (a0 + a1) + (a2 + a3);
+        __syncthreads();
+        if (tid < D) {
+            const float l = s_tot[1];
+            const float out = (l > 0.f) ? (s_red[0][tid] + s_red[1][tid]) / l : 0.f;
+            const int64_t ooff = ((int64_t)b * p.Hq + (int64_t)h * G + hh) * D + tid;
+            if (p.o_is_bf16) reinterpret_cast<uint16_t *>(p.O)[ooff] = (uint16_t)f32_to_bf16(out);
+            else reinterpret_cast<float *>(p.O)[ooff] = out;
+            if (tid == 0 && p.lse)
+                p.lse[(int64_t)b * p.Hq + (int64_t)h * G + hh] = (l > 0.f) ? (s_tot[0] + __log2f(l)) * kLn2 : -INFINITY;
+        }
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Generic kernel: every lane group reduces with a DPP all-reduce and updates the softmax state of all
+// G heads itself; the last workgroup folds the partials one (head, element) per thread.
 template <typename T, int D, int G>
-__global__ __launch_bounds__(kDecThreads) void decode_kernel(DecParams p) {
+__global__ __launch_bounds__(kDecThreads) void decode_generic_kernel(DecParams p) {
     constexpr int LPR = D / 8;
     constexpr int RPW = kWave / LPR;
     constexpr int kRowsPerWaveStep = RPW * kDecUnroll;
@@ -250,7 +550,13 @@ hipError_t launch_decode_init_workspace(void *ws, size_t state_bytes, hipStream_
 template <typename T, int D, int G>
 static hipError_t launch_g(const DecParams &p, hipStream_t stream) {
     const dim3 grid(p.max_splits, p.Hkv, p.B);
-    hipLaunchKernelGGL((decode_kernel<T, D, G>), grid, dim3(kDecThreads), 0, stream, p);
+    if constexpr (D == 128 && sizeof(T) == 2) {
+        if (p.q_is_bf16) {
+            hipLaunchKernelGGL((decode_bf16_kernel<D, G>), grid, dim3(kDecThreads), 0, stream, p);
+            return hipGetLastError();
+        }
+    }
+    hipLaunchKernelGGL((decode_generic_kernel<T, D, G>), grid, dim3(kDecThreads), 0, stream, p);
     return hipGetLastError();
 }
 

@@ -168,9 +168,11 @@ def test_repeatable_bit_for_bit():
     O0 = O0.clone()
     for _ in range(5):
         b = g.run_compress(case, torch.bfloat16)
-        r = int(a["comp_lens"].max())
         assert torch.equal(a["comp_lens"], b["comp_lens"]) and torch.equal(a["cid"], b["cid"])
-        assert torch.equal(a["Kc"][:, :, :r], b["Kc"][:, :, :r]) and torch.equal(a["counts"][:, :, :r], b["counts"][:, :, :r])
+        for h in range(2):
+            r = int(a["comp_lens"][0, h])
+            assert torch.equal(a["Kc"][0, h, :r], b["Kc"][0, h, :r]) and torch.equal(a["Vc"][0, h, :r], b["Vc"][0, h, :r])
+            assert torch.equal(a["counts"][0, h, :r], b["counts"][0, h, :r])
         O1, _ = sc.sc_decode_attn(Q, a["Kc"], a["Vc"], a["counts"], a["comp_lens"], workspace=ws)
         torch.cuda.synchronize()
         # split partials are combined in a fixed order, so the result does not depend on arrival order
