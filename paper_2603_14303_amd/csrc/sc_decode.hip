@@ -22,14 +22,21 @@
 
 namespace sc {
 
+#ifdef SC_DEC_TIMING
+#define SC_STAMP(k) do { if (threadIdx.x == 0) p.dbg[((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 + (k)] = wall_clock64(); } while (0)
+#else
+#define SC_STAMP(k) do {} while (0)
+#endif
+
 constexpr int kDecThreads = 256;
 constexpr int kDecWaves = kDecThreads / kWave;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr int kDecMaxSplits = 256;
+constexpr int kDecMaxSplits = 128;
 constexpr int kDecUnroll = 4;   // loads per step of the generic kernel
 
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
@@ -50,6 +57,9 @@ struct DecParams {
     int32_t *tickets;     // [B*Hkv], zero between calls
     float *part;          // [B*Hkv][max_splits][G][D + 2]
     int max_splits, min_rows;
+#ifdef SC_DEC_TIMING
+    unsigned long long *dbg;   // [blocks][16] timestamps (development builds only)
+#endif
 };
 
 __device__ __forceinline__ int splits_for(int rows, int max_splits, int min_rows) {
@@ -85,27 +95,167 @@ template <int N, int I = 0> struct BcastAll {
     }
 };
 
+
+// ------------------------------------------------------------------------------------------------
+// Fold the S split partials of one (sequence, KV head) into O; run by the workgroup that arrived last.
+// Every global load is issued before its first use: (1) all (m, l) pairs, (2) per pass up to
+// HB*KMAX independent 16-byte loads per thread, so the fold costs a few memory round trips in total.
+// ------------------------------------------------------------------------------------------------
+// Hand-over of split partials between workgroups that may sit on different XCDs (each XCD has its own
+// L2).  Partials are written with device-coherent (write-through) stores, so publishing them needs
+// no L2 write-back: a workgroup waits for its own stores, takes a ticket with a relaxed device-scope
+// atomic, and only the workgroup holding the last ticket invalidates its caches before reading.
+__device__ __forceinline__ void coherent_store(float *p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// returns 1 in every thread of the workgroup whose ticket is the last of the S splits
+__device__ __forceinline__ int elect_last_split(int32_t *ticket_ptr, int S, int tid, int *s_flag) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // own partial stores have completed
+    __syncthreads();
+    if (tid == 0) {
+        const int ticket = __hip_atomic_fetch_add(ticket_ptr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *s_flag = (ticket == S - 1);
+        if (ticket == S - 1) __hip_atomic_store(ticket_ptr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    const int last = *s_flag;
+    if (last) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // drop stale cached lines of the partial buffer
+    return last;
+}
+
+constexpr int kPartPad = 4;   // floats after the D accumulators of a partial: m, l, 2 unused (keeps 16-byte rows)
+
+template <int D, int G, int NTHREADS>
+__device__ __forceinline__ void combine_splits(const DecParams &p, const float *part_bh, int S, int b, int h,
+                                               int tid, int lane, int wave, float *s_w, float *s_l2, float *s_ml,
+                                               float *s_red) {
+    constexpr int kStride = D + kPartPad;
+    constexpr int HB = G < 4 ? G : 4;           // heads per pass
+    constexpr int QPR = D / 4;                  // 16-byte pieces per partial row
+    constexpr int NTC = NTHREADS < 512 ? NTHREADS : 512;   // threads that load partial rows
+    constexpr int RS = NTC / QPR;               // partial rows in flight per load wave
+    constexpr int KMAX = 64 / RS;               // loads per thread, head and block of 64 splits
+    constexpr int NWAVES = NTHREADS / kWave;
+    const int q4 = tid % QPR, rs = tid / QPR;
+    const bool loader = tid < NTC;
+    // first block of partial rows: issued together with the (m, l) loads, one memory round trip
+    float4 x[HB][KMAX];
+    auto load_rows = [&](int h0, int sb) {
+#pragma unroll
+        for (int hh = 0; hh < HB; ++hh)
+#pragma unroll
+            for (int k = 0; k < KMAX; ++k) {
+                const int s = sb + rs + RS * k;
+                if (loader && s < S && h0 + hh < G) {
+                    const f32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(
+                        part_bh + ((int64_t)s * G + h0 + hh) * kStride + 4 * q4));
+                    x[hh][k] = make_float4(t.x, t.y, t.z, t.w);
+                } else {
+                    x[hh][k] = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+            }
+    };
+    load_rows(0, 0);
+    for (int i = tid; i < S * G; i += NTHREADS) {
+        const float *src = part_bh + (int64_t)i * kStride + D;
+        s_w[i] = __builtin_nontemporal_load(src);
+        s_l2[i] = __builtin_nontemporal_load(src + 1);
+    }
+    __syncthreads();
+    for (int hh = wave; hh < G; hh += NWAVES) {
+        float mx = -INFINITY;
+        for (int s = lane; s < S; s += kWave) mx = fmaxf(mx, s_w[s * G + hh]);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+        const float m_safe = (mx == -INFINITY) ? 0.f : mx;
+        float lt = 0.f;
+        for (int s = lane; s < S; s += kWave) {
+            const float wgt = fast_exp2(s_w[s * G + hh] - m_safe);
+            s_w[s * G + hh] = wgt;
+            lt = fmaf(s_l2[s * G + hh], wgt, lt);
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) lt += __shfl_xor(lt, off, kWave);
+        if (lane == 0) { s_ml[2 * hh] = mx; s_ml[2 * hh + 1] = lt; }
+    }
+    __syncthreads();
+    for (int h0 = 0; h0 < G; h0 += HB) {
+        float4 acc[HB];
+#pragma unroll
+        for (int hh = 0; hh < HB; ++hh) acc[hh] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int sb = 0; sb < S; sb += 64) {
+            if (h0 != 0 || sb != 0) load_rows(h0, sb);
+#pragma unroll
+            for (int hh = 0; hh < HB; ++hh)
+#pragma unroll
+                for (int k = 0; k < KMAX; ++k) {
+                    const int s = sb + rs + RS * k;
+                    const float wgt = (s < S && h0 + hh < G) ? s_w[s * G + h0 + hh] : 0.f;
+                    acc[hh].x = fmaf(x[hh][k].x, wgt, acc[hh].x);
+                    acc[hh].y = fmaf(x[hh][k].y, wgt, acc[hh].y);
+                    acc[hh].z = fmaf(x[hh][k].z, wgt, acc[hh].z);
+                    acc[hh].w = fmaf(x[hh][k].w, wgt, acc[hh].w);
+                }
+        }
+        if (loader) {
+#pragma unroll
+            for (int hh = 0; hh < HB; ++hh)
+                *reinterpret_cast<float4 *>(s_red + ((rs * HB + hh) * D + 4 * q4)) = acc[hh];
+        }
+        __syncthreads();
+        for (int i = tid; i < HB * D; i += NTHREADS) {
+            const int hh = i / D, e = i % D;
+            if (h0 + hh < G) {
+                float a = 0.f;
+#pragma unroll
+                for (int r = 0; r < RS; ++r) a += s_red[(r * HB + hh) * D + e];
+                const float mx = s_ml[2 * (h0 + hh)], l = s_ml[2 * (h0 + hh) + 1];
+                const float out = (l > 0.f) ? a / l : 0.f;
+                const int64_t ooff = ((int64_t)b * p.Hq + (int64_t)h * G + h0 + hh) * D + e;
+                if (p.o_is_bf16) reinterpret_cast<uint16_t *>(p.O)[ooff] = (uint16_t)f32_to_bf16(out);
+                else reinterpret_cast<float *>(p.O)[ooff] = out;
+                if (e == 0 && p.lse)
+                    p.lse[(int64_t)b * p.Hq + (int64_t)h * G + h0 + hh] = (l > 0.f) ? (mx + __log2f(l)) * kLn2 : -INFINITY;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+template <int G> struct FastShape {
+    static constexpr int GP = G <= 4 ? 4 : 8;         // heads padded to 4 or 8 (padding heads are computed and dropped)
+    static constexpr int WAVES = GP == 8 ? 8 : 12;    // 12 waves x 8 KB of loads in flight per CU, <= 170 VGPRs each
+    static constexpr int THREADS = WAVES * kWave;
+    static constexpr int U = 4;                       // wave-wide loads of K (and of V) per step
+};
+
 template <int D, int G>
-__global__ __launch_bounds__(kDecThreads) void decode_bf16_kernel(DecParams p) {
+__global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecParams p) {
     static_assert(D == 128, "16 lanes per row");
     constexpr int LPR = 16;
     constexpr int RPW = kWave / LPR;                       // 4 rows per wave-wide load
-    constexpr int GP = G <= 1 ? 1 : (G <= 2 ? 2 : (G <= 4 ? 4 : 8));
-    constexpr int U = GP == 8 ? 4 : 16 / GP;               // loads per step
+    constexpr int GP = FastShape<G>::GP;
+    constexpr int WAVES = FastShape<G>::WAVES;
+    constexpr int THREADS = FastShape<G>::THREADS;
+    constexpr int U = FastShape<G>::U;
     constexpr int NT = U * GP / 16;                        // transposed reductions per step (2 for GP = 8)
     constexpr int UH = U / NT;                             // loads covered by one reduction
     constexpr int kRowsPerWaveStep = RPW * U;
-    constexpr int kRowsPerBlockStep = kRowsPerWaveStep * kDecWaves;
-    constexpr int kStride = D + 2;   // floats per (split, head) partial: acc[D], m, l
+    constexpr int kRowsPerBlockStep = kRowsPerWaveStep * WAVES;
+    constexpr int kStride = D + kPartPad;   // floats per (split, head) partial: acc[D], m, l, pad
+    constexpr int HB = G < 4 ? G : 4;
+    constexpr int kBufFloats = (WAVES * G * D) > (16 * HB * D) ? (WAVES * G * D) : (16 * HB * D);
 
-    __shared__ float s_acc[kDecWaves][G][D];
-    __shared__ float s_m[kDecWaves][G];
-    __shared__ float s_l[kDecWaves][G];
-    __shared__ float s_w[kDecMaxSplits];
-    __shared__ float s_red[2][D];
-    __shared__ float s_tot[2];
+    // s_buf: per-wave accumulators [WAVES][G][D] first, partial-row sums of the final fold later
+    __shared__ __attribute__((aligned(16))) float s_buf[kBufFloats];
+    __shared__ float s_m[WAVES][G];
+    __shared__ float s_l[WAVES][G];
+    __shared__ float s_w[kDecMaxSplits * G];
+    __shared__ float s_l2[kDecMaxSplits * G];
+    __shared__ float s_ml[2 * G];
     __shared__ int s_last;
 
+    SC_STAMP(0);
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // scalar: keeps the row loop wave-uniform
@@ -123,9 +273,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_bf16_kernel(DecParams p) {
     const bf16_t *Vbh = reinterpret_cast<const bf16_t *>(p.Vc) + bh * (int64_t)p.cap * D + 8 * c;
     const int32_t *cnt_bh = p.counts + bh * (int64_t)p.cap;
 
-    uint4 k0[U], v0[U], k1[U], v1[U];
-    int c0[U], c1[U];
-    auto issue = [&](uint4 (&kb)[U], uint4 (&vb)[U], int (&cb)[U], int base) {
+    uint4 kb[U], vb[U];
+    int cb[U];
+    auto issue = [&](int base) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int row = base + u * RPW + g;
@@ -140,8 +290,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_bf16_kernel(DecParams p) {
             }
         }
     };
+    SC_STAMP(1);
     int base = r0 + wave * kRowsPerWaveStep;
-    issue(k0, v0, c0, base);
+    issue(base);
 
     uint4 q[GP];
 #pragma unroll
@@ -158,7 +309,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_bf16_kernel(DecParams p) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[hh][e] = 0.f;
 
-    auto compute = [&](const uint4 (&kb)[U], const uint4 (&vb)[U], const int (&cb)[U]) {
+    while (base < r1) {
+        float pb[NT][16];
+        float al[NT][GP];
+        bool moved[NT];
 #pragma unroll
         for (int half = 0; half < NT; ++half) {
             // ---- scores: UH loads x GP heads = 16 partials -> one full dot product per lane
@@ -186,17 +340,18 @@ __global__ __launch_bounds__(kDecThreads) void decode_bf16_kernel(DecParams p) {
             const float pw = fast_exp2(s - m_safe);
             l_run = fmaf(l_run, alpha, orbit_sum<GP>(pw));
             m_run = m_new;
-            // ---- rescale (skipped when no running max moved) and accumulate P V
-            if (ballot64(alpha != 1.0f) != 0ull) {
-                float al[GP];
-                BcastAll<GP>::run(alpha, al);
+            moved[half] = ballot64(alpha != 1.0f) != 0ull;
+            if (moved[half]) BcastAll<GP>::run(alpha, al[half]);
+            BcastAll<16>::run(pw, pb[half]);
+        }
+#pragma unroll
+        for (int half = 0; half < NT; ++half) {
+            if (moved[half]) {
 #pragma unroll
                 for (int hh = 0; hh < GP; ++hh)
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[hh][e] *= al[hh];
+                    for (int e = 0; e < 8; ++e) acc[hh][e] *= al[half][hh];
             }
-            float pb[16];
-            BcastAll<16>::run(pw, pb);
 #pragma unroll
             for (int uu = 0; uu < UH; ++uu) {
                 const uint4 vv = vb[half * UH + uu];
@@ -205,140 +360,64 @@ __global__ __launch_bounds__(kDecThreads) void decode_bf16_kernel(DecParams p) {
 #pragma unroll
                 for (int hh = 0; hh < GP; ++hh)
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[hh][e] = fmaf(pb[uu * GP + hh], x[e], acc[hh][e]);
+                    for (int e = 0; e < 8; ++e) acc[hh][e] = fmaf(pb[half][uu * GP + hh], x[e], acc[hh][e]);
             }
         }
-    };
-
-    // two register sets alternate: while one step is computed the next step's loads are in flight
-    while (base < r1) {
-        if (base + kRowsPerBlockStep < r1) issue(k1, v1, c1, base + kRowsPerBlockStep);
-        compute(k0, v0, c0);
+        // the other 15 waves of the workgroup keep the memory pipe busy while this one computes
         base += kRowsPerBlockStep;
-        if (base >= r1) break;
-        if (base + kRowsPerBlockStep < r1) issue(k0, v0, c0, base + kRowsPerBlockStep);
-        compute(k1, v1, c1);
-        base += kRowsPerBlockStep;
+        if (base < r1) issue(base);
     }
 
+    SC_STAMP(2);
     // ---- fold the RPW lane groups of the wave (each saw different rows), then park in LDS
     {
-        float mw = m_run;
-#pragma unroll
-        for (int off = LPR; off < kWave; off <<= 1) mw = fmaxf(mw, __shfl_xor(mw, off, kWave));
+        const float mw = rows_allreduce_max(m_run);
         const float m_safe = (mw == -INFINITY) ? 0.f : mw;
         const float f = fast_exp2(m_run - m_safe);    // this lane group's factor for head c % GP
-        float lw = l_run * f;
-#pragma unroll
-        for (int off = LPR; off < kWave; off <<= 1) lw += __shfl_xor(lw, off, kWave);
+        const float lw = rows_allreduce_sum(l_run * f);
         float fh[GP];
         BcastAll<GP>::run(f, fh);
 #pragma unroll
         for (int hh = 0; hh < GP; ++hh) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                float a = acc[hh][e] * fh[hh];
-#pragma unroll
-                for (int off = LPR; off < kWave; off <<= 1) a += __shfl_xor(a, off, kWave);
-                acc[hh][e] = a;
-            }
+            for (int e = 0; e < 8; ++e) acc[hh][e] = rows_allreduce_sum(acc[hh][e] * fh[hh]);
             if (hh < G && g == 0) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) s_acc[wave][hh][8 * c + e] = acc[hh][e];
+                for (int e = 0; e < 8; ++e) s_buf[(wave * G + hh) * D + 8 * c + e] = acc[hh][e];
             }
         }
         if (g == 0 && c < G) { s_m[wave][c] = mw; s_l[wave][c] = lw; }
     }
     __syncthreads();
 
-    // ---- fold the waves, write this split's partial
+    SC_STAMP(3);
+    // ---- fold the waves, write this split's partial (device-coherent stores)
     float *part_bh = p.part + bh * (int64_t)p.max_splits * G * kStride;
-    for (int i = tid; i < G * D; i += kDecThreads) {
+    for (int i = tid; i < G * D; i += THREADS) {
         const int hh = i / D, e = i % D;
         float mw = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < kDecWaves; ++w) mw = fmaxf(mw, s_m[w][hh]);
+        for (int w = 0; w < WAVES; ++w) mw = fmaxf(mw, s_m[w][hh]);
         const float m_safe = (mw == -INFINITY) ? 0.f : mw;
         float a = 0.f, l = 0.f;
 #pragma unroll
-        for (int w = 0; w < kDecWaves; ++w) {
+        for (int w = 0; w < WAVES; ++w) {
             const float f = fast_exp2(s_m[w][hh] - m_safe);
-            a = fmaf(s_acc[w][hh][e], f, a);
+            a = fmaf(s_buf[(w * G + hh) * D + e], f, a);
             l = fmaf(s_l[w][hh], f, l);
         }
         float *dst = part_bh + ((int64_t)split * G + hh) * kStride;
-        dst[e] = a;
-        if (e == 0) { dst[D] = mw; dst[D + 1] = l; }
+        coherent_store(dst + e, a);
+        if (e == 0) { coherent_store(dst + D, mw); coherent_store(dst + D + 1, l); }
     }
 
+    SC_STAMP(4);
     // ---- the workgroup that arrives last combines all splits
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const int ticket = atomicAdd(p.tickets + bh, 1);
-        s_last = (ticket == S - 1);
-        if (ticket == S - 1) p.tickets[bh] = 0;   // ready for the next call
-    }
-    __syncthreads();
+    s_last = elect_last_split(p.tickets + bh, S, tid, &s_last);
+    SC_STAMP(5);
     if (!s_last) return;
-    __threadfence();
-    for (int hh = 0; hh < G; ++hh) {
-        // weights of the S partials of this head, w_s = 2^(m_s - max m), by wave 0
-        if (wave == 0) {
-            float mx = -INFINITY;
-            for (int s0 = 0; s0 < S; s0 += kWave) {
-                const int s = s0 + lane;
-                if (s < S) {
-                    const float ms = __builtin_nontemporal_load(part_bh + ((int64_t)s * G + hh) * kStride + D);
-                    s_w[s] = ms;
-                    mx = fmaxf(mx, ms);
-                }
-            }
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
-            const float m_safe = (mx == -INFINITY) ? 0.f : mx;
-            float lt = 0.f;
-            for (int s0 = 0; s0 < S; s0 += kWave) {
-                const int s = s0 + lane;
-                if (s < S) {
-                    const float wgt = fast_exp2(s_w[s] - m_safe);
-                    s_w[s] = wgt;
-                    lt = fmaf(__builtin_nontemporal_load(part_bh + ((int64_t)s * G + hh) * kStride + D + 1), wgt, lt);
-                }
-            }
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) lt += __shfl_xor(lt, off, kWave);
-            if (lane == 0) { s_tot[0] = mx; s_tot[1] = lt; }
-        }
-        __syncthreads();
-        // 256 threads: element e = tid % D, split parity tid / D; independent loads, 4 in flight
-        const int e = tid % D, par = tid / D;
-        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-        const float *src = part_bh + (int64_t)hh * kStride + e;
-        const int64_t sstep = (int64_t)G * kStride;
-        int s = par;
-        for (; s + 6 < S; s += 8) {
-            const float x0 = __builtin_nontemporal_load(src + (s + 0) * sstep);
-            const float x1 = __builtin_nontemporal_load(src + (s + 2) * sstep);
-            const float x2 = __builtin_nontemporal_load(src + (s + 4) * sstep);
-            const float x3 = __builtin_nontemporal_load(src + (s + 6) * sstep);
-            a0 = fmaf(x0, s_w[s], a0); a1 = fmaf(x1, s_w[s + 2], a1);
-            a2 = fmaf(x2, s_w[s + 4], a2); a3 = fmaf(x3, s_w[s + 6], a3);
-        }
-        for (; s < S; s += 2) a0 = fmaf(__builtin_nontemporal_load(src + s * sstep), s_w[s], a0);
-        s_red[par][e] = (a0 + a1) + (a2 + a3);
-        __syncthreads();
-        if (tid < D) {
-            const float l = s_tot[1];
-            const float out = (l > 0.f) ? (s_red[0][tid] + s_red[1][tid]) / l : 0.f;
-            const int64_t ooff = ((int64_t)b * p.Hq + (int64_t)h * G + hh) * D + tid;
-            if (p.o_is_bf16) reinterpret_cast<uint16_t *>(p.O)[ooff] = (uint16_t)f32_to_bf16(out);
-            else reinterpret_cast<float *>(p.O)[ooff] = out;
-            if (tid == 0 && p.lse)
-                p.lse[(int64_t)b * p.Hq + (int64_t)h * G + hh] = (l > 0.f) ? (s_tot[0] + __log2f(l)) * kLn2 : -INFINITY;
-        }
-        __syncthreads();
-    }
+    combine_splits<D, G, THREADS>(p, part_bh, S, b, h, tid, lane, wave, s_w, s_l2, s_ml, s_buf);
+    SC_STAMP(6);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -350,11 +429,15 @@ __global__ __launch_bounds__(kDecThreads) void decode_generic_kernel(DecParams p
     constexpr int RPW = kWave / LPR;
     constexpr int kRowsPerWaveStep = RPW * kDecUnroll;
     constexpr int kRowsPerBlockStep = kRowsPerWaveStep * kDecWaves;
-    constexpr int kStride = D + 2;   // floats per (split, head) partial: acc[D], m, l
+    constexpr int kStride = D + kPartPad;   // floats per (split, head) partial: acc[D], m, l, pad
 
     __shared__ float s_acc[kDecWaves][G][D];
     __shared__ float s_m[kDecWaves][G];
     __shared__ float s_l[kDecWaves][G];
+    __shared__ float s_w[kDecMaxSplits * G];
+    __shared__ float s_l2[kDecMaxSplits * G];
+    __shared__ float s_ml[2 * G];
+    __shared__ __attribute__((aligned(16))) float s_red[(kDecThreads / (D / 4)) * (G < 4 ? G : 4) * D];
     __shared__ int s_last;
 
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
@@ -488,40 +571,14 @@ __global__ __launch_bounds__(kDecThreads) void decode_generic_kernel(DecParams p
             l = fmaf(s_l[w][hh], f, l);
         }
         float *dst = part_bh + ((int64_t)split * G + hh) * kStride;
-        dst[e] = a;
-        if (e == 0) { dst[D] = mw; dst[D + 1] = l; }
+        coherent_store(dst + e, a);
+        if (e == 0) { coherent_store(dst + D, mw); coherent_store(dst + D + 1, l); }
     }
 
     // ---- the workgroup that arrives last combines all splits
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const int ticket = atomicAdd(p.tickets + bh, 1);
-        s_last = (ticket == S - 1);
-        if (ticket == S - 1) p.tickets[bh] = 0;   // ready for the next call
-    }
-    __syncthreads();
+    s_last = elect_last_split(p.tickets + bh, S, tid, &s_last);
     if (!s_last) return;
-    __threadfence();
-    for (int i = tid; i < G * D; i += kDecThreads) {
-        const int hh = i / D, e = i % D;
-        float mw = -INFINITY;
-        for (int s = 0; s < S; ++s)
-            mw = fmaxf(mw, __builtin_nontemporal_load(part_bh + ((int64_t)s * G + hh) * kStride + D));
-        const float m_safe = (mw == -INFINITY) ? 0.f : mw;
-        float a = 0.f, l = 0.f;
-        for (int s = 0; s < S; ++s) {
-            const float *src = part_bh + ((int64_t)s * G + hh) * kStride;
-            const float f = fast_exp2(__builtin_nontemporal_load(src + D) - m_safe);
-            a = fmaf(__builtin_nontemporal_load(src + e), f, a);
-            l = fmaf(__builtin_nontemporal_load(src + D + 1), f, l);
-        }
-        const float out = (l > 0.f) ? a / l : 0.f;
-        const int64_t ooff = ((int64_t)b * p.Hq + (int64_t)h * G + hh) * D + e;
-        if (p.o_is_bf16) reinterpret_cast<uint16_t *>(p.O)[ooff] = (uint16_t)f32_to_bf16(out);
-        else reinterpret_cast<float *>(p.O)[ooff] = out;
-        if (e == 0 && p.lse) p.lse[(int64_t)b * p.Hq + (int64_t)h * G + hh] = (l > 0.f) ? (mw + __log2f(l)) * kLn2 : -INFINITY;
-    }
+    combine_splits<D, G, kDecThreads>(p, part_bh, S, b, h, tid, lane, wave, s_w, s_l2, s_ml, s_red);
 }
 
 __global__ void zero_words_kernel(int32_t *p, size_t n) {
@@ -531,13 +588,13 @@ __global__ void zero_words_kernel(int32_t *p, size_t n) {
 
 size_t decode_workspace_state_bytes(int B, int Hkv) { return align_up((size_t)B * Hkv * 4, 256); }
 
-static int clamp_splits() { return max(1, min(kDecMaxSplits, tuning().decode_max_splits)); }
+static int clamp_splits() { return max(1, min(kDecMaxSplits, tuning().decode_max_splits)); }   // knob <= 0: automatic
 
 size_t decode_workspace_bytes(int B, int Hq, int Hkv, int cap, int d) {
     (void)cap;
     const int G = Hq / Hkv;
     // sized for the largest split count the tuning knob may take, so the knob never invalidates a workspace
-    return decode_workspace_state_bytes(B, Hkv) + align_up((size_t)B * Hkv * kDecMaxSplits * G * (d + 2) * 4, 256);
+    return decode_workspace_state_bytes(B, Hkv) + align_up((size_t)B * Hkv * kDecMaxSplits * G * (d + kPartPad) * 4, 256);
 }
 
 hipError_t launch_decode_init_workspace(void *ws, size_t state_bytes, hipStream_t stream) {
@@ -552,7 +609,7 @@ static hipError_t launch_g(const DecParams &p, hipStream_t stream) {
     const dim3 grid(p.max_splits, p.Hkv, p.B);
     if constexpr (D == 128 && sizeof(T) == 2) {
         if (p.q_is_bf16) {
-            hipLaunchKernelGGL((decode_bf16_kernel<D, G>), grid, dim3(kDecThreads), 0, stream, p);
+            hipLaunchKernelGGL((decode_bf16_kernel<D, G>), grid, dim3(FastShape<G>::THREADS), 0, stream, p);
             return hipGetLastError();
         }
     }
@@ -586,10 +643,18 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream) {
     p.lse = a.lse;
     p.tickets = reinterpret_cast<int32_t *>(a.ws);
     p.part = reinterpret_cast<float *>(reinterpret_cast<char *>(a.ws) + decode_workspace_state_bytes(a.B, a.Hkv));
+#ifdef SC_DEC_TIMING
+    p.dbg = reinterpret_cast<unsigned long long *>(a.lse);   // development builds borrow the lse pointer
+    p.lse = nullptr;
+#endif
     p.min_rows = max(1, tuning().decode_min_rows);
+    // Splits per (sequence, KV head): enough workgroups to cover the 256 CUs about once; more splits
+    // only add partials to fold and tickets to take (both are serial tails of the kernel).
+    int splits = clamp_splits();
+    if (tuning().decode_max_splits <= 0) splits = max(2, min(32, 256 / max(1, a.B * a.Hkv)));
     // never more splits than the capacity can feed
     const int by_cap = (a.cap + p.min_rows - 1) / p.min_rows;
-    p.max_splits = max(1, min(clamp_splits(), by_cap));
+    p.max_splits = max(1, min(splits, by_cap));
     const int G = a.Hq / a.Hkv;
     if (a.kv_dtype == DType::BF16)
         return a.d == 128 ? launch_td<bf16_t, 128>(p, G, stream) : launch_td<bf16_t, 64>(p, G, stream);

@@ -121,6 +121,22 @@ __device__ __forceinline__ float row_transpose_reduce(const float (&p)[LPR], int
     return (c & 1) ? hi : lo;
 }
 
+// Reductions over the four 16-lane rows of a wave (same position inside the row), every lane gets the
+// result.  v_permlane16_swap / v_permlane32_swap exchange odd and even rows (halves) of two registers
+// in one VALU operation: swapping x with itself yields {even|even, odd|odd}, whose sum is the pair sum.
+__device__ __forceinline__ float rows_allreduce_sum(float x) {
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float rows_allreduce_max(float x) {
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 // Arbitrary lane gather through the LDS crossbar (no LDS memory is touched).
 __device__ __forceinline__ float lane_gather(float x, int src_lane) {
     return __int_as_float(__builtin_amdgcn_ds_bpermute(src_lane << 2, __float_as_int(x)));
