@@ -1,0 +1,552 @@
+// Fast path of sc_gsc_merge for bf16 keys/values with head dim 128 (paper Sec. 2.3 Alg. 1 / Eq. 2 and
+// Sec. 2.4 Eq. 3).
+//
+// Two streaming passes, each reading its operand from HBM exactly once:
+//   pass 1  reads K.  One wavefront handles four consecutive chunks.  It packs whole chunks (each
+//           with its closing delimiter) into "windows" of at most 64 rows held in registers, 16 lanes
+//           per row.  Inside a window the seeds of Alg. 1 are taken in row order; a delimiter is a
+//           one-row chunk, so the order in which seeds appear IS the output row order.  For a seed,
+//           lanes form partial dot products with v_dot2_f32_bf16, a transposed DPP reduction gives
+//           one cosine per lane, a ballot marks the absorbed rows (decisions inside +-1e-4 of tau are
+//           redone in fp64).  The cluster means of K are then one small matrix product on the matrix
+//           cores: (output row x window row) 0/1 membership times (window row x 128) keys, fp32
+//           accumulate, with a ones-column giving the cluster sizes.  Outputs: merged keys at a
+//           provisional position (the window's own rows), every token's output index inside its
+//           window, clusters per chunk.
+//   scan    exclusive scan of (clusters + delimiter) over the chunks of a (sequence, head).
+//   pass 2  reads V and the output indices, repeats the membership product for V, writes merged values
+//           and sizes to their final rows and moves the merged keys there.
+// Chunks longer than one window run the same steps over several windows with the seeds carried
+// along (their keys are re-read through L2); if such a chunk has more than 16 clusters its key merge
+// is left to pass 2.
+#include "sc_device.h"
+#include "sc_gsc_params.h"
+#include "sc_host.h"
+
+namespace sc {
+
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2f_t;
+typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef float floatx4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kFastThreads = 256;
+constexpr int kFastWaves = kFastThreads / kWave;
+constexpr int kFastD = 128;
+constexpr int kWin = 64;                 // rows of a window
+constexpr int kDeferredBit = 1 << 30;    // pcount flag: key merge of this chunk happens in pass 2 (see kPcountMask)
+constexpr float kFastBand = 1e-4f;       // fp32 cosine error for d = 128 is < 2e-5; inside the band -> fp64
+
+__device__ __forceinline__ float dot2f(uint32_t a, uint32_t b, float c) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2f_t, a), __builtin_bit_cast(bf16x2f_t, b), c, false);
+}
+__device__ __forceinline__ float dot8(const uint4 &a, const uint4 &b) {
+    float s = dot2f(a.x, b.x, 0.f);
+    s = dot2f(a.y, b.y, s);
+    s = dot2f(a.z, b.z, s);
+    return dot2f(a.w, b.w, s);
+}
+__device__ __forceinline__ uint64_t bits_range(int lo, int hi) {   // bits [lo, hi), 0 <= lo <= hi <= 64
+    const uint64_t upto_hi = (hi >= 64) ? ~0ull : ((1ull << hi) - 1ull);
+    const uint64_t upto_lo = (lo >= 64) ? ~0ull : ((1ull << lo) - 1ull);
+    return upto_hi & ~upto_lo;
+}
+__device__ __forceinline__ uint32_t bperm_u32(uint32_t x, int src_lane) {
+    return (uint32_t)__builtin_amdgcn_ds_bpermute(src_lane << 2, (int)x);
+}
+__device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
+__device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
+__device__ __forceinline__ uint32_t dword_of(const uint4 &v, int j) {   // j compile-time after unrolling
+    return j == 0 ? v.x : (j == 1 ? v.y : (j == 2 ? v.z : v.w));
+}
+
+// Rows of a window / block as loaded: lane (g = lane/16, c = lane%16) holds elements 8c..8c+7 of rows
+// 4t + g, t = 0..15 (one coalesced 16-byte load per t covers four whole rows).
+struct RowRegs {
+    uint4 r[16];
+};
+
+__device__ __forceinline__ void load_rows(RowRegs &x, const bf16_t *base_c, int64_t stride_n, int first_row, int nrows,
+                                          int g) {
+    const int t_eff = (nrows + 3) >> 2;
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+        const int row = 4 * t + g;
+        if (t < t_eff && row < nrows)
+            x.r[t] = *reinterpret_cast<const uint4 *>(base_c + (int64_t)(first_row + row) * stride_n);
+        else
+            x.r[t] = make_uint4(0, 0, 0, 0);
+    }
+}
+
+// dot product of every row with a 16-lane-replicated piece vector; result in row order (lane r = row r)
+__device__ __forceinline__ float rows_dot(const RowRegs &x, const uint4 &piece, int t_lo, int t_hi, int c, int lane) {
+    float part[16];
+#pragma unroll
+    for (int t = 0; t < 16; ++t) part[t] = (t >= t_lo && t < t_hi) ? dot8(x.r[t], piece) : 0.f;
+    const float v = row_transpose_reduce<16>(part, c);   // lane (g, c) holds row 4c + g
+    return lane_gather(v, ((lane & 3) << 4) | (lane >> 2));
+}
+__device__ __forceinline__ float rows_norm2(const RowRegs &x, int t_hi, int c, int lane) {
+    float part[16];
+#pragma unroll
+    for (int t = 0; t < 16; ++t) part[t] = (t < t_hi) ? dot8(x.r[t], x.r[t]) : 0.f;
+    const float v = row_transpose_reduce<16>(part, c);
+    return lane_gather(v, ((lane & 3) << 4) | (lane >> 2));
+}
+
+// piece c of row i (wave-uniform i) broadcast to the four lane groups, taken from the registers
+__device__ __forceinline__ uint4 seed_piece(const RowRegs &x, int i, int c) {
+    const int src = ((i & 3) << 4) | c;
+    uint4 s = make_uint4(0, 0, 0, 0);
+#define SC_SEED_CASE(T)                                                                       \
+    case T:                                                                                   \
+        s.x = bperm_u32(x.r[T].x, src); s.y = bperm_u32(x.r[T].y, src);                       \
+        s.z = bperm_u32(x.r[T].z, src); s.w = bperm_u32(x.r[T].w, src);                       \
+        break;
+    switch (i >> 2) {
+        SC_SEED_CASE(0) SC_SEED_CASE(1) SC_SEED_CASE(2) SC_SEED_CASE(3) SC_SEED_CASE(4) SC_SEED_CASE(5)
+        SC_SEED_CASE(6) SC_SEED_CASE(7) SC_SEED_CASE(8) SC_SEED_CASE(9) SC_SEED_CASE(10) SC_SEED_CASE(11)
+        SC_SEED_CASE(12) SC_SEED_CASE(13) SC_SEED_CASE(14) SC_SEED_CASE(15)
+    }
+#undef SC_SEED_CASE
+    return s;
+}
+
+// fp64 re-evaluation of one (seed, candidate) pair by the whole wave: Eq. 2 in double precision
+__device__ __forceinline__ bool cosine_exceeds_f64_fast(const bf16_t *seed_row, const bf16_t *cand_row, float tau, int lane) {
+    double dot = 0.0, ss = 0.0, cc = 0.0;
+#pragma unroll
+    for (int e = lane; e < kFastD; e += kWave) {
+        const double s = load1_f64(seed_row + e), c = load1_f64(cand_row + e);
+        dot += s * c; ss += s * s; cc += c * c;
+    }
+    dot = wave_allreduce_sum(dot);
+    ss = wave_allreduce_sum(ss);
+    cc = wave_allreduce_sum(cc);
+    return dot / (sqrt(ss) * sqrt(cc)) > (double)tau;   // NaN compares false
+}
+
+// One seed against the unassigned candidates `cmask` of the block in registers.  Returns the mask of
+// absorbed rows.  dotv / nsq are in row order.
+__device__ __forceinline__ uint64_t absorb(const RowRegs &x, const uint4 &piece, float s_nsq, float nsq, uint64_t cmask,
+                                           int t_lo, int t_hi, float tau, const bf16_t *seed_row_ptr,
+                                           const bf16_t *block_row0_ptr, int64_t stride_n, int c, int lane) {
+    const float dotv = rows_dot(x, piece, t_lo, t_hi, c, lane);
+    const float sim = dotv * __frsqrt_rn(nsq) * __frsqrt_rn(s_nsq);
+    const bool odd = !(nsq > 1e-30f && nsq < 1e30f) || !(s_nsq > 1e-30f && s_nsq < 1e30f);
+    const bool cand = (cmask >> lane) & 1ull;
+    const bool sure_yes = sim > tau + kFastBand;
+    const bool sure_no = sim < tau - kFastBand;
+    const bool unsure = odd || !(sure_yes || sure_no);
+    bool yes = cand && !unsure && sure_yes;
+    uint64_t recheck = ballot64(cand && unsure);
+    while (recheck != 0ull) {
+        const int j = first_bit(recheck);
+        recheck &= recheck - 1ull;
+        const bool res = cosine_exceeds_f64_fast(seed_row_ptr, block_row0_ptr + (int64_t)j * stride_n, tau, lane);
+        if (lane == j) yes = res;
+    }
+    return ballot64(yes);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Membership product on the matrix cores.  For output tile `ot` (16 output rows) and the rows in
+// registers: D[j][i] += sum over rows of [orow(row) == 16*ot + 4*(lane/16) + i] * x[row][8c + j],
+// Dn[i] += the number of such rows.  v_mfma_f32_16x16x16_bf16: A[m][k] lane l holds m = l%16,
+// k = 4*(l/16)+i; B[k][n] lane l holds n = l%16, k = 4*(l/16)+i; D[m][n] lane l holds n = l%16,
+// m = 4*(l/16)+i.  The k index (l/16, i) of k-step q stands for row 16q + 4i + l/16, which is register
+// 4q + i of the lane's own group, so the B operands are built from registers alone.
+// orow_t[q*4 + i] = output index of row 16q + 4i + lane/16 (or -1).
+__device__ __forceinline__ void membership_mfma(const RowRegs &x, const int (&orow_t)[16], int ot, int q_hi, int lane,
+                                                floatx4_t (&D)[8], floatx4_t &Dn) {
+    const int want = 16 * ot + (lane & 15);
+    const short4_t ones = {0x3F80, 0x3F80, 0x3F80, 0x3F80};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if (q < q_hi) {
+            short4_t a;
+            a[0] = (orow_t[4 * q + 0] == want) ? (short)0x3F80 : (short)0;
+            a[1] = (orow_t[4 * q + 1] == want) ? (short)0x3F80 : (short)0;
+            a[2] = (orow_t[4 * q + 2] == want) ? (short)0x3F80 : (short)0;
+            a[3] = (orow_t[4 * q + 3] == want) ? (short)0x3F80 : (short)0;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t d0 = dword_of(x.r[4 * q + 0], j >> 1), d1 = dword_of(x.r[4 * q + 1], j >> 1);
+                const uint32_t d2 = dword_of(x.r[4 * q + 2], j >> 1), d3 = dword_of(x.r[4 * q + 3], j >> 1);
+                const uint32_t lo = (j & 1) ? pack_hi(d0, d1) : pack_lo(d0, d1);
+                const uint32_t hi = (j & 1) ? pack_hi(d2, d3) : pack_lo(d2, d3);
+                const uint2 bb = make_uint2(lo, hi);
+                D[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, __builtin_bit_cast(short4_t, bb), D[j], 0, 0, 0);
+            }
+            Dn = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, ones, Dn, 0, 0, 0);
+        }
+    }
+}
+
+// output indices from row order (lane r = row r) to the operand order of membership_mfma
+__device__ __forceinline__ void orow_to_operand_order(int my_o, int lane, int (&orow_t)[16]) {
+    const int g = lane >> 4;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) orow_t[4 * q + i] = lane_gather(my_o, 16 * q + 4 * i + g);
+}
+
+// scale the sums of tile `ot` by 1/size and store rows [16*ot, 16*ot+16) ∩ [0, n_out) at dst_row0 + o
+template <typename TO>
+__device__ __forceinline__ void store_tile(const floatx4_t (&D)[8], const floatx4_t &Dn, int ot, int n_out, TO *dst_c,
+                                           int64_t dst_row0, int64_t row_limit, int lane) {
+    const int g = lane >> 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int o = 16 * ot + 4 * g + i;
+        if (o < n_out && dst_row0 + o < row_limit) {
+            const float inv = (Dn[i] > 1.5f) ? 1.0f / Dn[i] : 1.0f;
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = (Dn[i] > 1.5f) ? D[j][i] * inv : D[j][i];
+            store8(dst_c + (dst_row0 + o) * kFastD, v);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// work decomposition shared by both passes: item = chunks_per_item chunks of one (b, h) handled by a
+// workgroup, wave w takes the contiguous quarter of them; rows of chunk m including its delimiter
+__device__ __forceinline__ int chunk_rows(const int *s_off, int idx, int m, int M) {
+    return (m < M - 1) ? (s_off[idx + 1] - s_off[idx]) : (s_off[idx + 1] - 1 - s_off[idx]);
+}
+
+// ------------------------------------------------------------------------------------------------
+template <typename TO>
+__global__ __launch_bounds__(kFastThreads) void gsc_pass1_kernel(GscParams p) {
+    __shared__ int s_off[kMaxChunksPerItem + 1];
+    const int b = blockIdx.z, h = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int g = lane >> 4, c = lane & 15;
+    const int M = p.num_chunks[b];
+    if (M <= 0) return;
+    int n = p.seq_lens ? p.seq_lens[b] : p.N_max;
+    n = n < 0 ? 0 : (n > p.N_max ? p.N_max : n);
+    const int C = p.chunks_per_item;
+    const int per_wave = (C + kFastWaves - 1) / kFastWaves;
+    const int items = (M + C - 1) / C;
+    const int64_t bh = (int64_t)b * p.Hkv + h;
+    const bf16_t *Kbh = reinterpret_cast<const bf16_t *>(p.K) + b * p.stride_b + h * p.stride_h;
+    const bf16_t *Kc_ = Kbh + 8 * c;   // this lane's column piece
+    const int32_t *off = p.offsets + (int64_t)b * p.offsets_stride_b;
+    uint16_t *orow_bh = p.orow + bh * p.N_max;
+    int32_t *pcount_bh = p.pcount + bh * ((int64_t)p.N_max + 1);
+    int32_t *seed_bh = p.seedrow + bh * p.N_max;
+    int32_t *cid_bh = p.cluster_id ? p.cluster_id + bh * p.N_max : nullptr;   // only when the caller asked
+    int32_t *cid32_bh = p.cid + bh * p.N_max;                                    // always there (workspace)
+    TO *ktmp_c = reinterpret_cast<TO *>(p.ktmp) + bh * (int64_t)p.N_max * kFastD + 8 * c;
+    const float tau = p.tau;
+
+    for (int item = blockIdx.x; item < items; item += gridDim.x) {
+        const int m0 = item * C;
+        const int nch = min(C, M - m0);
+        __syncthreads();
+        if (tid <= nch) s_off[tid] = off[m0 + tid];
+        __syncthreads();
+        const int idx_end = min(nch, (wave + 1) * per_wave);
+        int idx = wave * per_wave;
+        while (idx < idx_end) {
+            const int rows_first = __builtin_amdgcn_readfirstlane(chunk_rows(s_off, idx, m0 + idx, M));
+            const int w0 = __builtin_amdgcn_readfirstlane(s_off[idx]);
+            if (rows_first <= kWin) {
+                // ---------------- window of whole chunks, at most 64 rows
+                int idx_hi = idx, R = 0;
+                while (idx_hi < idx_end) {
+                    const int rr = __builtin_amdgcn_readfirstlane(chunk_rows(s_off, idx_hi, m0 + idx_hi, M));
+                    if (R + rr > kWin) break;
+                    R += rr;
+                    idx_hi += 1;
+                }
+                const int nchw = idx_hi - idx;
+                RowRegs x;
+                load_rows(x, Kc_, p.stride_n, w0, R, g);
+                const int t_all = (R + 3) >> 2;
+                // chunk range [lo, hi) of every row; a delimiter is a one-row range of its own
+                int lo = lane, hi = lane + 1;
+                bool in_chunk = false;
+                for (int j = 0; j < nchw; ++j) {
+                    const int cs = __builtin_amdgcn_readfirstlane(s_off[idx + j]) - w0;
+                    const int ce = __builtin_amdgcn_readfirstlane(s_off[idx + j + 1]) - 1 - w0;
+                    if (lane >= cs && lane < ce) { lo = cs; hi = ce; in_chunk = true; }
+                }
+                const float nsq = rows_norm2(x, t_all, c, lane);
+                uint64_t todo = bits_range(0, R);
+                uint64_t seedmask = 0ull;
+                int nseed = 0, my_o = -1, my_cid = -1, cur_lo = -1, cfo = 0;
+                while (todo != 0ull) {
+                    const int i = __builtin_amdgcn_readfirstlane(first_bit(todo));
+                    todo &= ~(1ull << i);
+                    seedmask |= 1ull << i;
+                    const int o = nseed;
+                    nseed += 1;
+                    const int lo_i = __builtin_amdgcn_readlane(lo, i), hi_i = __builtin_amdgcn_readlane(hi, i);
+                    if (lo_i != cur_lo) { cur_lo = lo_i; cfo = o; }
+                    const uint64_t cmask = bits_range(lo_i, hi_i) & todo;
+                    uint64_t members = 1ull << i;
+                    if (cmask != 0ull) {
+                        const uint4 piece = seed_piece(x, i, c);
+                        const float s_nsq = __shfl(nsq, i, kWave);
+                        const uint64_t got = absorb(x, piece, s_nsq, nsq, cmask, lo_i >> 2, (hi_i + 3) >> 2, tau,
+                                                    Kbh + (int64_t)(w0 + i) * p.stride_n,
+                                                    Kbh + (int64_t)w0 * p.stride_n, p.stride_n, c, lane);
+                        todo &= ~got;
+                        members |= got;
+                    }
+                    if ((members >> lane) & 1ull) { my_o = o; my_cid = in_chunk ? (o - cfo) : -1; }
+                }
+                if (lane < R) {
+                    orow_bh[w0 + lane] = (uint16_t)my_o;
+                    if (cid_bh) cid_bh[w0 + lane] = my_cid;
+                }
+                if (lane < nchw) {
+                    const int cs = s_off[idx + lane] - w0, ce = s_off[idx + lane + 1] - 1 - w0;
+                    pcount_bh[m0 + idx + lane] = __popcll(seedmask & bits_range(cs, ce));
+                }
+                // merged keys of the window -> provisional rows [w0, w0 + nseed)
+                int orow_t[16];
+                orow_to_operand_order(my_o, lane, orow_t);
+                const int q_hi = (R + 15) >> 4;
+                for (int ot = 0; ot * 16 < nseed; ++ot) {
+                    floatx4_t D[8], Dn = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) D[j] = Dn;
+                    membership_mfma(x, orow_t, ot, q_hi, lane, D, Dn);
+                    store_tile<TO>(D, Dn, ot, nseed, ktmp_c, (int64_t)w0, (int64_t)p.N_max, lane);
+                }
+                idx = idx_hi;
+            } else {
+                // ---------------- one chunk longer than a window: blocks of 64 rows, seeds carried along
+                const int start = w0;
+                const int l = __builtin_amdgcn_readfirstlane(s_off[idx + 1]) - 1 - start;
+                const bool closed = (start + l) < n;
+                int nseeds = 0;
+                floatx4_t D[8], Dn = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < 8; ++j) D[j] = Dn;
+                for (int rb = 0; rb < l; rb += kWin) {
+                    const int R = min(kWin, l - rb);
+                    const int t_all = (R + 3) >> 2;
+                    RowRegs x;
+                    load_rows(x, Kc_, p.stride_n, start + rb, R, g);
+                    const float nsq = rows_norm2(x, t_all, c, lane);
+                    uint64_t todo = bits_range(0, R);
+                    int my_o = -1;
+                    const int seeds_before = nseeds;
+                    const bf16_t *block0 = Kbh + (int64_t)(start + rb) * p.stride_n;
+                    for (int s = 0; s < seeds_before && todo != 0ull; ++s) {
+                        const int srow = __hip_atomic_load(seed_bh + start + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        const bf16_t *sp = Kbh + (int64_t)(start + srow) * p.stride_n;
+                        const uint4 piece = *reinterpret_cast<const uint4 *>(sp + 8 * c);
+                        const float s_nsq = row_allreduce_sum<16>(dot8(piece, piece));
+                        const uint64_t got = absorb(x, piece, s_nsq, nsq, todo, 0, t_all, tau, sp, block0, p.stride_n, c, lane);
+                        todo &= ~got;
+                        if ((got >> lane) & 1ull) my_o = s;
+                    }
+                    while (todo != 0ull) {
+                        const int i = __builtin_amdgcn_readfirstlane(first_bit(todo));
+                        todo &= ~(1ull << i);
+                        const int o = nseeds;
+                        nseeds += 1;
+                        if (lane == 0)
+                            __hip_atomic_store(seed_bh + start + o, rb + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        uint64_t members = 1ull << i;
+                        if (todo != 0ull) {
+                            const uint4 piece = seed_piece(x, i, c);
+                            const float s_nsq = __shfl(nsq, i, kWave);
+                            const uint64_t got = absorb(x, piece, s_nsq, nsq, todo, 0, t_all, tau,
+                                                        block0 + (int64_t)i * p.stride_n, block0, p.stride_n, c, lane);
+                            todo &= ~got;
+                            members |= got;
+                        }
+                        if ((members >> lane) & 1ull) my_o = o;
+                    }
+                    if (lane < R) cid32_bh[start + rb + lane] = my_o;   // cluster index; pass 2 reads this one
+                    // running sums of the first 16 clusters
+                    int orow_t[16];
+                    orow_to_operand_order(my_o, lane, orow_t);
+                    membership_mfma(x, orow_t, 0, (R + 15) >> 4, lane, D, Dn);
+                    if (rb + kWin < l) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // seed list stores done
+                }
+                const bool deferred = nseeds > 16;
+                if (!deferred) store_tile<TO>(D, Dn, 0, nseeds, ktmp_c, (int64_t)start, (int64_t)p.N_max, lane);
+                if (closed) {
+                    if (lane == 0 && cid_bh) cid_bh[start + l] = -1;
+                    if (!deferred && g == 0) {
+                        // the delimiter's key, unchanged, right after the chunk's cores
+                        float v[8];
+                        load8(Kc_ + (int64_t)(start + l) * p.stride_n, v);
+                        store8(ktmp_c + ((int64_t)start + nseeds) * kFastD, v);
+                    }
+                }
+                if (lane == 0) pcount_bh[m0 + idx] = nseeds | (deferred ? kDeferredBit : 0);
+                idx += 1;
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+template <typename TO>
+__global__ __launch_bounds__(kFastThreads) void gsc_pass2_kernel(GscParams p) {
+    __shared__ int s_off[kMaxChunksPerItem + 1];
+    __shared__ int s_base[kMaxChunksPerItem + 1];
+    __shared__ int s_pc[kMaxChunksPerItem + 1];
+    const int b = blockIdx.z, h = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int g = lane >> 4, c = lane & 15;
+    const int M = p.num_chunks[b];
+    if (M <= 0) return;
+    int n = p.seq_lens ? p.seq_lens[b] : p.N_max;
+    n = n < 0 ? 0 : (n > p.N_max ? p.N_max : n);
+    const int C = p.chunks_per_item;
+    const int per_wave = (C + kFastWaves - 1) / kFastWaves;
+    const int items = (M + C - 1) / C;
+    const int64_t bh = (int64_t)b * p.Hkv + h;
+    const bf16_t *Kbh = reinterpret_cast<const bf16_t *>(p.K) + b * p.stride_b + h * p.stride_h + 8 * c;
+    const bf16_t *Vbh = reinterpret_cast<const bf16_t *>(p.V) + b * p.stride_b + h * p.stride_h + 8 * c;
+    const int32_t *off = p.offsets + (int64_t)b * p.offsets_stride_b;
+    const uint16_t *orow_bh = p.orow + bh * p.N_max;
+    const int32_t *cid32_bh = p.cid + bh * p.N_max;
+    const int32_t *pcount_bh = p.pcount + bh * ((int64_t)p.N_max + 1);
+    const int32_t *rowbase_bh = p.rowbase + bh * ((int64_t)p.N_max + 2);
+    const TO *ktmp_c = reinterpret_cast<const TO *>(p.ktmp) + bh * (int64_t)p.N_max * kFastD + 8 * c;
+    TO *Kc_c = reinterpret_cast<TO *>(p.Kc) + bh * (int64_t)p.cap * kFastD + 8 * c;
+    TO *Vc_c = reinterpret_cast<TO *>(p.Vc) + bh * (int64_t)p.cap * kFastD + 8 * c;
+    int32_t *counts_bh = p.counts + bh * p.cap;
+    const int64_t cap = p.cap;
+
+    for (int item = blockIdx.x; item < items; item += gridDim.x) {
+        const int m0 = item * C;
+        const int nch = min(C, M - m0);
+        __syncthreads();
+        if (tid <= nch) {
+            s_off[tid] = off[m0 + tid];
+            s_base[tid] = rowbase_bh[m0 + tid];
+            s_pc[tid] = (tid < nch) ? pcount_bh[m0 + tid] : 0;
+        }
+        __syncthreads();
+        const int idx_end = min(nch, (wave + 1) * per_wave);
+        int idx = wave * per_wave;
+        while (idx < idx_end) {
+            const int rows_first = __builtin_amdgcn_readfirstlane(chunk_rows(s_off, idx, m0 + idx, M));
+            const int w0 = __builtin_amdgcn_readfirstlane(s_off[idx]);
+            const int64_t out0 = __builtin_amdgcn_readfirstlane(s_base[idx]);
+            if (rows_first <= kWin) {
+                int idx_hi = idx, R = 0;
+                while (idx_hi < idx_end) {
+                    const int rr = __builtin_amdgcn_readfirstlane(chunk_rows(s_off, idx_hi, m0 + idx_hi, M));
+                    if (R + rr > kWin) break;
+                    R += rr;
+                    idx_hi += 1;
+                }
+                const int nseed = __builtin_amdgcn_readfirstlane(s_base[idx_hi]) - (int)out0;
+                RowRegs x;
+                load_rows(x, Vbh, p.stride_n, w0, R, g);
+                const int my_o = (lane < R) ? (int)orow_bh[w0 + lane] : -1;
+                int orow_t[16];
+                orow_to_operand_order(my_o, lane, orow_t);
+                const int q_hi = (R + 15) >> 4;
+                for (int ot = 0; ot * 16 < nseed; ++ot) {
+                    floatx4_t D[8], Dn = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) D[j] = Dn;
+                    membership_mfma(x, orow_t, ot, q_hi, lane, D, Dn);
+                    store_tile<TO>(D, Dn, ot, nseed, Vc_c, out0, cap, lane);
+                    if (c == 0) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int o = 16 * ot + 4 * g + i;
+                            if (o < nseed && out0 + o < cap) counts_bh[out0 + o] = (int)(Dn[i] + 0.5f);
+                        }
+                    }
+                }
+                // merged keys: provisional rows [w0, w0 + nseed) -> final rows
+                for (int o0 = 0; o0 < nseed; o0 += 4) {
+                    const int o = o0 + g;
+                    if (o < nseed && out0 + o < cap) {
+                        float v[8];
+                        load8(ktmp_c + ((int64_t)w0 + o) * kFastD, v);
+                        store8(Kc_c + (out0 + o) * kFastD, v);
+                    }
+                }
+                idx = idx_hi;
+            } else {
+                const int start = w0;
+                const int l = __builtin_amdgcn_readfirstlane(s_off[idx + 1]) - 1 - start;
+                const bool closed = (start + l) < n;
+                const int pc_raw = __builtin_amdgcn_readfirstlane(s_pc[idx]);
+                const bool deferred = (pc_raw & kDeferredBit) != 0;
+                const int pcl = pc_raw & ~kDeferredBit;
+                const int n_out = pcl + (closed ? 1 : 0);
+                const int l_all = l + (closed ? 1 : 0);       // the delimiter row takes part as output row pcl
+                for (int src = 0; src < (deferred ? 2 : 1); ++src) {
+                    const bf16_t *Xbh = (src == 0) ? Vbh : Kbh;
+                    TO *dst_c = (src == 0) ? Vc_c : Kc_c;
+                    for (int ot = 0; ot * 16 < n_out; ++ot) {
+                        floatx4_t D[8], Dn = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) D[j] = Dn;
+                        for (int rb = 0; rb < l_all; rb += kWin) {
+                            const int R = min(kWin, l_all - rb);
+                            RowRegs x;
+                            load_rows(x, Xbh, p.stride_n, start + rb, R, g);
+                            int my_o = -1;
+                            if (lane < R) {
+                                const int tok = start + rb + lane;
+                                my_o = (tok == start + l) ? pcl : cid32_bh[tok];
+                            }
+                            int orow_t[16];
+                            orow_to_operand_order(my_o, lane, orow_t);
+                            membership_mfma(x, orow_t, ot, (R + 15) >> 4, lane, D, Dn);
+                        }
+                        store_tile<TO>(D, Dn, ot, n_out, dst_c, out0, cap, lane);
+                        if (src == 0 && c == 0) {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const int o = 16 * ot + 4 * g + i;
+                                if (o < n_out && out0 + o < cap) counts_bh[out0 + o] = (int)(Dn[i] + 0.5f);
+                            }
+                        }
+                    }
+                }
+                if (!deferred) {
+                    for (int o0 = 0; o0 < n_out; o0 += 4) {
+                        const int o = o0 + g;
+                        if (o < n_out && out0 + o < cap) {
+                            float v[8];
+                            load8(ktmp_c + ((int64_t)start + o) * kFastD, v);
+                            store8(Kc_c + (out0 + o) * kFastD, v);
+                        }
+                    }
+                }
+                idx += 1;
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+hipError_t launch_gsc_fast(const GscParams &p, hipStream_t stream) {
+    const int max_items = (p.N_max + 1 + p.chunks_per_item - 1) / p.chunks_per_item;
+    const int gx = max(1, min(max_items, tuning().gsc_grid_x));
+    const dim3 grid(gx, p.Hkv, p.B);
+    if (p.out_is_bf16) hipLaunchKernelGGL((gsc_pass1_kernel<bf16_t>), grid, dim3(kFastThreads), 0, stream, p);
+    else hipLaunchKernelGGL((gsc_pass1_kernel<float>), grid, dim3(kFastThreads), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = launch_gsc_scan(p, stream);
+    if (e != hipSuccess) return e;
+    if (p.out_is_bf16) hipLaunchKernelGGL((gsc_pass2_kernel<bf16_t>), grid, dim3(kFastThreads), 0, stream, p);
+    else hipLaunchKernelGGL((gsc_pass2_kernel<float>), grid, dim3(kFastThreads), 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace sc

@@ -17,32 +17,10 @@
 //                  fp32 in member order, divides by the size and writes the core; delimiter rows and
 //                  singletons are copied.
 #include "sc_device.h"
+#include "sc_gsc_params.h"
 #include "sc_host.h"
 
 namespace sc {
-
-constexpr int kGscThreads = 256;
-constexpr int kMaxChunksPerItem = 32;
-constexpr float kBand = 1e-4f;   // fp32 cosine error for d <= 128 is < 2e-5; inside the band -> fp64
-
-struct GscParams {
-    const void *K, *V;
-    int64_t stride_b, stride_h, stride_n;
-    const int32_t *seq_lens, *offsets;
-    int64_t offsets_stride_b;
-    const int32_t *num_chunks;
-    int B, Hkv, N_max;
-    float tau;
-    void *Kc, *Vc;
-    int out_is_bf16;
-    int cap;
-    int32_t *counts, *comp_lens;
-    int32_t *cid;        // [B, Hkv, N_max]
-    int32_t *seedrow;    // [B, Hkv, N_max]   seed positions of the chunk being processed
-    int32_t *pcount;     // [B, Hkv, N_max + 1]
-    int32_t *rowbase;    // [B, Hkv, N_max + 2]
-    int chunks_per_item;
-};
 
 // ------------------------------------------------------------------------------------------------
 // fp64 re-evaluation of one (seed, candidate) pair by the whole wave: Eq. 2 in double precision.
@@ -234,7 +212,7 @@ __global__ __launch_bounds__(256) void gsc_scan_kernel(GscParams p) {
 #pragma unroll
         for (int k = 0; k < kItems; ++k) {
             const int m = base + tid * kItems + k;
-            v[k] = (m < M) ? pcount_bh[m] + ((m < M - 1) ? 1 : 0) : 0;
+            v[k] = (m < M) ? (pcount_bh[m] & kPcountMask) + ((m < M - 1) ? 1 : 0) : 0;
             sum += v[k];
         }
         int incl = sum;
@@ -397,14 +375,20 @@ __global__ __launch_bounds__(kGscThreads) void gsc_merge_kernel(GscParams p) {
 
 // ------------------------------------------------------------------------------------------------
 size_t gsc_merge_workspace_bytes(int B, int Hkv, int N_max, int d) {
-    (void)d;
     const size_t bh = (size_t)B * Hkv;
     size_t bytes = 0;
     bytes += align_up(bh * (size_t)N_max * 4, 256);          // cid
     bytes += align_up(bh * (size_t)N_max * 4, 256);          // seedrow
     bytes += align_up(bh * ((size_t)N_max + 1) * 4, 256);    // pcount
     bytes += align_up(bh * ((size_t)N_max + 2) * 4, 256);    // rowbase
+    bytes += align_up(bh * (size_t)N_max * 2, 256);          // orow
+    bytes += align_up(bh * (size_t)N_max * (size_t)d * 4, 256);   // ktmp (sized for fp32 output)
     return bytes;
+}
+
+hipError_t launch_gsc_scan(const GscParams &p, hipStream_t stream) {
+    hipLaunchKernelGGL(gsc_scan_kernel, dim3(p.Hkv, p.B), dim3(256), 0, stream, p);
+    return hipGetLastError();
 }
 
 template <typename T, int D>
@@ -445,7 +429,14 @@ hipError_t launch_gsc_merge(const GscMergeArgs &a, hipStream_t stream) {
     p.pcount = reinterpret_cast<int32_t *>(w);
     w += align_up(bh * ((size_t)a.N_max + 1) * 4, 256);
     p.rowbase = reinterpret_cast<int32_t *>(w);
+    w += align_up(bh * ((size_t)a.N_max + 2) * 4, 256);
+    p.orow = reinterpret_cast<uint16_t *>(w);
+    w += align_up(bh * (size_t)a.N_max * 2, 256);
+    p.ktmp = w;
     p.cid = a.cluster_id ? a.cluster_id : ws_cid;
+    p.cluster_id = a.cluster_id;
+
+    if (a.in_dtype == DType::BF16 && a.d == 128 && tuning().gsc_fast_path) return launch_gsc_fast(p, stream);
 
     if (a.in_dtype == DType::BF16) {
         return a.d == 128 ? launch_typed<bf16_t, 128>(p, stream) : launch_typed<bf16_t, 64>(p, stream);
