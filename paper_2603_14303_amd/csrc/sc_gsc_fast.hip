@@ -29,6 +29,15 @@ typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2f_t;
 typedef short short4_t __attribute__((ext_vector_type(4)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
+#ifdef SC_GSC_TIMING
+// development builds: per-wave timestamps into the unused upper half of the key staging area
+#define SC_GSTAMP(k) do { if (lane == 0) dbg[(((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 4 + wave) * 16 + (k)] = wall_clock64(); } while (0)
+#define SC_GVAL(k, v) do { if (lane == 0) dbg[(((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 4 + wave) * 16 + (k)] = (unsigned long long)(v); } while (0)
+#else
+#define SC_GSTAMP(k) do {} while (0)
+#define SC_GVAL(k, v) do {} while (0)
+#endif
+
 constexpr int kFastThreads = 256;
 constexpr int kFastWaves = kFastThreads / kWave;
 constexpr int kFastD = 128;
@@ -210,6 +219,114 @@ __device__ __forceinline__ void store_tile(const floatx4_t (&D)[8], const floatx
     }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// All pairwise similarities of a window at once (Eq. 2 for every pair the seeds of Alg. 1 can ask for).
+// The window's rows are parked in LDS (row stride 272 B) and read back in the operand layout of
+// v_mfma_f32_16x16x16_bf16 (lane l: row l%16 of a 16-row tile, elements 4*(l/16)..+3 of a 16-element
+// slice); a tile of keys is both the A operand (rows m) and the B operand (rows n) of the Gram tile
+// G[m][n] = k_m . k_n.  The ten upper-triangle tiles of the 64 x 64 Gram matrix take 80 MFMAs.
+// Each lane then turns its 4 x 10 dot products into cosines, compares them with tau and files the
+// outcome as bit m of a per-column word; an OR over the four lane groups completes the words, and lane
+// r (row order) ends up with  yes[r]: bit m set iff Sim(m, r) > tau + band   (m < r or same tile)
+//                             unsure[r]: bit m set iff the fp32 value is within the band (or not a number).
+constexpr int kLdsRowBytes = 272;                         // 256 B of keys + 16 B pad: conflict-free tile reads
+constexpr int kLdsWaveBytes = kWin * kLdsRowBytes + 256;  // + 64 reciprocal norms
+
+__device__ __forceinline__ void wave_lds_fence() {
+    // LDS traffic of one wavefront executes in order; this only stops the compiler from moving
+    // accesses of other lanes' data across the hand-over point
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+__device__ __forceinline__ uint32_t or_rows(uint32_t x) {   // OR over the four 16-lane rows, same lane position
+    auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+    x = r[0] | r[1];
+    r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+    return r[0] | r[1];
+}
+
+__device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, float nsq, int R, float tau, int lane,
+                                               uint64_t &yes_row, uint64_t &unsure_row) {
+    const int g = lane >> 4, c = lane & 15;
+    float *s_rinv = reinterpret_cast<float *>(lds + kWin * kLdsRowBytes);
+#pragma unroll
+    for (int t = 0; t < 16; ++t)
+        *reinterpret_cast<uint4 *>(lds + (4 * t + g) * kLdsRowBytes + 16 * c) = x.r[t];
+    // a norm that is zero, denormal, huge or not a number makes every cosine with that row "unsure"
+    const bool odd = !(nsq > 1e-30f && nsq < 1e30f);
+    s_rinv[lane] = odd ? __builtin_nanf("") : __frsqrt_rn(nsq);
+    wave_lds_fence();
+
+    const int nt = (R + 15) >> 4;   // 16-row tiles in use
+    floatx4_t acc[10];
+#pragma unroll
+    for (int k = 0; k < 10; ++k) acc[k] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        short4_t a[4];
+#pragma unroll
+        for (int I = 0; I < 4; ++I) {
+            const uint2 v = *reinterpret_cast<const uint2 *>(lds + (16 * I + c) * kLdsRowBytes + (16 * ks + 4 * g) * 2);
+            a[I] = __builtin_bit_cast(short4_t, v);
+        }
+        int k = 0;
+#pragma unroll
+        for (int I = 0; I < 4; ++I)
+#pragma unroll
+            for (int J = I; J < 4; ++J) {
+                if (J < nt) acc[k] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a[I], a[J], acc[k], 0, 0, 0);
+                ++k;
+            }
+    }
+    float rn[4];
+    floatx4_t rm[4];
+#pragma unroll
+    for (int I = 0; I < 4; ++I) {
+        rn[I] = s_rinv[16 * I + c];
+        rm[I] = *reinterpret_cast<const floatx4_t *>(s_rinv + 16 * I + 4 * g);
+    }
+    // per column tile J: bits m (0..63) as two dwords
+    uint32_t y[4][2], u[4][2];
+#pragma unroll
+    for (int J = 0; J < 4; ++J) { y[J][0] = y[J][1] = u[J][0] = u[J][1] = 0u; }
+    const float hi_t = tau + kFastBand, lo_t = tau - kFastBand;
+    const int sh = 4 * g;
+    {
+        int k = 0;
+#pragma unroll
+        for (int I = 0; I < 4; ++I)
+#pragma unroll
+            for (int J = I; J < 4; ++J) {
+                if (J < nt) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float sim = acc[k][i] * rm[I][i] * rn[J];
+                        const bool yy = sim > hi_t;
+                        const bool uu = !yy && !(sim < lo_t);
+                        const uint32_t bit = 1u << (16 * (I & 1) + i);
+                        y[J][I >> 1] |= (yy ? bit : 0u) << sh;
+                        u[J][I >> 1] |= (uu ? bit : 0u) << sh;
+                    }
+                }
+                ++k;
+            }
+    }
+    // complete the words over the four lane groups, then every lane keeps the words of its own row
+    uint32_t yl = 0, yh = 0, ul = 0, uh = 0;
+#pragma unroll
+    for (int J = 0; J < 4; ++J) {
+        const uint32_t a0 = or_rows(y[J][0]), a1 = or_rows(y[J][1]);
+        const uint32_t b0 = or_rows(u[J][0]), b1 = or_rows(u[J][1]);
+        if (g == J) { yl = a0; yh = a1; ul = b0; uh = b1; }
+    }
+    yes_row = ((uint64_t)yh << 32) | yl;
+    unsure_row = ((uint64_t)uh << 32) | ul;
+    wave_lds_fence();   // the LDS area is reused by the next window
+}
+
 // ------------------------------------------------------------------------------------------------
 // work decomposition shared by both passes: item = chunks_per_item chunks of one (b, h) handled by a
 // workgroup, wave w takes the contiguous quarter of them; rows of chunk m including its delimiter
@@ -218,9 +335,10 @@ __device__ __forceinline__ int chunk_rows(const int *s_off, int idx, int m, int 
 }
 
 // ------------------------------------------------------------------------------------------------
-template <typename TO>
-__global__ __launch_bounds__(kFastThreads) void gsc_pass1_kernel(GscParams p) {
+template <typename TO, bool LONG>
+__global__ __launch_bounds__(kFastThreads, 2) void gsc_pass1_kernel(GscParams p) {
     __shared__ int s_off[kMaxChunksPerItem + 1];
+    __shared__ __attribute__((aligned(16))) char s_lds[LONG ? 16 : kFastWaves * kLdsWaveBytes];
     const int b = blockIdx.z, h = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -243,6 +361,11 @@ __global__ __launch_bounds__(kFastThreads) void gsc_pass1_kernel(GscParams p) {
     int32_t *cid32_bh = p.cid + bh * p.N_max;                                    // always there (workspace)
     TO *ktmp_c = reinterpret_cast<TO *>(p.ktmp) + bh * (int64_t)p.N_max * kFastD + 8 * c;
     const float tau = p.tau;
+#ifdef SC_GSC_TIMING
+    unsigned long long *dbg = reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(p.ktmp) + (size_t)p.B * p.Hkv * p.N_max * kFastD * 2);
+    int first_window = 1;
+#endif
+    SC_GSTAMP(0);
 
     for (int item = blockIdx.x; item < items; item += gridDim.x) {
         const int m0 = item * C;
@@ -250,6 +373,7 @@ __global__ __launch_bounds__(kFastThreads) void gsc_pass1_kernel(GscParams p) {
         __syncthreads();
         if (tid <= nch) s_off[tid] = off[m0 + tid];
         __syncthreads();
+        SC_GSTAMP(1);
         const int idx_end = min(nch, (wave + 1) * per_wave);
         int idx = wave * per_wave;
         while (idx < idx_end) {
@@ -265,6 +389,7 @@ __global__ __launch_bounds__(kFastThreads) void gsc_pass1_kernel(GscParams p) {
                     idx_hi += 1;
                 }
                 const int nchw = idx_hi - idx;
+                if (LONG) { idx = idx_hi; continue; }   // windows belong to the other instantiation
                 RowRegs x;
                 load_rows(x, Kc_, p.stride_n, w0, R, g);
                 const int t_all = (R + 3) >> 2;
@@ -277,6 +402,11 @@ __global__ __launch_bounds__(kFastThreads) void gsc_pass1_kernel(GscParams p) {
                     if (lane >= cs && lane < ce) { lo = cs; hi = ce; in_chunk = true; }
                 }
                 const float nsq = rows_norm2(x, t_all, c, lane);
+                uint64_t yes_row, unsure_row;
+                gram_bitmatrix(s_lds + wave * kLdsWaveBytes, x, nsq, R, tau, lane, yes_row, unsure_row);
+#ifdef SC_GSC_TIMING
+                if (first_window) { SC_GSTAMP(2); }
+#endif
                 uint64_t todo = bits_range(0, R);
                 uint64_t seedmask = 0ull;
                 int nseed = 0, my_o = -1, my_cid = -1, cur_lo = -1, cfo = 0;
@@ -291,16 +421,25 @@ __global__ __launch_bounds__(kFastThreads) void gsc_pass1_kernel(GscParams p) {
                     const uint64_t cmask = bits_range(lo_i, hi_i) & todo;
                     uint64_t members = 1ull << i;
                     if (cmask != 0ull) {
-                        const uint4 piece = seed_piece(x, i, c);
-                        const float s_nsq = __shfl(nsq, i, kWave);
-                        const uint64_t got = absorb(x, piece, s_nsq, nsq, cmask, lo_i >> 2, (hi_i + 3) >> 2, tau,
-                                                    Kbh + (int64_t)(w0 + i) * p.stride_n,
-                                                    Kbh + (int64_t)w0 * p.stride_n, p.stride_n, c, lane);
+                        const bool cand = (cmask >> lane) & 1ull;
+                        bool yes = cand && ((yes_row >> i) & 1ull);
+                        uint64_t recheck = ballot64(cand && ((unsure_row >> i) & 1ull));
+                        while (recheck != 0ull) {
+                            const int j = first_bit(recheck);
+                            recheck &= recheck - 1ull;
+                            const bool res = cosine_exceeds_f64_fast(Kbh + (int64_t)(w0 + i) * p.stride_n,
+                                                                     Kbh + (int64_t)(w0 + j) * p.stride_n, tau, lane);
+                            if (lane == j) yes = res;
+                        }
+                        const uint64_t got = ballot64(yes);
                         todo &= ~got;
                         members |= got;
                     }
                     if ((members >> lane) & 1ull) { my_o = o; my_cid = in_chunk ? (o - cfo) : -1; }
                 }
+#ifdef SC_GSC_TIMING
+                if (first_window) { SC_GSTAMP(3); SC_GVAL(8, nseed); SC_GVAL(9, R); }
+#endif
                 if (lane < R) {
                     orow_bh[w0 + lane] = (uint16_t)my_o;
                     if (cid_bh) cid_bh[w0 + lane] = my_cid;
@@ -320,9 +459,13 @@ __global__ __launch_bounds__(kFastThreads) void gsc_pass1_kernel(GscParams p) {
                     membership_mfma(x, orow_t, ot, q_hi, lane, D, Dn);
                     store_tile<TO>(D, Dn, ot, nseed, ktmp_c, (int64_t)w0, (int64_t)p.N_max, lane);
                 }
+#ifdef SC_GSC_TIMING
+                if (first_window) { SC_GSTAMP(4); first_window = 0; }
+#endif
                 idx = idx_hi;
             } else {
                 // ---------------- one chunk longer than a window: blocks of 64 rows, seeds carried along
+                if (!LONG) { idx += 1; continue; }
                 const int start = w0;
                 const int l = __builtin_amdgcn_readfirstlane(s_off[idx + 1]) - 1 - start;
                 const bool closed = (start + l) < n;
@@ -389,12 +532,13 @@ __global__ __launch_bounds__(kFastThreads) void gsc_pass1_kernel(GscParams p) {
                 idx += 1;
             }
         }
+        SC_GSTAMP(5);
     }
 }
 
 // ------------------------------------------------------------------------------------------------
 template <typename TO>
-__global__ __launch_bounds__(kFastThreads) void gsc_pass2_kernel(GscParams p) {
+__global__ __launch_bounds__(kFastThreads, 2) void gsc_pass2_kernel(GscParams p) {
     __shared__ int s_off[kMaxChunksPerItem + 1];
     __shared__ int s_base[kMaxChunksPerItem + 1];
     __shared__ int s_pc[kMaxChunksPerItem + 1];
@@ -422,6 +566,11 @@ __global__ __launch_bounds__(kFastThreads) void gsc_pass2_kernel(GscParams p) {
     TO *Vc_c = reinterpret_cast<TO *>(p.Vc) + bh * (int64_t)p.cap * kFastD + 8 * c;
     int32_t *counts_bh = p.counts + bh * p.cap;
     const int64_t cap = p.cap;
+#ifdef SC_GSC_TIMING
+    unsigned long long *dbg = reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(p.ktmp) + (size_t)p.B * p.Hkv * p.N_max * kFastD * 2) + (size_t)gridDim.x * gridDim.y * gridDim.z * 64;
+    int first_window = 1;
+#endif
+    SC_GSTAMP(0);
 
     for (int item = blockIdx.x; item < items; item += gridDim.x) {
         const int m0 = item * C;
@@ -433,6 +582,7 @@ __global__ __launch_bounds__(kFastThreads) void gsc_pass2_kernel(GscParams p) {
             s_pc[tid] = (tid < nch) ? pcount_bh[m0 + tid] : 0;
         }
         __syncthreads();
+        SC_GSTAMP(1);
         const int idx_end = min(nch, (wave + 1) * per_wave);
         int idx = wave * per_wave;
         while (idx < idx_end) {
@@ -453,6 +603,9 @@ __global__ __launch_bounds__(kFastThreads) void gsc_pass2_kernel(GscParams p) {
                 const int my_o = (lane < R) ? (int)orow_bh[w0 + lane] : -1;
                 int orow_t[16];
                 orow_to_operand_order(my_o, lane, orow_t);
+#ifdef SC_GSC_TIMING
+                if (first_window) { SC_GSTAMP(2); SC_GVAL(8, nseed); SC_GVAL(9, R); }
+#endif
                 const int q_hi = (R + 15) >> 4;
                 for (int ot = 0; ot * 16 < nseed; ++ot) {
                     floatx4_t D[8], Dn = {0.f, 0.f, 0.f, 0.f};
@@ -468,6 +621,9 @@ __global__ __launch_bounds__(kFastThreads) void gsc_pass2_kernel(GscParams p) {
                         }
                     }
                 }
+#ifdef SC_GSC_TIMING
+                if (first_window) { SC_GSTAMP(3); }
+#endif
                 // merged keys: provisional rows [w0, w0 + nseed) -> final rows
                 for (int o0 = 0; o0 < nseed; o0 += 4) {
                     const int o = o0 + g;
@@ -477,6 +633,9 @@ __global__ __launch_bounds__(kFastThreads) void gsc_pass2_kernel(GscParams p) {
                         store8(Kc_c + (out0 + o) * kFastD, v);
                     }
                 }
+#ifdef SC_GSC_TIMING
+                if (first_window) { SC_GSTAMP(4); first_window = 0; }
+#endif
                 idx = idx_hi;
             } else {
                 const int start = w0;
@@ -530,6 +689,7 @@ __global__ __launch_bounds__(kFastThreads) void gsc_pass2_kernel(GscParams p) {
                 idx += 1;
             }
         }
+        SC_GSTAMP(5);
     }
 }
 
@@ -538,9 +698,14 @@ hipError_t launch_gsc_fast(const GscParams &p, hipStream_t stream) {
     const int max_items = (p.N_max + 1 + p.chunks_per_item - 1) / p.chunks_per_item;
     const int gx = max(1, min(max_items, tuning().gsc_grid_x));
     const dim3 grid(gx, p.Hkv, p.B);
-    if (p.out_is_bf16) hipLaunchKernelGGL((gsc_pass1_kernel<bf16_t>), grid, dim3(kFastThreads), 0, stream, p);
-    else hipLaunchKernelGGL((gsc_pass1_kernel<float>), grid, dim3(kFastThreads), 0, stream, p);
+    if (p.out_is_bf16) hipLaunchKernelGGL((gsc_pass1_kernel<bf16_t, false>), grid, dim3(kFastThreads), 0, stream, p);
+    else hipLaunchKernelGGL((gsc_pass1_kernel<float, false>), grid, dim3(kFastThreads), 0, stream, p);
     hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // chunks longer than one window (same decomposition, the other code path)
+    if (p.out_is_bf16) hipLaunchKernelGGL((gsc_pass1_kernel<bf16_t, true>), grid, dim3(kFastThreads), 0, stream, p);
+    else hipLaunchKernelGGL((gsc_pass1_kernel<float, true>), grid, dim3(kFastThreads), 0, stream, p);
+    e = hipGetLastError();
     if (e != hipSuccess) return e;
     e = launch_gsc_scan(p, stream);
     if (e != hipSuccess) return e;
