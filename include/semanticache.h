@@ -159,7 +159,7 @@ sc_status sc_decode_attn(const void *Q, sc_dtype q_dtype,
 /* ------------------------------------------------------------------------------------------------
  * Launch-shape knobs for experiments (process-wide, not thread-safe; results never depend on them
  * beyond floating-point summation order in sc_decode_attn).  Keys: "decode_max_splits",
- * "decode_min_rows", "gsc_chunks_per_item", "gsc_grid_x", "gsc_fast_path".  Return 0 / the value, or -1 for an
+ * "decode_min_rows", "gsc_chunks_per_item", "gsc_grid_x", "gsc_fast_path", "gsc_chunks_per_task".  Return 0 / the value, or -1 for an
  * unknown key.
  */
 int sc_tune_set(const char *key, int value);

@@ -31,15 +31,14 @@ typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
 #ifdef SC_GSC_TIMING
 // development builds: per-wave timestamps into the unused upper half of the key staging area
-#define SC_GSTAMP(k) do { if (lane == 0) dbg[(((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 4 + wave) * 16 + (k)] = wall_clock64(); } while (0)
-#define SC_GVAL(k, v) do { if (lane == 0) dbg[(((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 4 + wave) * 16 + (k)] = (unsigned long long)(v); } while (0)
+#define SC_GSTAMP(k) do { if (lane == 0) dbg[(((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 1 + wave) * 16 + (k)] = wall_clock64(); } while (0)
+#define SC_GVAL(k, v) do { if (lane == 0) dbg[(((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 1 + wave) * 16 + (k)] = (unsigned long long)(v); } while (0)
 #else
 #define SC_GSTAMP(k) do {} while (0)
 #define SC_GVAL(k, v) do {} while (0)
 #endif
 
-constexpr int kFastThreads = 256;
-constexpr int kFastWaves = kFastThreads / kWave;
+
 constexpr int kFastD = 128;
 constexpr int kWin = 64;                 // rows of a window
 constexpr int kDeferredBit = 1 << 30;    // pcount flag: key merge of this chunk happens in pass 2 (see kPcountMask)
@@ -201,6 +200,25 @@ __device__ __forceinline__ void orow_to_operand_order(int my_o, int lane, int (&
         for (int i = 0; i < 4; ++i) orow_t[4 * q + i] = lane_gather(my_o, 16 * q + 4 * i + g);
 }
 
+// 8 elements of an output row, moved without conversion
+template <typename TO> struct RawPiece;
+template <> struct RawPiece<bf16_t> {
+    uint4 v;
+    __device__ __forceinline__ void load(const bf16_t *p) { v = *reinterpret_cast<const uint4 *>(p); }
+    __device__ __forceinline__ void store(bf16_t *p) const { *reinterpret_cast<uint4 *>(p) = v; }
+};
+template <> struct RawPiece<float> {
+    float4 a, b;
+    __device__ __forceinline__ void load(const float *p) {
+        a = *reinterpret_cast<const float4 *>(p);
+        b = *reinterpret_cast<const float4 *>(p + 4);
+    }
+    __device__ __forceinline__ void store(float *p) const {
+        *reinterpret_cast<float4 *>(p) = a;
+        *reinterpret_cast<float4 *>(p + 4) = b;
+    }
+};
+
 // scale the sums of tile `ot` by 1/size and store rows [16*ot, 16*ot+16) ∩ [0, n_out) at dst_row0 + o
 template <typename TO>
 __device__ __forceinline__ void store_tile(const floatx4_t (&D)[8], const floatx4_t &Dn, int ot, int n_out, TO *dst_c,
@@ -328,28 +346,37 @@ __device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, floa
 }
 
 // ------------------------------------------------------------------------------------------------
-// work decomposition shared by both passes: item = chunks_per_item chunks of one (b, h) handled by a
-// workgroup, wave w takes the contiguous quarter of them; rows of chunk m including its delimiter
-__device__ __forceinline__ int chunk_rows(const int *s_off, int idx, int m, int M) {
-    return (m < M - 1) ? (s_off[idx + 1] - s_off[idx]) : (s_off[idx + 1] - 1 - s_off[idx]);
-}
+// Work decomposition shared by both passes: a task is `chunks_per_item` (<= 32) consecutive chunks of
+// one (sequence, head), handled by one single-wavefront workgroup, so a finished task frees its
+// registers and LDS at once and the hardware dispatcher balances the load.  The task's chunk offsets
+// live in one register (lane j holds offsets[m0 + j]) and are read with v_readlane.
+struct TaskOffsets {
+    int v;      // lane j: offsets[m0 + j] for j <= nch
+    int m0, M;
+    __device__ __forceinline__ int at(int j) const { return __builtin_amdgcn_readlane(v, j); }
+    // rows of chunk idx of the task including its closing delimiter (the last chunk of a sequence has none)
+    __device__ __forceinline__ int rows(int idx) const {
+        return (m0 + idx < M - 1) ? (at(idx + 1) - at(idx)) : (at(idx + 1) - 1 - at(idx));
+    }
+};
+
+constexpr int kFastTaskThreads = kWave;
 
 // ------------------------------------------------------------------------------------------------
 template <typename TO, bool LONG>
-__global__ __launch_bounds__(kFastThreads, 2) void gsc_pass1_kernel(GscParams p) {
-    __shared__ int s_off[kMaxChunksPerItem + 1];
-    __shared__ __attribute__((aligned(16))) char s_lds[LONG ? 16 : kFastWaves * kLdsWaveBytes];
+__global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_pass1_kernel(GscParams p) {
+    __shared__ __attribute__((aligned(16))) char s_lds[LONG ? 16 : kLdsWaveBytes];
     const int b = blockIdx.z, h = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int lane = threadIdx.x;
+    const int wave = 0;
+    (void)wave;
     const int g = lane >> 4, c = lane & 15;
     const int M = p.num_chunks[b];
     if (M <= 0) return;
     int n = p.seq_lens ? p.seq_lens[b] : p.N_max;
     n = n < 0 ? 0 : (n > p.N_max ? p.N_max : n);
     const int C = p.chunks_per_item;
-    const int per_wave = (C + kFastWaves - 1) / kFastWaves;
-    const int items = (M + C - 1) / C;
+    const int tasks = (M + C - 1) / C;
     const int64_t bh = (int64_t)b * p.Hkv + h;
     const bf16_t *Kbh = reinterpret_cast<const bf16_t *>(p.K) + b * p.stride_b + h * p.stride_h;
     const bf16_t *Kc_ = Kbh + 8 * c;   // this lane's column piece
@@ -362,28 +389,28 @@ __global__ __launch_bounds__(kFastThreads, 2) void gsc_pass1_kernel(GscParams p)
     TO *ktmp_c = reinterpret_cast<TO *>(p.ktmp) + bh * (int64_t)p.N_max * kFastD + 8 * c;
     const float tau = p.tau;
 #ifdef SC_GSC_TIMING
-    unsigned long long *dbg = reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(p.ktmp) + (size_t)p.B * p.Hkv * p.N_max * kFastD * 2);
+    unsigned long long *dbg = reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(p.ktmp) + (size_t)p.B * p.Hkv * p.N_max * kFastD * 2) + (LONG ? (size_t)gridDim.x * gridDim.y * gridDim.z * 128 : 0);
     int first_window = 1;
 #endif
     SC_GSTAMP(0);
 
-    for (int item = blockIdx.x; item < items; item += gridDim.x) {
-        const int m0 = item * C;
+    for (int task = blockIdx.x; task < tasks; task += gridDim.x) {
+        TaskOffsets to;
+        to.m0 = task * C;
+        to.M = M;
+        const int m0 = to.m0;
         const int nch = min(C, M - m0);
-        __syncthreads();
-        if (tid <= nch) s_off[tid] = off[m0 + tid];
-        __syncthreads();
+        to.v = (lane <= nch) ? off[m0 + lane] : 0;
         SC_GSTAMP(1);
-        const int idx_end = min(nch, (wave + 1) * per_wave);
-        int idx = wave * per_wave;
-        while (idx < idx_end) {
-            const int rows_first = __builtin_amdgcn_readfirstlane(chunk_rows(s_off, idx, m0 + idx, M));
-            const int w0 = __builtin_amdgcn_readfirstlane(s_off[idx]);
+        int idx = 0;
+        while (idx < nch) {
+            const int rows_first = to.rows(idx);
+            const int w0 = to.at(idx);
             if (rows_first <= kWin) {
                 // ---------------- window of whole chunks, at most 64 rows
                 int idx_hi = idx, R = 0;
-                while (idx_hi < idx_end) {
-                    const int rr = __builtin_amdgcn_readfirstlane(chunk_rows(s_off, idx_hi, m0 + idx_hi, M));
+                while (idx_hi < nch) {
+                    const int rr = to.rows(idx_hi);
                     if (R + rr > kWin) break;
                     R += rr;
                     idx_hi += 1;
@@ -397,56 +424,58 @@ __global__ __launch_bounds__(kFastThreads, 2) void gsc_pass1_kernel(GscParams p)
                 int lo = lane, hi = lane + 1;
                 bool in_chunk = false;
                 for (int j = 0; j < nchw; ++j) {
-                    const int cs = __builtin_amdgcn_readfirstlane(s_off[idx + j]) - w0;
-                    const int ce = __builtin_amdgcn_readfirstlane(s_off[idx + j + 1]) - 1 - w0;
+                    const int cs = to.at(idx + j) - w0;
+                    const int ce = to.at(idx + j + 1) - 1 - w0;
                     if (lane >= cs && lane < ce) { lo = cs; hi = ce; in_chunk = true; }
                 }
                 const float nsq = rows_norm2(x, t_all, c, lane);
                 uint64_t yes_row, unsure_row;
-                gram_bitmatrix(s_lds + wave * kLdsWaveBytes, x, nsq, R, tau, lane, yes_row, unsure_row);
+                gram_bitmatrix(s_lds, x, nsq, R, tau, lane, yes_row, unsure_row);
 #ifdef SC_GSC_TIMING
                 if (first_window) { SC_GSTAMP(2); }
 #endif
+                // Alg. 1 on the bit matrix, one seed per chunk and round: the first unassigned row of a
+                // chunk is its next seed and absorbs the unassigned rows of the chunk whose bit is set
+                const uint64_t my_range = bits_range(lo, hi);
                 uint64_t todo = bits_range(0, R);
                 uint64_t seedmask = 0ull;
-                int nseed = 0, my_o = -1, my_cid = -1, cur_lo = -1, cfo = 0;
+                int my_seed = -1;
                 while (todo != 0ull) {
-                    const int i = __builtin_amdgcn_readfirstlane(first_bit(todo));
-                    todo &= ~(1ull << i);
-                    seedmask |= 1ull << i;
-                    const int o = nseed;
-                    nseed += 1;
-                    const int lo_i = __builtin_amdgcn_readlane(lo, i), hi_i = __builtin_amdgcn_readlane(hi, i);
-                    if (lo_i != cur_lo) { cur_lo = lo_i; cfo = o; }
-                    const uint64_t cmask = bits_range(lo_i, hi_i) & todo;
-                    uint64_t members = 1ull << i;
-                    if (cmask != 0ull) {
-                        const bool cand = (cmask >> lane) & 1ull;
-                        bool yes = cand && ((yes_row >> i) & 1ull);
-                        uint64_t recheck = ballot64(cand && ((unsure_row >> i) & 1ull));
-                        while (recheck != 0ull) {
-                            const int j = first_bit(recheck);
-                            recheck &= recheck - 1ull;
-                            const bool res = cosine_exceeds_f64_fast(Kbh + (int64_t)(w0 + i) * p.stride_n,
-                                                                     Kbh + (int64_t)(w0 + j) * p.stride_n, tau, lane);
-                            if (lane == j) yes = res;
-                        }
-                        const uint64_t got = ballot64(yes);
-                        todo &= ~got;
-                        members |= got;
+                    const uint64_t mine = todo & my_range;
+                    const int s = (mine != 0ull) ? (__ffsll((unsigned long long)mine) - 1) : 64;
+                    const bool open = (todo >> lane) & 1ull;
+                    const bool is_seed = open && (s == lane);
+                    const bool cand = open && (s != lane);
+                    bool yes = cand && ((yes_row >> (s & 63)) & 1ull);
+                    uint64_t recheck = ballot64(cand && ((unsure_row >> (s & 63)) & 1ull));
+                    while (recheck != 0ull) {
+                        const int j = __builtin_amdgcn_readfirstlane(first_bit(recheck));
+                        recheck &= recheck - 1ull;
+                        const int sj = __builtin_amdgcn_readlane(s, j);
+                        const bool res = cosine_exceeds_f64_fast(Kbh + (int64_t)(w0 + sj) * p.stride_n,
+                                                                 Kbh + (int64_t)(w0 + j) * p.stride_n, tau, lane);
+                        if (lane == j) yes = res;
                     }
-                    if ((members >> lane) & 1ull) { my_o = o; my_cid = in_chunk ? (o - cfo) : -1; }
+                    const uint64_t seeds_now = ballot64(is_seed);
+                    const uint64_t got = ballot64(yes);
+                    if (is_seed || yes) my_seed = s;
+                    seedmask |= seeds_now;
+                    todo &= ~(seeds_now | got);
                 }
+                // seeds in row order are the output rows of the window
+                const int nseed = __popcll(seedmask);
+                const int my_o = (lane < R) ? __popcll(seedmask & bits_range(0, my_seed)) : -1;
 #ifdef SC_GSC_TIMING
                 if (first_window) { SC_GSTAMP(3); SC_GVAL(8, nseed); SC_GVAL(9, R); }
 #endif
                 if (lane < R) {
                     orow_bh[w0 + lane] = (uint16_t)my_o;
-                    if (cid_bh) cid_bh[w0 + lane] = my_cid;
+                    if (cid_bh) cid_bh[w0 + lane] = in_chunk ? __popcll(seedmask & bits_range(lo, my_seed)) : -1;
                 }
-                if (lane < nchw) {
-                    const int cs = s_off[idx + lane] - w0, ce = s_off[idx + lane + 1] - 1 - w0;
-                    pcount_bh[m0 + idx + lane] = __popcll(seedmask & bits_range(cs, ce));
+                {
+                    const int cs = __shfl(to.v, min(idx + lane, 63), kWave) - w0;
+                    const int ce = __shfl(to.v, min(idx + lane + 1, 63), kWave) - 1 - w0;
+                    if (lane < nchw) pcount_bh[m0 + idx + lane] = __popcll(seedmask & bits_range(cs, ce));
                 }
                 // merged keys of the window -> provisional rows [w0, w0 + nseed)
                 int orow_t[16];
@@ -467,7 +496,7 @@ __global__ __launch_bounds__(kFastThreads, 2) void gsc_pass1_kernel(GscParams p)
                 // ---------------- one chunk longer than a window: blocks of 64 rows, seeds carried along
                 if (!LONG) { idx += 1; continue; }
                 const int start = w0;
-                const int l = __builtin_amdgcn_readfirstlane(s_off[idx + 1]) - 1 - start;
+                const int l = to.at(idx + 1) - 1 - start;
                 const bool closed = (start + l) < n;
                 int nseeds = 0;
                 floatx4_t D[8], Dn = {0.f, 0.f, 0.f, 0.f};
@@ -538,21 +567,18 @@ __global__ __launch_bounds__(kFastThreads, 2) void gsc_pass1_kernel(GscParams p)
 
 // ------------------------------------------------------------------------------------------------
 template <typename TO>
-__global__ __launch_bounds__(kFastThreads, 2) void gsc_pass2_kernel(GscParams p) {
-    __shared__ int s_off[kMaxChunksPerItem + 1];
-    __shared__ int s_base[kMaxChunksPerItem + 1];
-    __shared__ int s_pc[kMaxChunksPerItem + 1];
+__global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_pass2_kernel(GscParams p) {
     const int b = blockIdx.z, h = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int lane = threadIdx.x;
+    const int wave = 0;
+    (void)wave;
     const int g = lane >> 4, c = lane & 15;
     const int M = p.num_chunks[b];
     if (M <= 0) return;
     int n = p.seq_lens ? p.seq_lens[b] : p.N_max;
     n = n < 0 ? 0 : (n > p.N_max ? p.N_max : n);
     const int C = p.chunks_per_item;
-    const int per_wave = (C + kFastWaves - 1) / kFastWaves;
-    const int items = (M + C - 1) / C;
+    const int tasks = (M + C - 1) / C;
     const int64_t bh = (int64_t)b * p.Hkv + h;
     const bf16_t *Kbh = reinterpret_cast<const bf16_t *>(p.K) + b * p.stride_b + h * p.stride_h + 8 * c;
     const bf16_t *Vbh = reinterpret_cast<const bf16_t *>(p.V) + b * p.stride_b + h * p.stride_h + 8 * c;
@@ -572,35 +598,41 @@ __global__ __launch_bounds__(kFastThreads, 2) void gsc_pass2_kernel(GscParams p)
 #endif
     SC_GSTAMP(0);
 
-    for (int item = blockIdx.x; item < items; item += gridDim.x) {
-        const int m0 = item * C;
+    for (int task = blockIdx.x; task < tasks; task += gridDim.x) {
+        TaskOffsets to;
+        to.m0 = task * C;
+        to.M = M;
+        const int m0 = to.m0;
         const int nch = min(C, M - m0);
-        __syncthreads();
-        if (tid <= nch) {
-            s_off[tid] = off[m0 + tid];
-            s_base[tid] = rowbase_bh[m0 + tid];
-            s_pc[tid] = (tid < nch) ? pcount_bh[m0 + tid] : 0;
-        }
-        __syncthreads();
+        to.v = (lane <= nch) ? off[m0 + lane] : 0;
+        const int basev = (lane <= nch) ? rowbase_bh[m0 + lane] : 0;
+        const int pcv = (lane < nch) ? pcount_bh[m0 + lane] : 0;
         SC_GSTAMP(1);
-        const int idx_end = min(nch, (wave + 1) * per_wave);
-        int idx = wave * per_wave;
-        while (idx < idx_end) {
-            const int rows_first = __builtin_amdgcn_readfirstlane(chunk_rows(s_off, idx, m0 + idx, M));
-            const int w0 = __builtin_amdgcn_readfirstlane(s_off[idx]);
-            const int64_t out0 = __builtin_amdgcn_readfirstlane(s_base[idx]);
+        int idx = 0;
+        while (idx < nch) {
+            const int rows_first = to.rows(idx);
+            const int w0 = to.at(idx);
+            const int64_t out0 = __builtin_amdgcn_readlane(basev, idx);
             if (rows_first <= kWin) {
                 int idx_hi = idx, R = 0;
-                while (idx_hi < idx_end) {
-                    const int rr = __builtin_amdgcn_readfirstlane(chunk_rows(s_off, idx_hi, m0 + idx_hi, M));
+                while (idx_hi < nch) {
+                    const int rr = to.rows(idx_hi);
                     if (R + rr > kWin) break;
                     R += rr;
                     idx_hi += 1;
                 }
-                const int nseed = __builtin_amdgcn_readfirstlane(s_base[idx_hi]) - (int)out0;
+                const int nseed = __builtin_amdgcn_readlane(basev, idx_hi) - (int)out0;
                 RowRegs x;
                 load_rows(x, Vbh, p.stride_n, w0, R, g);
                 const int my_o = (lane < R) ? (int)orow_bh[w0 + lane] : -1;
+                // merged keys of the window: provisional rows [w0, w0 + nseed); the first 16 are fetched
+                // now and stored at the end, so their latency hides behind the value merge
+                RawPiece<TO> kmove[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int o = 4 * k + g;
+                    if (o < nseed) kmove[k].load(ktmp_c + ((int64_t)w0 + o) * kFastD);
+                }
                 int orow_t[16];
                 orow_to_operand_order(my_o, lane, orow_t);
 #ifdef SC_GSC_TIMING
@@ -624,13 +656,17 @@ __global__ __launch_bounds__(kFastThreads, 2) void gsc_pass2_kernel(GscParams p)
 #ifdef SC_GSC_TIMING
                 if (first_window) { SC_GSTAMP(3); }
 #endif
-                // merged keys: provisional rows [w0, w0 + nseed) -> final rows
-                for (int o0 = 0; o0 < nseed; o0 += 4) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int o = 4 * k + g;
+                    if (o < nseed && out0 + o < cap) kmove[k].store(Kc_c + (out0 + o) * kFastD);
+                }
+                for (int o0 = 16; o0 < nseed; o0 += 4) {
                     const int o = o0 + g;
                     if (o < nseed && out0 + o < cap) {
-                        float v[8];
-                        load8(ktmp_c + ((int64_t)w0 + o) * kFastD, v);
-                        store8(Kc_c + (out0 + o) * kFastD, v);
+                        RawPiece<TO> t;
+                        t.load(ktmp_c + ((int64_t)w0 + o) * kFastD);
+                        t.store(Kc_c + (out0 + o) * kFastD);
                     }
                 }
 #ifdef SC_GSC_TIMING
@@ -639,9 +675,9 @@ __global__ __launch_bounds__(kFastThreads, 2) void gsc_pass2_kernel(GscParams p)
                 idx = idx_hi;
             } else {
                 const int start = w0;
-                const int l = __builtin_amdgcn_readfirstlane(s_off[idx + 1]) - 1 - start;
+                const int l = to.at(idx + 1) - 1 - start;
                 const bool closed = (start + l) < n;
-                const int pc_raw = __builtin_amdgcn_readfirstlane(s_pc[idx]);
+                const int pc_raw = __builtin_amdgcn_readlane(pcv, idx);
                 const bool deferred = (pc_raw & kDeferredBit) != 0;
                 const int pcl = pc_raw & ~kDeferredBit;
                 const int n_out = pcl + (closed ? 1 : 0);
@@ -680,9 +716,9 @@ __global__ __launch_bounds__(kFastThreads, 2) void gsc_pass2_kernel(GscParams p)
                     for (int o0 = 0; o0 < n_out; o0 += 4) {
                         const int o = o0 + g;
                         if (o < n_out && out0 + o < cap) {
-                            float v[8];
-                            load8(ktmp_c + ((int64_t)start + o) * kFastD, v);
-                            store8(Kc_c + (out0 + o) * kFastD, v);
+                            RawPiece<TO> t;
+                            t.load(ktmp_c + ((int64_t)start + o) * kFastD);
+                            t.store(Kc_c + (out0 + o) * kFastD);
                         }
                     }
                 }
@@ -695,22 +731,22 @@ __global__ __launch_bounds__(kFastThreads, 2) void gsc_pass2_kernel(GscParams p)
 
 // ------------------------------------------------------------------------------------------------
 hipError_t launch_gsc_fast(const GscParams &p, hipStream_t stream) {
-    const int max_items = (p.N_max + 1 + p.chunks_per_item - 1) / p.chunks_per_item;
-    const int gx = max(1, min(max_items, tuning().gsc_grid_x));
+    const int max_tasks = (p.N_max + 1 + p.chunks_per_item - 1) / p.chunks_per_item;
+    const int gx = max(1, min(max_tasks, tuning().gsc_grid_x));
     const dim3 grid(gx, p.Hkv, p.B);
-    if (p.out_is_bf16) hipLaunchKernelGGL((gsc_pass1_kernel<bf16_t, false>), grid, dim3(kFastThreads), 0, stream, p);
-    else hipLaunchKernelGGL((gsc_pass1_kernel<float, false>), grid, dim3(kFastThreads), 0, stream, p);
+    if (p.out_is_bf16) hipLaunchKernelGGL((gsc_pass1_kernel<bf16_t, false>), grid, dim3(kFastTaskThreads), 0, stream, p);
+    else hipLaunchKernelGGL((gsc_pass1_kernel<float, false>), grid, dim3(kFastTaskThreads), 0, stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // chunks longer than one window (same decomposition, the other code path)
-    if (p.out_is_bf16) hipLaunchKernelGGL((gsc_pass1_kernel<bf16_t, true>), grid, dim3(kFastThreads), 0, stream, p);
-    else hipLaunchKernelGGL((gsc_pass1_kernel<float, true>), grid, dim3(kFastThreads), 0, stream, p);
+    if (p.out_is_bf16) hipLaunchKernelGGL((gsc_pass1_kernel<bf16_t, true>), grid, dim3(kFastTaskThreads), 0, stream, p);
+    else hipLaunchKernelGGL((gsc_pass1_kernel<float, true>), grid, dim3(kFastTaskThreads), 0, stream, p);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     e = launch_gsc_scan(p, stream);
     if (e != hipSuccess) return e;
-    if (p.out_is_bf16) hipLaunchKernelGGL((gsc_pass2_kernel<bf16_t>), grid, dim3(kFastThreads), 0, stream, p);
-    else hipLaunchKernelGGL((gsc_pass2_kernel<float>), grid, dim3(kFastThreads), 0, stream, p);
+    if (p.out_is_bf16) hipLaunchKernelGGL((gsc_pass2_kernel<bf16_t>), grid, dim3(kFastTaskThreads), 0, stream, p);
+    else hipLaunchKernelGGL((gsc_pass2_kernel<float>), grid, dim3(kFastTaskThreads), 0, stream, p);
     return hipGetLastError();
 }
 

@@ -436,7 +436,10 @@ hipError_t launch_gsc_merge(const GscMergeArgs &a, hipStream_t stream) {
     p.cid = a.cluster_id ? a.cluster_id : ws_cid;
     p.cluster_id = a.cluster_id;
 
-    if (a.in_dtype == DType::BF16 && a.d == 128 && tuning().gsc_fast_path) return launch_gsc_fast(p, stream);
+    if (a.in_dtype == DType::BF16 && a.d == 128 && tuning().gsc_fast_path) {
+        p.chunks_per_item = max(1, min(kMaxChunksPerItem, tuning().gsc_chunks_per_task));
+        return launch_gsc_fast(p, stream);
+    }
 
     if (a.in_dtype == DType::BF16) {
         return a.d == 128 ? launch_typed<bf16_t, 128>(p, stream) : launch_typed<bf16_t, 64>(p, stream);
