@@ -35,12 +35,19 @@ __device__ __forceinline__ void load8(const float *p, float (&x)[8]) {
     const float4 b = *reinterpret_cast<const float4 *>(p + 4);
     x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
 }
+// two fp32 -> packed bf16 pair, round-to-nearest-even (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    typedef __bf16 bf16x2_v __attribute__((ext_vector_type(2)));
+    typedef float f32x2_v __attribute__((ext_vector_type(2)));
+    const f32x2_v f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_v));
+}
 __device__ __forceinline__ void store8(bf16_t *p, const float (&x)[8]) {
     uint4 v;
-    v.x = f32_to_bf16(x[0]) | (f32_to_bf16(x[1]) << 16);
-    v.y = f32_to_bf16(x[2]) | (f32_to_bf16(x[3]) << 16);
-    v.z = f32_to_bf16(x[4]) | (f32_to_bf16(x[5]) << 16);
-    v.w = f32_to_bf16(x[6]) | (f32_to_bf16(x[7]) << 16);
+    v.x = pack_bf16x2(x[0], x[1]);
+    v.y = pack_bf16x2(x[2], x[3]);
+    v.z = pack_bf16x2(x[4], x[5]);
+    v.w = pack_bf16x2(x[6], x[7]);
     *reinterpret_cast<uint4 *>(p) = v;
 }
 __device__ __forceinline__ void store8(float *p, const float (&x)[8]) {

@@ -136,16 +136,20 @@ __device__ __forceinline__ bool cosine_exceeds_f64_fast(const bf16_t *seed_row, 
 
 // One seed against the unassigned candidates `cmask` of the block in registers.  Returns the mask of
 // absorbed rows.  dotv / nsq are in row order.
-__device__ __forceinline__ uint64_t absorb(const RowRegs &x, const uint4 &piece, float s_nsq, float nsq, uint64_t cmask,
+__device__ __forceinline__ float safe_rinv(float nsq) {
+    // a norm that is zero, denormal, huge or not a number makes every cosine with that row "unsure"
+    return (nsq > 1e-30f && nsq < 1e30f) ? __frsqrt_rn(nsq) : __builtin_nanf("");
+}
+// s_rinv / rinv: reciprocal norms of the seed and of the rows (row order); NaN marks an unusable norm
+__device__ __forceinline__ uint64_t absorb(const RowRegs &x, const uint4 &piece, float s_rinv, float rinv, uint64_t cmask,
                                            int t_lo, int t_hi, float tau, const bf16_t *seed_row_ptr,
                                            const bf16_t *block_row0_ptr, int64_t stride_n, int c, int lane) {
     const float dotv = rows_dot(x, piece, t_lo, t_hi, c, lane);
-    const float sim = dotv * __frsqrt_rn(nsq) * __frsqrt_rn(s_nsq);
-    const bool odd = !(nsq > 1e-30f && nsq < 1e30f) || !(s_nsq > 1e-30f && s_nsq < 1e30f);
+    const float sim = dotv * rinv * s_rinv;
     const bool cand = (cmask >> lane) & 1ull;
     const bool sure_yes = sim > tau + kFastBand;
     const bool sure_no = sim < tau - kFastBand;
-    const bool unsure = odd || !(sure_yes || sure_no);
+    const bool unsure = !(sure_yes || sure_no);
     bool yes = cand && !unsure && sure_yes;
     uint64_t recheck = ballot64(cand && unsure);
     while (recheck != 0ull) {
@@ -228,7 +232,7 @@ __device__ __forceinline__ void store_tile(const floatx4_t (&D)[8], const floatx
     for (int i = 0; i < 4; ++i) {
         const int o = 16 * ot + 4 * g + i;
         if (o < n_out && dst_row0 + o < row_limit) {
-            const float inv = (Dn[i] > 1.5f) ? 1.0f / Dn[i] : 1.0f;
+            const float inv = __builtin_amdgcn_rcpf(Dn[i]);   // exact for powers of two, 1 ulp otherwise
             float v[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) v[j] = (Dn[i] > 1.5f) ? D[j][i] * inv : D[j][i];
@@ -266,17 +270,22 @@ __device__ __forceinline__ uint32_t or_rows(uint32_t x) {   // OR over the four 
     return r[0] | r[1];
 }
 
-__device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, float nsq, int R, float tau, int lane,
-                                               uint64_t &yes_row, uint64_t &unsure_row) {
+#ifdef SC_GSC_TIMING
+#define SC_ISTAMP(k) do { if (stamps && lane == 0) stamps[k] = wall_clock64(); } while (0)
+#else
+#define SC_ISTAMP(k) do {} while (0)
+#endif
+__device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, int R, float tau, int lane,
+                                               uint64_t &yes_row, uint64_t &unsure_row, unsigned long long *stamps = nullptr) {
+    (void)stamps;
+    SC_ISTAMP(10);
     const int g = lane >> 4, c = lane & 15;
     float *s_rinv = reinterpret_cast<float *>(lds + kWin * kLdsRowBytes);
 #pragma unroll
     for (int t = 0; t < 16; ++t)
         *reinterpret_cast<uint4 *>(lds + (4 * t + g) * kLdsRowBytes + 16 * c) = x.r[t];
-    // a norm that is zero, denormal, huge or not a number makes every cosine with that row "unsure"
-    const bool odd = !(nsq > 1e-30f && nsq < 1e30f);
-    s_rinv[lane] = odd ? __builtin_nanf("") : __frsqrt_rn(nsq);
     wave_lds_fence();
+    SC_ISTAMP(11);
 
     const int nt = (R + 15) >> 4;   // 16-row tiles in use
     floatx4_t acc[10];
@@ -299,6 +308,19 @@ __device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, floa
                 ++k;
             }
     }
+    SC_ISTAMP(12);
+    // squared norms are the diagonal of the Gram matrix: tile (I, I), row 4g+i == column c
+    {
+        const int kd[4] = {0, 4, 7, 9};
+#pragma unroll
+        for (int I = 0; I < 4; ++I) {
+            const int i = c - 4 * g;
+            const floatx4_t d = acc[kd[I]];
+            const float nsq = (i == 0) ? d[0] : ((i == 1) ? d[1] : ((i == 2) ? d[2] : d[3]));
+            if (i >= 0 && i < 4) s_rinv[16 * I + c] = safe_rinv(nsq);
+        }
+    }
+    wave_lds_fence();
     float rn[4];
     floatx4_t rm[4];
 #pragma unroll
@@ -332,6 +354,7 @@ __device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, floa
                 ++k;
             }
     }
+    SC_ISTAMP(13);
     // complete the words over the four lane groups, then every lane keeps the words of its own row
     uint32_t yl = 0, yh = 0, ul = 0, uh = 0;
 #pragma unroll
@@ -363,9 +386,9 @@ struct TaskOffsets {
 constexpr int kFastTaskThreads = kWave;
 
 // ------------------------------------------------------------------------------------------------
-template <typename TO, bool LONG>
+template <typename TO>
 __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_pass1_kernel(GscParams p) {
-    __shared__ __attribute__((aligned(16))) char s_lds[LONG ? 16 : kLdsWaveBytes];
+    __shared__ __attribute__((aligned(16))) char s_lds[kLdsWaveBytes];
     const int b = blockIdx.z, h = blockIdx.y;
     const int lane = threadIdx.x;
     const int wave = 0;
@@ -389,7 +412,7 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_pass1_kernel(GscParam
     TO *ktmp_c = reinterpret_cast<TO *>(p.ktmp) + bh * (int64_t)p.N_max * kFastD + 8 * c;
     const float tau = p.tau;
 #ifdef SC_GSC_TIMING
-    unsigned long long *dbg = reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(p.ktmp) + (size_t)p.B * p.Hkv * p.N_max * kFastD * 2) + (LONG ? (size_t)gridDim.x * gridDim.y * gridDim.z * 128 : 0);
+    unsigned long long *dbg = reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(p.ktmp) + (size_t)p.B * p.Hkv * p.N_max * kFastD * 2);
     int first_window = 1;
 #endif
     SC_GSTAMP(0);
@@ -416,10 +439,8 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_pass1_kernel(GscParam
                     idx_hi += 1;
                 }
                 const int nchw = idx_hi - idx;
-                if (LONG) { idx = idx_hi; continue; }   // windows belong to the other instantiation
                 RowRegs x;
                 load_rows(x, Kc_, p.stride_n, w0, R, g);
-                const int t_all = (R + 3) >> 2;
                 // chunk range [lo, hi) of every row; a delimiter is a one-row range of its own
                 int lo = lane, hi = lane + 1;
                 bool in_chunk = false;
@@ -428,9 +449,12 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_pass1_kernel(GscParam
                     const int ce = to.at(idx + j + 1) - 1 - w0;
                     if (lane >= cs && lane < ce) { lo = cs; hi = ce; in_chunk = true; }
                 }
-                const float nsq = rows_norm2(x, t_all, c, lane);
                 uint64_t yes_row, unsure_row;
-                gram_bitmatrix(s_lds, x, nsq, R, tau, lane, yes_row, unsure_row);
+#ifdef SC_GSC_TIMING
+                gram_bitmatrix(s_lds, x, R, tau, lane, yes_row, unsure_row, first_window ? dbg + ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 : nullptr);
+#else
+                gram_bitmatrix(s_lds, x, R, tau, lane, yes_row, unsure_row);
+#endif
 #ifdef SC_GSC_TIMING
                 if (first_window) { SC_GSTAMP(2); }
 #endif
@@ -494,7 +518,6 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_pass1_kernel(GscParam
                 idx = idx_hi;
             } else {
                 // ---------------- one chunk longer than a window: blocks of 64 rows, seeds carried along
-                if (!LONG) { idx += 1; continue; }
                 const int start = w0;
                 const int l = to.at(idx + 1) - 1 - start;
                 const bool closed = (start + l) < n;
@@ -507,20 +530,25 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_pass1_kernel(GscParam
                     const int t_all = (R + 3) >> 2;
                     RowRegs x;
                     load_rows(x, Kc_, p.stride_n, start + rb, R, g);
-                    const float nsq = rows_norm2(x, t_all, c, lane);
+                    // similarities inside the block (bit matrix) and the rows' reciprocal norms
+                    uint64_t yes_row, unsure_row;
+                    gram_bitmatrix(s_lds, x, R, tau, lane, yes_row, unsure_row);
+                    const float rinv = reinterpret_cast<const float *>(s_lds + kWin * kLdsRowBytes)[lane];
                     uint64_t todo = bits_range(0, R);
                     int my_o = -1;
                     const int seeds_before = nseeds;
                     const bf16_t *block0 = Kbh + (int64_t)(start + rb) * p.stride_n;
+                    // seeds of earlier blocks, in order: one dot product per row against the seed's key
                     for (int s = 0; s < seeds_before && todo != 0ull; ++s) {
                         const int srow = __hip_atomic_load(seed_bh + start + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         const bf16_t *sp = Kbh + (int64_t)(start + srow) * p.stride_n;
                         const uint4 piece = *reinterpret_cast<const uint4 *>(sp + 8 * c);
-                        const float s_nsq = row_allreduce_sum<16>(dot8(piece, piece));
-                        const uint64_t got = absorb(x, piece, s_nsq, nsq, todo, 0, t_all, tau, sp, block0, p.stride_n, c, lane);
+                        const float s_rinv = safe_rinv(row_allreduce_sum<16>(dot8(piece, piece)));
+                        const uint64_t got = absorb(x, piece, s_rinv, rinv, todo, 0, t_all, tau, sp, block0, p.stride_n, c, lane);
                         todo &= ~got;
                         if ((got >> lane) & 1ull) my_o = s;
                     }
+                    // seeds inside the block, from the bit matrix
                     while (todo != 0ull) {
                         const int i = __builtin_amdgcn_readfirstlane(first_bit(todo));
                         todo &= ~(1ull << i);
@@ -528,16 +556,19 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_pass1_kernel(GscParam
                         nseeds += 1;
                         if (lane == 0)
                             __hip_atomic_store(seed_bh + start + o, rb + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        uint64_t members = 1ull << i;
-                        if (todo != 0ull) {
-                            const uint4 piece = seed_piece(x, i, c);
-                            const float s_nsq = __shfl(nsq, i, kWave);
-                            const uint64_t got = absorb(x, piece, s_nsq, nsq, todo, 0, t_all, tau,
-                                                        block0 + (int64_t)i * p.stride_n, block0, p.stride_n, c, lane);
-                            todo &= ~got;
-                            members |= got;
+                        const bool cand = (todo >> lane) & 1ull;
+                        bool yes = cand && ((yes_row >> i) & 1ull);
+                        uint64_t recheck = ballot64(cand && ((unsure_row >> i) & 1ull));
+                        while (recheck != 0ull) {
+                            const int j = __builtin_amdgcn_readfirstlane(first_bit(recheck));
+                            recheck &= recheck - 1ull;
+                            const bool res = cosine_exceeds_f64_fast(block0 + (int64_t)i * p.stride_n,
+                                                                     block0 + (int64_t)j * p.stride_n, tau, lane);
+                            if (lane == j) yes = res;
                         }
-                        if ((members >> lane) & 1ull) my_o = o;
+                        const uint64_t got = ballot64(yes);
+                        todo &= ~got;
+                        if (lane == i || yes) my_o = o;
                     }
                     if (lane < R) cid32_bh[start + rb + lane] = my_o;   // cluster index; pass 2 reads this one
                     // running sums of the first 16 clusters
@@ -731,17 +762,16 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_pass2_kernel(GscParam
 
 // ------------------------------------------------------------------------------------------------
 hipError_t launch_gsc_fast(const GscParams &p, hipStream_t stream) {
+    // single-wave workgroups loop over the tasks of their (sequence, head); about 6000 of them keep the
+    // 2048 wave slots of the chip fed without spending time on dispatching workgroups that find no task
     const int max_tasks = (p.N_max + 1 + p.chunks_per_item - 1) / p.chunks_per_item;
-    const int gx = max(1, min(max_tasks, tuning().gsc_grid_x));
+    int gx = tuning().gsc_grid_x;
+    if (gx <= 0) gx = max(16, min(1024, 6144 / max(1, p.B * p.Hkv)));
+    gx = max(1, min(max_tasks, gx));
     const dim3 grid(gx, p.Hkv, p.B);
-    if (p.out_is_bf16) hipLaunchKernelGGL((gsc_pass1_kernel<bf16_t, false>), grid, dim3(kFastTaskThreads), 0, stream, p);
-    else hipLaunchKernelGGL((gsc_pass1_kernel<float, false>), grid, dim3(kFastTaskThreads), 0, stream, p);
+    if (p.out_is_bf16) hipLaunchKernelGGL((gsc_pass1_kernel<bf16_t>), grid, dim3(kFastTaskThreads), 0, stream, p);
+    else hipLaunchKernelGGL((gsc_pass1_kernel<float>), grid, dim3(kFastTaskThreads), 0, stream, p);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    // chunks longer than one window (same decomposition, the other code path)
-    if (p.out_is_bf16) hipLaunchKernelGGL((gsc_pass1_kernel<bf16_t, true>), grid, dim3(kFastTaskThreads), 0, stream, p);
-    else hipLaunchKernelGGL((gsc_pass1_kernel<float, true>), grid, dim3(kFastTaskThreads), 0, stream, p);
-    e = hipGetLastError();
     if (e != hipSuccess) return e;
     e = launch_gsc_scan(p, stream);
     if (e != hipSuccess) return e;

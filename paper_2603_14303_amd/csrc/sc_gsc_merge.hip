@@ -394,7 +394,7 @@ hipError_t launch_gsc_scan(const GscParams &p, hipStream_t stream) {
 template <typename T, int D>
 static hipError_t launch_typed(const GscParams &p, hipStream_t stream) {
     const int max_items = (p.N_max + 1 + p.chunks_per_item - 1) / p.chunks_per_item;
-    const int gx = max(1, min(max_items, tuning().gsc_grid_x));
+    const int gx = max(1, min(max_items, tuning().gsc_grid_x > 0 ? tuning().gsc_grid_x : 128));
     const dim3 grid(gx, p.Hkv, p.B);
     hipLaunchKernelGGL((gsc_assign_kernel<T, D>), grid, dim3(kGscThreads), 0, stream, p);
     hipError_t e = hipGetLastError();
