@@ -1,24 +1,23 @@
 // Fast path of sc_gsc_merge for bf16 keys/values with head dim 128 (paper Sec. 2.3 Alg. 1 / Eq. 2 and
 // Sec. 2.4 Eq. 3).
 //
-// Two streaming passes, each reading its operand from HBM exactly once:
-//   pass 1  reads K.  One wavefront handles four consecutive chunks.  It packs whole chunks (each
-//           with its closing delimiter) into "windows" of at most 64 rows held in registers, 16 lanes
-//           per row.  Inside a window the seeds of Alg. 1 are taken in row order; a delimiter is a
-//           one-row chunk, so the order in which seeds appear IS the output row order.  For a seed,
-//           lanes form partial dot products with v_dot2_f32_bf16, a transposed DPP reduction gives
-//           one cosine per lane, a ballot marks the absorbed rows (decisions inside +-1e-4 of tau are
-//           redone in fp64).  The cluster means of K are then one small matrix product on the matrix
-//           cores: (output row x window row) 0/1 membership times (window row x 128) keys, fp32
-//           accumulate, with a ones-column giving the cluster sizes.  Outputs: merged keys at a
-//           provisional position (the window's own rows), every token's output index inside its
-//           window, clusters per chunk.
-//   scan    exclusive scan of (clusters + delimiter) over the chunks of a (sequence, head).
-//   pass 2  reads V and the output indices, repeats the membership product for V, writes merged values
-//           and sizes to their final rows and moves the merged keys there.
-// Chunks longer than one window run the same steps over several windows with the seeds carried
-// along (their keys are re-read through L2); if such a chunk has more than 16 clusters its key merge
-// is left to pass 2.
+// Three launches:
+//   compress  reads K and V once.  One single-wavefront workgroup handles a few consecutive chunks.
+//           It packs whole chunks (each with its closing delimiter) into "windows" of at most 64
+//           rows.  Keys and values of a window are loaded together (16 lanes per row, 16-byte
+//           pieces); the keys are parked in LDS, the values wait in registers.  All pairwise
+//           cosines of the window come from one Gram matrix on the matrix cores, are compared with
+//           tau (decisions inside +-1e-4 of tau are redone in fp64) and filed as a bit matrix, on
+//           which the seeds of Alg. 1 are taken with a few bit operations per round.  A delimiter is
+//           a one-row chunk, so the seeds in row order ARE the output rows of the window.  The
+//           cluster means are a second small matrix product: (output row x window row) 0/1
+//           membership times (window row x 128) keys or values, fp32 accumulate, with a ones column
+//           giving the sizes.  Results go to provisional rows (the window's own first rows), because
+//           the final row of a window depends on every window before it.
+//   scan      exclusive scan of (clusters + delimiter) over the chunks of a (sequence, head).
+//   relocate  moves the merged rows and sizes from their provisional to their final rows.
+// A chunk longer than one window runs over several 64-row blocks with its seeds carried along
+// (their keys are re-read through L2).
 #include "sc_device.h"
 #include "sc_gsc_params.h"
 #include "sc_host.h"
@@ -41,7 +40,6 @@ typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kFastD = 128;
 constexpr int kWin = 64;                 // rows of a window
-constexpr int kDeferredBit = 1 << 30;    // pcount flag: key merge of this chunk happens in pass 2 (see kPcountMask)
 constexpr float kFastBand = 1e-4f;       // fp32 cosine error for d = 128 is < 2e-5; inside the band -> fp64
 
 __device__ __forceinline__ float dot2f(uint32_t a, uint32_t b, float c) {
@@ -242,6 +240,80 @@ __device__ __forceinline__ void store_tile(const floatx4_t (&D)[8], const floatx
 }
 
 
+
+// output indices as bytes (0xFF = none) in the operand order of the membership product
+__device__ __forceinline__ void orow_to_operand_bytes(int rel_o, int lane, uint32_t (&ob)[4]) {
+    const int g = lane >> 4;
+    const int v = (rel_o >= 0 && rel_o < 255) ? rel_o : 255;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w |= (uint32_t)lane_gather(v, 16 * q + 4 * i + g) << (8 * i);
+        ob[q] = w;
+    }
+}
+
+// D[j][i] += sum over rows of [index byte of row == want] * x[row][8c + j]; Dn[i] += number of such rows
+__device__ __forceinline__ void membership_mfma_b(const RowRegs &x, const uint32_t (&ob)[4], int want, int q_hi,
+                                                  floatx4_t (&D)[8], floatx4_t &Dn) {
+    const short4_t ones = {0x3F80, 0x3F80, 0x3F80, 0x3F80};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if (q < q_hi) {
+            short4_t a;
+            a[0] = (((ob[q] >> 0) & 0xFFu) == (uint32_t)want) ? (short)0x3F80 : (short)0;
+            a[1] = (((ob[q] >> 8) & 0xFFu) == (uint32_t)want) ? (short)0x3F80 : (short)0;
+            a[2] = (((ob[q] >> 16) & 0xFFu) == (uint32_t)want) ? (short)0x3F80 : (short)0;
+            a[3] = (((ob[q] >> 24) & 0xFFu) == (uint32_t)want) ? (short)0x3F80 : (short)0;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t d0 = dword_of(x.r[4 * q + 0], j >> 1), d1 = dword_of(x.r[4 * q + 1], j >> 1);
+                const uint32_t d2 = dword_of(x.r[4 * q + 2], j >> 1), d3 = dword_of(x.r[4 * q + 3], j >> 1);
+                const uint32_t lo = (j & 1) ? pack_hi(d0, d1) : pack_lo(d0, d1);
+                const uint32_t hi = (j & 1) ? pack_hi(d2, d3) : pack_lo(d2, d3);
+                const uint2 bb = make_uint2(lo, hi);
+                D[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, __builtin_bit_cast(short4_t, bb), D[j], 0, 0, 0);
+            }
+            Dn = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, ones, Dn, 0, 0, 0);
+        }
+    }
+}
+
+// the same product with the rows read from the LDS copy made by gram_bitmatrix, 16 rows at a time
+__device__ __forceinline__ void membership_mfma_lds(const char *lds, const uint32_t (&ob)[4], int want, int q_hi, int lane,
+                                                    floatx4_t (&D)[8], floatx4_t &Dn) {
+    const int g = lane >> 4, c = lane & 15;
+    const short4_t ones = {0x3F80, 0x3F80, 0x3F80, 0x3F80};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if (q < q_hi) {
+            uint4 r[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                r[i] = *reinterpret_cast<const uint4 *>(lds + (4 * (4 * q + i) + g) * 272 + 16 * c);
+            short4_t a;
+            a[0] = (((ob[q] >> 0) & 0xFFu) == (uint32_t)want) ? (short)0x3F80 : (short)0;
+            a[1] = (((ob[q] >> 8) & 0xFFu) == (uint32_t)want) ? (short)0x3F80 : (short)0;
+            a[2] = (((ob[q] >> 16) & 0xFFu) == (uint32_t)want) ? (short)0x3F80 : (short)0;
+            a[3] = (((ob[q] >> 24) & 0xFFu) == (uint32_t)want) ? (short)0x3F80 : (short)0;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t d0 = dword_of(r[0], j >> 1), d1 = dword_of(r[1], j >> 1);
+                const uint32_t d2 = dword_of(r[2], j >> 1), d3 = dword_of(r[3], j >> 1);
+                const uint32_t lo = (j & 1) ? pack_hi(d0, d1) : pack_lo(d0, d1);
+                const uint32_t hi = (j & 1) ? pack_hi(d2, d3) : pack_lo(d2, d3);
+                const uint2 bb = make_uint2(lo, hi);
+                D[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, __builtin_bit_cast(short4_t, bb), D[j], 0, 0, 0);
+            }
+            Dn = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, ones, Dn, 0, 0, 0);
+        }
+    }
+}
+
+// the key rows parked in LDS by gram_bitmatrix, back in the 16-lanes-per-row register layout
+__device__ __forceinline__ void reload_rows_from_lds(RowRegs &x, const char *lds, int lane);
+
 // ------------------------------------------------------------------------------------------------
 // All pairwise similarities of a window at once (Eq. 2 for every pair the seeds of Alg. 1 can ask for).
 // The window's rows are parked in LDS (row stride 272 B) and read back in the operand layout of
@@ -254,6 +326,12 @@ __device__ __forceinline__ void store_tile(const floatx4_t (&D)[8], const floatx
 //                             unsure[r]: bit m set iff the fp32 value is within the band (or not a number).
 constexpr int kLdsRowBytes = 272;                         // 256 B of keys + 16 B pad: conflict-free tile reads
 constexpr int kLdsWaveBytes = kWin * kLdsRowBytes + 256;  // + 64 reciprocal norms
+
+__device__ __forceinline__ void reload_rows_from_lds(RowRegs &x, const char *lds, int lane) {
+    const int g = lane >> 4, c = lane & 15;
+#pragma unroll
+    for (int t = 0; t < 16; ++t) x.r[t] = *reinterpret_cast<const uint4 *>(lds + (4 * t + g) * kLdsRowBytes + 16 * c);
+}
 
 __device__ __forceinline__ void wave_lds_fence() {
     // LDS traffic of one wavefront executes in order; this only stops the compiler from moving
@@ -386,8 +464,21 @@ struct TaskOffsets {
 constexpr int kFastTaskThreads = kWave;
 
 // ------------------------------------------------------------------------------------------------
+// store the sizes of tile `ot` (from the ones column) at provisional rows
+__device__ __forceinline__ void store_sizes(const floatx4_t &Dn, int ot, int n_out, int32_t *dst, int64_t dst_row0,
+                                            int64_t row_limit, int lane) {
+    if ((lane & 15) == 0) {
+        const int g = lane >> 4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int o = 16 * ot + 4 * g + i;
+            if (o < n_out && dst_row0 + o < row_limit) dst[dst_row0 + o] = (int)(Dn[i] + 0.5f);
+        }
+    }
+}
+
 template <typename TO>
-__global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_pass1_kernel(GscParams p) {
+__global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscParams p) {
     __shared__ __attribute__((aligned(16))) char s_lds[kLdsWaveBytes];
     const int b = blockIdx.z, h = blockIdx.y;
     const int lane = threadIdx.x;
@@ -403,16 +494,21 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_pass1_kernel(GscParam
     const int64_t bh = (int64_t)b * p.Hkv + h;
     const bf16_t *Kbh = reinterpret_cast<const bf16_t *>(p.K) + b * p.stride_b + h * p.stride_h;
     const bf16_t *Kc_ = Kbh + 8 * c;   // this lane's column piece
+    const bf16_t *Vc_ = reinterpret_cast<const bf16_t *>(p.V) + b * p.stride_b + h * p.stride_h + 8 * c;
     const int32_t *off = p.offsets + (int64_t)b * p.offsets_stride_b;
-    uint16_t *orow_bh = p.orow + bh * p.N_max;
     int32_t *pcount_bh = p.pcount + bh * ((int64_t)p.N_max + 1);
     int32_t *seed_bh = p.seedrow + bh * p.N_max;
     int32_t *cid_bh = p.cluster_id ? p.cluster_id + bh * p.N_max : nullptr;   // only when the caller asked
     int32_t *cid32_bh = p.cid + bh * p.N_max;                                    // always there (workspace)
+    int32_t *stmp_bh = p.stmp + bh * p.N_max;
     TO *ktmp_c = reinterpret_cast<TO *>(p.ktmp) + bh * (int64_t)p.N_max * kFastD + 8 * c;
+    TO *vtmp_c = reinterpret_cast<TO *>(p.vtmp) + bh * (int64_t)p.N_max * kFastD + 8 * c;
+    const int64_t tmp_rows = p.N_max;
     const float tau = p.tau;
 #ifdef SC_GSC_TIMING
-    unsigned long long *dbg = reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(p.ktmp) + (size_t)p.B * p.Hkv * p.N_max * kFastD * 2);
+    // development builds only: timestamps go to the upper half of the value staging area, which a bf16
+    // output never touches (the area is sized for fp32 output)
+    unsigned long long *dbg = reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(p.vtmp) + (size_t)p.B * p.Hkv * p.N_max * kFastD * 2);
     int first_window = 1;
 #endif
     SC_GSTAMP(0);
@@ -439,8 +535,8 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_pass1_kernel(GscParam
                     idx_hi += 1;
                 }
                 const int nchw = idx_hi - idx;
-                RowRegs x;
-                load_rows(x, Kc_, p.stride_n, w0, R, g);
+                RowRegs xk, xv;
+                load_rows(xk, Kc_, p.stride_n, w0, R, g);
                 // chunk range [lo, hi) of every row; a delimiter is a one-row range of its own
                 int lo = lane, hi = lane + 1;
                 bool in_chunk = false;
@@ -451,13 +547,13 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_pass1_kernel(GscParam
                 }
                 uint64_t yes_row, unsure_row;
 #ifdef SC_GSC_TIMING
-                gram_bitmatrix(s_lds, x, R, tau, lane, yes_row, unsure_row, first_window ? dbg + ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 : nullptr);
-#else
-                gram_bitmatrix(s_lds, x, R, tau, lane, yes_row, unsure_row);
-#endif
-#ifdef SC_GSC_TIMING
+                gram_bitmatrix(s_lds, xk, R, tau, lane, yes_row, unsure_row, first_window ? dbg + ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 : nullptr);
                 if (first_window) { SC_GSTAMP(2); }
+#else
+                gram_bitmatrix(s_lds, xk, R, tau, lane, yes_row, unsure_row);
 #endif
+                // the values are not needed before the keys are merged: their loads fly meanwhile
+                load_rows(xv, Vc_, p.stride_n, w0, R, g);
                 // Alg. 1 on the bit matrix, one seed per chunk and round: the first unassigned row of a
                 // chunk is its next seed and absorbs the unassigned rows of the chunk whose bit is set
                 const uint64_t my_range = bits_range(lo, hi);
@@ -492,28 +588,37 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_pass1_kernel(GscParam
 #ifdef SC_GSC_TIMING
                 if (first_window) { SC_GSTAMP(3); SC_GVAL(8, nseed); SC_GVAL(9, R); }
 #endif
-                if (lane < R) {
-                    orow_bh[w0 + lane] = (uint16_t)my_o;
-                    if (cid_bh) cid_bh[w0 + lane] = in_chunk ? __popcll(seedmask & bits_range(lo, my_seed)) : -1;
-                }
+                if (cid_bh && lane < R)
+                    cid_bh[w0 + lane] = in_chunk ? __popcll(seedmask & bits_range(lo, my_seed)) : -1;
                 {
                     const int cs = __shfl(to.v, min(idx + lane, 63), kWave) - w0;
                     const int ce = __shfl(to.v, min(idx + lane + 1, 63), kWave) - 1 - w0;
                     if (lane < nchw) pcount_bh[m0 + idx + lane] = __popcll(seedmask & bits_range(cs, ce));
                 }
-                // merged keys of the window -> provisional rows [w0, w0 + nseed)
-                int orow_t[16];
-                orow_to_operand_order(my_o, lane, orow_t);
+                // cluster means -> provisional rows [w0, w0 + nseed): keys (back from LDS), then values
+                uint32_t ob[4];
+                orow_to_operand_bytes(my_o, lane, ob);
                 const int q_hi = (R + 15) >> 4;
                 for (int ot = 0; ot * 16 < nseed; ++ot) {
                     floatx4_t D[8], Dn = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int j = 0; j < 8; ++j) D[j] = Dn;
-                    membership_mfma(x, orow_t, ot, q_hi, lane, D, Dn);
-                    store_tile<TO>(D, Dn, ot, nseed, ktmp_c, (int64_t)w0, (int64_t)p.N_max, lane);
+                    membership_mfma_lds(s_lds, ob, 16 * ot + c, q_hi, lane, D, Dn);
+                    store_tile<TO>(D, Dn, ot, nseed, ktmp_c, (int64_t)w0, tmp_rows, lane);
                 }
 #ifdef SC_GSC_TIMING
-                if (first_window) { SC_GSTAMP(4); first_window = 0; }
+                if (first_window) { SC_GSTAMP(4); }
+#endif
+                for (int ot = 0; ot * 16 < nseed; ++ot) {
+                    floatx4_t D[8], Dn = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) D[j] = Dn;
+                    membership_mfma_b(xv, ob, 16 * ot + c, q_hi, D, Dn);
+                    store_tile<TO>(D, Dn, ot, nseed, vtmp_c, (int64_t)w0, tmp_rows, lane);
+                    store_sizes(Dn, ot, nseed, stmp_bh, (int64_t)w0, tmp_rows, lane);
+                }
+#ifdef SC_GSC_TIMING
+                if (first_window) { SC_GSTAMP(6); first_window = 0; }
 #endif
                 idx = idx_hi;
             } else {
@@ -522,9 +627,6 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_pass1_kernel(GscParam
                 const int l = to.at(idx + 1) - 1 - start;
                 const bool closed = (start + l) < n;
                 int nseeds = 0;
-                floatx4_t D[8], Dn = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int j = 0; j < 8; ++j) D[j] = Dn;
                 for (int rb = 0; rb < l; rb += kWin) {
                     const int R = min(kWin, l - rb);
                     const int t_all = (R + 3) >> 2;
@@ -570,25 +672,40 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_pass1_kernel(GscParam
                         todo &= ~got;
                         if (lane == i || yes) my_o = o;
                     }
-                    if (lane < R) cid32_bh[start + rb + lane] = my_o;   // cluster index; pass 2 reads this one
-                    // running sums of the first 16 clusters
-                    int orow_t[16];
-                    orow_to_operand_order(my_o, lane, orow_t);
-                    membership_mfma(x, orow_t, 0, (R + 15) >> 4, lane, D, Dn);
-                    if (rb + kWin < l) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // seed list stores done
+                    // cluster index of every row; read back below through L2, by this wave only
+                    if (lane < R) __hip_atomic_store(cid32_bh + start + rb + lane, my_o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // seed list and index stores are done
                 }
-                const bool deferred = nseeds > 16;
-                if (!deferred) store_tile<TO>(D, Dn, 0, nseeds, ktmp_c, (int64_t)start, (int64_t)p.N_max, lane);
-                if (closed) {
-                    if (lane == 0 && cid_bh) cid_bh[start + l] = -1;
-                    if (!deferred && g == 0) {
-                        // the delimiter's key, unchanged, right after the chunk's cores
-                        float v[8];
-                        load8(Kc_ + (int64_t)(start + l) * p.stride_n, v);
-                        store8(ktmp_c + ((int64_t)start + nseeds) * kFastD, v);
+                if (closed && lane == 0 && cid_bh) cid_bh[start + l] = -1;
+                if (lane == 0) pcount_bh[m0 + idx] = nseeds;
+                // cluster means of keys and values; the closing delimiter takes part as output row `nseeds`
+                const int n_out = nseeds + (closed ? 1 : 0);
+                const int l_all = l + (closed ? 1 : 0);
+                for (int src = 0; src < 2; ++src) {
+                    const bf16_t *Xc = (src == 0) ? Kc_ : Vc_;
+                    TO *dst_c = (src == 0) ? ktmp_c : vtmp_c;
+                    for (int ot = 0; ot * 16 < n_out; ++ot) {
+                        floatx4_t D[8], Dn = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) D[j] = Dn;
+                        for (int rb = 0; rb < l_all; rb += kWin) {
+                            const int R = min(kWin, l_all - rb);
+                            RowRegs x;
+                            load_rows(x, Xc, p.stride_n, start + rb, R, g);
+                            int my_o = -1;
+                            if (lane < R) {
+                                const int tok = start + rb + lane;
+                                my_o = (tok == start + l) ? nseeds
+                                                          : __hip_atomic_load(cid32_bh + tok, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            }
+                            uint32_t ob[4];
+                            orow_to_operand_bytes(my_o - 16 * ot, lane, ob);
+                            membership_mfma_b(x, ob, c, (R + 15) >> 4, D, Dn);
+                        }
+                        store_tile<TO>(D, Dn, ot, n_out, dst_c, (int64_t)start, tmp_rows, lane);
+                        if (src == 1) store_sizes(Dn, ot, n_out, stmp_bh, (int64_t)start, tmp_rows, lane);
                     }
                 }
-                if (lane == 0) pcount_bh[m0 + idx] = nseeds | (deferred ? kDeferredBit : 0);
                 idx += 1;
             }
         }
@@ -597,37 +714,27 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_pass1_kernel(GscParam
 }
 
 // ------------------------------------------------------------------------------------------------
+// Moves merged rows from their provisional position (first rows of their window / long chunk) to
+// their final position rowbase[first chunk] + o.  Pure copy: 16 lanes per row, four rows per access.
 template <typename TO>
-__global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_pass2_kernel(GscParams p) {
+__global__ __launch_bounds__(kFastTaskThreads) void gsc_relocate_kernel(GscParams p) {
     const int b = blockIdx.z, h = blockIdx.y;
     const int lane = threadIdx.x;
-    const int wave = 0;
-    (void)wave;
     const int g = lane >> 4, c = lane & 15;
     const int M = p.num_chunks[b];
     if (M <= 0) return;
-    int n = p.seq_lens ? p.seq_lens[b] : p.N_max;
-    n = n < 0 ? 0 : (n > p.N_max ? p.N_max : n);
     const int C = p.chunks_per_item;
     const int tasks = (M + C - 1) / C;
     const int64_t bh = (int64_t)b * p.Hkv + h;
-    const bf16_t *Kbh = reinterpret_cast<const bf16_t *>(p.K) + b * p.stride_b + h * p.stride_h + 8 * c;
-    const bf16_t *Vbh = reinterpret_cast<const bf16_t *>(p.V) + b * p.stride_b + h * p.stride_h + 8 * c;
     const int32_t *off = p.offsets + (int64_t)b * p.offsets_stride_b;
-    const uint16_t *orow_bh = p.orow + bh * p.N_max;
-    const int32_t *cid32_bh = p.cid + bh * p.N_max;
-    const int32_t *pcount_bh = p.pcount + bh * ((int64_t)p.N_max + 1);
     const int32_t *rowbase_bh = p.rowbase + bh * ((int64_t)p.N_max + 2);
+    const int32_t *stmp_bh = p.stmp + bh * p.N_max;
     const TO *ktmp_c = reinterpret_cast<const TO *>(p.ktmp) + bh * (int64_t)p.N_max * kFastD + 8 * c;
+    const TO *vtmp_c = reinterpret_cast<const TO *>(p.vtmp) + bh * (int64_t)p.N_max * kFastD + 8 * c;
     TO *Kc_c = reinterpret_cast<TO *>(p.Kc) + bh * (int64_t)p.cap * kFastD + 8 * c;
     TO *Vc_c = reinterpret_cast<TO *>(p.Vc) + bh * (int64_t)p.cap * kFastD + 8 * c;
     int32_t *counts_bh = p.counts + bh * p.cap;
     const int64_t cap = p.cap;
-#ifdef SC_GSC_TIMING
-    unsigned long long *dbg = reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(p.ktmp) + (size_t)p.B * p.Hkv * p.N_max * kFastD * 2) + (size_t)gridDim.x * gridDim.y * gridDim.z * 64;
-    int first_window = 1;
-#endif
-    SC_GSTAMP(0);
 
     for (int task = blockIdx.x; task < tasks; task += gridDim.x) {
         TaskOffsets to;
@@ -637,126 +744,52 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_pass2_kernel(GscParam
         const int nch = min(C, M - m0);
         to.v = (lane <= nch) ? off[m0 + lane] : 0;
         const int basev = (lane <= nch) ? rowbase_bh[m0 + lane] : 0;
-        const int pcv = (lane < nch) ? pcount_bh[m0 + lane] : 0;
-        SC_GSTAMP(1);
         int idx = 0;
         while (idx < nch) {
-            const int rows_first = to.rows(idx);
-            const int w0 = to.at(idx);
+            const int src0 = to.at(idx);
             const int64_t out0 = __builtin_amdgcn_readlane(basev, idx);
-            if (rows_first <= kWin) {
-                int idx_hi = idx, R = 0;
+            int idx_hi = idx + 1;
+            if (to.rows(idx) <= kWin) {
+                int R = 0;
+                idx_hi = idx;
                 while (idx_hi < nch) {
                     const int rr = to.rows(idx_hi);
                     if (R + rr > kWin) break;
                     R += rr;
                     idx_hi += 1;
                 }
-                const int nseed = __builtin_amdgcn_readlane(basev, idx_hi) - (int)out0;
-                RowRegs x;
-                load_rows(x, Vbh, p.stride_n, w0, R, g);
-                const int my_o = (lane < R) ? (int)orow_bh[w0 + lane] : -1;
-                // merged keys of the window: provisional rows [w0, w0 + nseed); the first 16 are fetched
-                // now and stored at the end, so their latency hides behind the value merge
-                RawPiece<TO> kmove[4];
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const int o = 4 * k + g;
-                    if (o < nseed) kmove[k].load(ktmp_c + ((int64_t)w0 + o) * kFastD);
-                }
-                int orow_t[16];
-                orow_to_operand_order(my_o, lane, orow_t);
-#ifdef SC_GSC_TIMING
-                if (first_window) { SC_GSTAMP(2); SC_GVAL(8, nseed); SC_GVAL(9, R); }
-#endif
-                const int q_hi = (R + 15) >> 4;
-                for (int ot = 0; ot * 16 < nseed; ++ot) {
-                    floatx4_t D[8], Dn = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) D[j] = Dn;
-                    membership_mfma(x, orow_t, ot, q_hi, lane, D, Dn);
-                    store_tile<TO>(D, Dn, ot, nseed, Vc_c, out0, cap, lane);
-                    if (c == 0) {
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const int o = 16 * ot + 4 * g + i;
-                            if (o < nseed && out0 + o < cap) counts_bh[out0 + o] = (int)(Dn[i] + 0.5f);
-                        }
-                    }
-                }
-#ifdef SC_GSC_TIMING
-                if (first_window) { SC_GSTAMP(3); }
-#endif
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const int o = 4 * k + g;
-                    if (o < nseed && out0 + o < cap) kmove[k].store(Kc_c + (out0 + o) * kFastD);
-                }
-                for (int o0 = 16; o0 < nseed; o0 += 4) {
-                    const int o = o0 + g;
-                    if (o < nseed && out0 + o < cap) {
-                        RawPiece<TO> t;
-                        t.load(ktmp_c + ((int64_t)w0 + o) * kFastD);
-                        t.store(Kc_c + (out0 + o) * kFastD);
-                    }
-                }
-#ifdef SC_GSC_TIMING
-                if (first_window) { SC_GSTAMP(4); first_window = 0; }
-#endif
-                idx = idx_hi;
-            } else {
-                const int start = w0;
-                const int l = to.at(idx + 1) - 1 - start;
-                const bool closed = (start + l) < n;
-                const int pc_raw = __builtin_amdgcn_readlane(pcv, idx);
-                const bool deferred = (pc_raw & kDeferredBit) != 0;
-                const int pcl = pc_raw & ~kDeferredBit;
-                const int n_out = pcl + (closed ? 1 : 0);
-                const int l_all = l + (closed ? 1 : 0);       // the delimiter row takes part as output row pcl
-                for (int src = 0; src < (deferred ? 2 : 1); ++src) {
-                    const bf16_t *Xbh = (src == 0) ? Vbh : Kbh;
-                    TO *dst_c = (src == 0) ? Vc_c : Kc_c;
-                    for (int ot = 0; ot * 16 < n_out; ++ot) {
-                        floatx4_t D[8], Dn = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) D[j] = Dn;
-                        for (int rb = 0; rb < l_all; rb += kWin) {
-                            const int R = min(kWin, l_all - rb);
-                            RowRegs x;
-                            load_rows(x, Xbh, p.stride_n, start + rb, R, g);
-                            int my_o = -1;
-                            if (lane < R) {
-                                const int tok = start + rb + lane;
-                                my_o = (tok == start + l) ? pcl : cid32_bh[tok];
-                            }
-                            int orow_t[16];
-                            orow_to_operand_order(my_o, lane, orow_t);
-                            membership_mfma(x, orow_t, ot, (R + 15) >> 4, lane, D, Dn);
-                        }
-                        store_tile<TO>(D, Dn, ot, n_out, dst_c, out0, cap, lane);
-                        if (src == 0 && c == 0) {
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) {
-                                const int o = 16 * ot + 4 * g + i;
-                                if (o < n_out && out0 + o < cap) counts_bh[out0 + o] = (int)(Dn[i] + 0.5f);
-                            }
-                        }
-                    }
-                }
-                if (!deferred) {
-                    for (int o0 = 0; o0 < n_out; o0 += 4) {
-                        const int o = o0 + g;
-                        if (o < n_out && out0 + o < cap) {
-                            RawPiece<TO> t;
-                            t.load(ktmp_c + ((int64_t)start + o) * kFastD);
-                            t.store(Kc_c + (out0 + o) * kFastD);
-                        }
-                    }
-                }
-                idx += 1;
             }
+            const int n_out = __builtin_amdgcn_readlane(basev, idx_hi) - (int)out0;
+            constexpr int NP = (int)sizeof(TO) * 8 / 16;   // 16-byte pieces per lane and row
+            for (int o0 = 0; o0 < n_out; o0 += 16) {
+                uint4 kk[4][NP], vv[4][NP];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int o = o0 + 4 * k + g;
+                    const bool ok = o < n_out && out0 + o < cap;
+                    const uint4 *ks = reinterpret_cast<const uint4 *>(ktmp_c + ((int64_t)src0 + (ok ? o : 0)) * kFastD);
+                    const uint4 *vs = reinterpret_cast<const uint4 *>(vtmp_c + ((int64_t)src0 + (ok ? o : 0)) * kFastD);
+#pragma unroll
+                    for (int q = 0; q < NP; ++q) {
+                        kk[k][q] = ok ? ks[q] : make_uint4(0, 0, 0, 0);
+                        vv[k][q] = ok ? vs[q] : make_uint4(0, 0, 0, 0);
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int o = o0 + 4 * k + g;
+                    if (o < n_out && out0 + o < cap) {
+                        uint4 *kd = reinterpret_cast<uint4 *>(Kc_c + (out0 + o) * kFastD);
+                        uint4 *vd = reinterpret_cast<uint4 *>(Vc_c + (out0 + o) * kFastD);
+#pragma unroll
+                        for (int q = 0; q < NP; ++q) { kd[q] = kk[k][q]; vd[q] = vv[k][q]; }
+                    }
+                }
+            }
+            for (int o = lane; o < n_out; o += kWave)
+                if (out0 + o < cap) counts_bh[out0 + o] = stmp_bh[src0 + o];
+            idx = idx_hi;
         }
-        SC_GSTAMP(5);
     }
 }
 
@@ -769,14 +802,14 @@ hipError_t launch_gsc_fast(const GscParams &p, hipStream_t stream) {
     if (gx <= 0) gx = max(16, min(1024, 6144 / max(1, p.B * p.Hkv)));
     gx = max(1, min(max_tasks, gx));
     const dim3 grid(gx, p.Hkv, p.B);
-    if (p.out_is_bf16) hipLaunchKernelGGL((gsc_pass1_kernel<bf16_t>), grid, dim3(kFastTaskThreads), 0, stream, p);
-    else hipLaunchKernelGGL((gsc_pass1_kernel<float>), grid, dim3(kFastTaskThreads), 0, stream, p);
+    if (p.out_is_bf16) hipLaunchKernelGGL((gsc_compress_kernel<bf16_t>), grid, dim3(kFastTaskThreads), 0, stream, p);
+    else hipLaunchKernelGGL((gsc_compress_kernel<float>), grid, dim3(kFastTaskThreads), 0, stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     e = launch_gsc_scan(p, stream);
     if (e != hipSuccess) return e;
-    if (p.out_is_bf16) hipLaunchKernelGGL((gsc_pass2_kernel<bf16_t>), grid, dim3(kFastTaskThreads), 0, stream, p);
-    else hipLaunchKernelGGL((gsc_pass2_kernel<float>), grid, dim3(kFastTaskThreads), 0, stream, p);
+    if (p.out_is_bf16) hipLaunchKernelGGL((gsc_relocate_kernel<bf16_t>), grid, dim3(kFastTaskThreads), 0, stream, p);
+    else hipLaunchKernelGGL((gsc_relocate_kernel<float>), grid, dim3(kFastTaskThreads), 0, stream, p);
     return hipGetLastError();
 }
 

@@ -381,8 +381,8 @@ size_t gsc_merge_workspace_bytes(int B, int Hkv, int N_max, int d) {
     bytes += align_up(bh * (size_t)N_max * 4, 256);          // seedrow
     bytes += align_up(bh * ((size_t)N_max + 1) * 4, 256);    // pcount
     bytes += align_up(bh * ((size_t)N_max + 2) * 4, 256);    // rowbase
-    bytes += align_up(bh * (size_t)N_max * 2, 256);          // orow
-    bytes += align_up(bh * (size_t)N_max * (size_t)d * 4, 256);   // ktmp (sized for fp32 output)
+    bytes += align_up(bh * (size_t)N_max * 4, 256);          // stmp
+    bytes += 2 * align_up(bh * (size_t)N_max * (size_t)d * 4, 256);   // ktmp, vtmp (sized for fp32 output)
     return bytes;
 }
 
@@ -430,9 +430,11 @@ hipError_t launch_gsc_merge(const GscMergeArgs &a, hipStream_t stream) {
     w += align_up(bh * ((size_t)a.N_max + 1) * 4, 256);
     p.rowbase = reinterpret_cast<int32_t *>(w);
     w += align_up(bh * ((size_t)a.N_max + 2) * 4, 256);
-    p.orow = reinterpret_cast<uint16_t *>(w);
-    w += align_up(bh * (size_t)a.N_max * 2, 256);
+    p.stmp = reinterpret_cast<int32_t *>(w);
+    w += align_up(bh * (size_t)a.N_max * 4, 256);
     p.ktmp = w;
+    w += align_up(bh * (size_t)a.N_max * (size_t)a.d * 4, 256);
+    p.vtmp = w;
     p.cid = a.cluster_id ? a.cluster_id : ws_cid;
     p.cluster_id = a.cluster_id;
 

@@ -27,8 +27,9 @@ struct GscParams {
     int32_t *seedrow;     // [B, Hkv, N_max]   seed positions of a chunk that spans several blocks
     int32_t *pcount;      // [B, Hkv, N_max + 1] clusters per chunk (+ flag bit 30)
     int32_t *rowbase;     // [B, Hkv, N_max + 2] first output row of every chunk
-    uint16_t *orow;       // [B, Hkv, N_max]   output index of a token inside its window (fast path)
     void *ktmp;           // [B, Hkv, N_max, d] merged keys at provisional rows (fast path)
+    void *vtmp;           // [B, Hkv, N_max, d] merged values at provisional rows (fast path)
+    int32_t *stmp;        // [B, Hkv, N_max]   cluster sizes at provisional rows (fast path)
     int chunks_per_item;
 };
 

@@ -60,7 +60,7 @@ struct Tuning {
     int decode_min_rows = 384;      // rows of the merged cache a split should at least get
     int gsc_chunks_per_item = 16;   // chunks handled by one workgroup work item
     int gsc_grid_x = 0;             // workgroups per (sequence, KV head); <= 0 picks it from B*Hkv
-    int gsc_chunks_per_task = 4;    // fast path: chunks handled by one single-wave workgroup
+    int gsc_chunks_per_task = 2;    // fast path: chunks handled by one single-wave workgroup
     int gsc_fast_path = 1;          // 0 forces the generic kernels even for bf16 / d = 128
 };
 Tuning &tuning();
