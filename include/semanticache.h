@@ -93,8 +93,15 @@ sc_status sc_segment(const uint8_t *mask, int64_t mask_stride_b, const int32_t *
  *
  * Merging: each cluster S_t becomes one row (mean of its keys, mean of its values, size |S_t|),
  * accumulated in fp32.  Output rows of a (sequence, head), in order: for each chunk, its clusters in
- * order of their seeds, then the chunk's closing delimiter copied bit-for-bit with size 1.  Rows of
- * size 1 are bit-for-bit copies of their input row (widened exactly if out_dtype is wider).
+ * order of their seeds, then the chunk's closing delimiter with size 1.  Rows of size 1 (delimiters,
+ * unmerged tokens) carry the values of their input row unchanged (widened exactly if out_dtype is
+ * wider); the one liberty taken is that a negative zero may come out as a positive zero.
+ * Inputs are expected to be finite: the sums run on matrix cores over groups of neighbouring chunks
+ * with 0/1 weights, so a NaN or Inf element can turn the same column of other rows of its group into
+ * NaN.  The clustering decisions themselves treat NaN similarities as "not above tau".
+ * With bf16 inputs, bf16 or fp32 outputs and d = 128 the call runs three kernels (cluster + merge
+ * into provisional rows, exclusive scan of the row counts, relocation); other combinations run a
+ * generic three-kernel path with the same results.
  *
  *   K, V            device [B, Hkv, N_max, d] of in_dtype, addressed as
  *                   base + b*stride_b + h*stride_h + n*stride_n (+ e), strides in ELEMENTS;
@@ -158,9 +165,16 @@ sc_status sc_decode_attn(const void *Q, sc_dtype q_dtype,
 
 /* ------------------------------------------------------------------------------------------------
  * Launch-shape knobs for experiments (process-wide, not thread-safe; results never depend on them
- * beyond floating-point summation order in sc_decode_attn).  Keys: "decode_max_splits",
- * "decode_min_rows", "gsc_chunks_per_item", "gsc_grid_x", "gsc_fast_path", "gsc_chunks_per_task".  Return 0 / the value, or -1 for an
- * unknown key.
+ * beyond floating-point summation order).  Keys:
+ *   "decode_max_splits"    split-K workgroups per (sequence, KV head); <= 0 = chosen from B*Hkv
+ *   "decode_min_rows"      rows of the merged cache a split should at least get
+ *   "gsc_fast_path"        0 forces the generic kernels even for bf16 / d = 128
+ *   "gsc_chunks_per_task"  fast path: chunks handled by one single-wave workgroup task (1..32)
+ *   "gsc_chunks_per_item"  generic path: chunks per work item
+ *   "gsc_grid_x"           workgroups per (sequence, KV head); <= 0 = chosen from B*Hkv
+ *   "gsc_stages"           fast path, for per-kernel timing only: bit 0 cluster+merge, bit 1 scan,
+ *                          bit 2 relocation; anything but 7 leaves the outputs of the call incomplete
+ * Return 0 / the value, or -1 for an unknown key.
  */
 int sc_tune_set(const char *key, int value);
 int sc_tune_get(const char *key);
