@@ -17,14 +17,20 @@ NEAR_TAU = 1e-6
 
 
 def build_case(w: wl.Workload, tau: float, layer: int = 0, n_max: int | None = None,
-               batch: int | None = None, exclude_near: bool = True, heads: int | None = None):
+               batch: int | None = None, exclude_near: bool = True, heads: int | None = None,
+               sample=None, workers: int = 8):
     """Generate one layer of workload w (optionally truncated) and its oracle compression.
+
+    sample: None = the oracle runs on every (sequence, head); else a list of (b, h) pairs: all
+    inputs are still generated (the kernels run on the full shape) but the oracle, and the
+    re-draw of near-threshold chunks, only cover the listed pairs.
 
     Returns a dict with numpy arrays:
       mask u8 [B, N], seq_lens i32 [B], K, V f32 [B, Hkv, N, d] (bf16-exact for bf16 workloads),
       offsets (list of int32 arrays), num_chunks i32 [B],
-      ref: per (b, h) oracle result dicts (fp64), redraws (int), n_pairs (int)
+      ref: per sampled (b, h) oracle result dicts (fp64), redraws (int), n_pairs (int)
     """
+    from concurrent.futures import ThreadPoolExecutor
     B = batch if batch is not None else w.batch
     N = n_max if n_max is not None else w.n_max
     H = heads if heads is not None else w.kv_heads
@@ -37,36 +43,54 @@ def build_case(w: wl.Workload, tau: float, layer: int = 0, n_max: int | None = N
     mask = np.zeros((B, N), dtype=np.uint8)
     K = np.zeros((B, H, N, d), dtype=np.float32)
     V = np.zeros((B, H, N, d), dtype=np.float32)
-    offsets, ref = [], {}
-    redraws, pairs = 0, 0
+    offsets = []
     for b in range(B):
         n = int(lens[b])
         full = wl.delimiter_mask(w, b, n=min(n, w.n_max))
         mask[b, :n] = full[:n]
-        off = oracle.segment(mask[b], n)
-        offsets.append(off)
-        for h in range(H):
-            k, v = wl.keys_values(w, layer, b, h, mask[b], n)
-            r = oracle.compress_head(k, v, off, tau)
-            if exclude_near:
-                attempt = 0
-                while True:
-                    bad = np.nonzero(r["chunk_margin"] <= NEAR_TAU)[0]
-                    if bad.size == 0:
-                        break
-                    attempt += 1
-                    assert attempt < 50, "could not move similarities away from tau"
-                    for m in bad:
-                        s, e = int(off[m]), int(off[m + 1]) - 1
-                        k[s:e] = wl.redraw_chunk_keys(w, layer, b, h, int(m), attempt, e - s)
-                        redraws += 1
-                    r = oracle.compress_head(k, v, off, tau)
-            K[b, h, :n], V[b, h, :n] = k, v
-            ref[(b, h)] = r
-            pairs += r["n_pairs"]
+        offsets.append(oracle.segment(mask[b], n))
+    wanted = None if sample is None else set((int(b), int(h)) for b, h in sample)
+
+    def one(bh):
+        b, h = bh
+        n = int(lens[b])
+        off = offsets[b]
+        k, v = wl.keys_values(w, layer, b, h, mask[b], n)
+        K[b, h, :n], V[b, h, :n] = k, v
+        if wanted is not None and bh not in wanted:
+            return bh, None, 0
+        r = oracle.compress_head(k, v, off, tau)
+        redraws = 0
+        if exclude_near:
+            attempt = 0
+            while True:
+                bad = np.nonzero(r["chunk_margin"] <= NEAR_TAU)[0]
+                if bad.size == 0:
+                    break
+                attempt += 1
+                assert attempt < 50, "could not move similarities away from tau"
+                for m in bad:
+                    s, e = int(off[m]), int(off[m + 1]) - 1
+                    k[s:e] = wl.redraw_chunk_keys(w, layer, b, h, int(m), attempt, e - s)
+                    redraws += 1
+                r = oracle.compress_head(k, v, off, tau)
+            K[b, h, :n] = k
+        rows = r["n_rows"]
+        for key in ("Kc", "Vc", "counts"):          # keep the produced rows only (memory at full sizes)
+            r[key] = r[key][:rows].copy()
+        return bh, r, redraws
+
+    ref, redraws, pairs = {}, 0, 0
+    todo = [(b, h) for b in range(B) for h in range(H)]
+    with ThreadPoolExecutor(max(1, workers)) as pool:
+        for bh, r, nr in pool.map(one, todo):
+            if r is not None:
+                ref[bh] = r
+                pairs += r["n_pairs"]
+            redraws += nr
     return dict(workload=w, tau=float(tau), mask=mask, seq_lens=lens, K=K, V=V, offsets=offsets,
                 num_chunks=np.array([o.shape[0] - 1 for o in offsets], dtype=np.int32),
-                ref=ref, redraws=redraws, n_pairs=pairs)
+                ref=ref, redraws=redraws, n_pairs=pairs, layer=layer)
 
 
 def reference_attention(q, K, V, scale):
