@@ -65,22 +65,51 @@ __device__ __forceinline__ uint32_t dword_of(const uint4 &v, int j) {   // j com
     return j == 0 ? v.x : (j == 1 ? v.y : (j == 2 ? v.z : v.w));
 }
 
+// LDS layout of a wavefront
+constexpr int kLdsRowBytes = 272;                         // 256 B of keys + 16 B pad: conflict-free tile reads
+constexpr int kLdsRinvOff = kWin * kLdsRowBytes;          // 64 reciprocal norms
+constexpr int kLdsBitsOff = kLdsRinvOff + 256;            // per row: yes lo/hi, unsure lo/hi (16 B)
+constexpr int kLdsIdxOff = kLdsBitsOff + kWin * 16;       // 64 output-index bytes
+constexpr int kLdsWaveBytes = kLdsIdxOff + 64;
+
+__device__ __forceinline__ void wave_lds_fence() {
+    // LDS traffic of one wavefront executes in order; this only stops the compiler from moving
+    // accesses of other lanes' data across the hand-over point
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
 // Rows of a window / block as loaded: lane (g = lane/16, c = lane%16) holds elements 8c..8c+7 of rows
 // 4t + g, t = 0..15 (one coalesced 16-byte load per t covers four whole rows).
 struct RowRegs {
     uint4 r[16];
 };
 
-__device__ __forceinline__ void load_rows(RowRegs &x, const bf16_t *base_c, int64_t stride_n, int first_row, int nrows,
-                                          int g) {
-    const int t_eff = (nrows + 3) >> 2;
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+// Rows [first_row, first_row + nrows) through a buffer descriptor that ends after the last wanted row:
+// the hardware returns zeros for every access beyond it, so no lane needs a predicate or a 64-bit
+// address.  row_stride_bytes * 64 must fit in 31 bits (checked by the launcher).
+struct RowSource {
+    __amdgpu_buffer_rsrc_t rsrc;
+    int voff;     // this lane's offset inside a group of four rows: g * stride + 16 * c
+    int step;     // four rows further: 4 * stride
+};
+__device__ __forceinline__ RowSource row_source(const bf16_t *base, int64_t stride_n, int first_row, int nrows, int g, int c) {
+    RowSource rs;
+    const int sb = (int)stride_n * 2;
+    rs.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(base + (int64_t)first_row * stride_n), (short)0,
+                                                nrows > 0 ? (nrows - 1) * sb + kFastD * 2 : 0, 0x00020000);
+    rs.voff = g * sb + 16 * c;
+    rs.step = 4 * sb;
+    return rs;
+}
+__device__ __forceinline__ void load_rows(RowRegs &x, const RowSource &rs) {
 #pragma unroll
     for (int t = 0; t < 16; ++t) {
-        const int row = 4 * t + g;
-        if (t < t_eff && row < nrows)
-            x.r[t] = *reinterpret_cast<const uint4 *>(base_c + (int64_t)(first_row + row) * stride_n);
-        else
-            x.r[t] = make_uint4(0, 0, 0, 0);
+        const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rs.rsrc, rs.voff + t * rs.step, 0, 0);
+        x.r[t] = make_uint4(v.x, v.y, v.z, v.w);
     }
 }
 
@@ -223,9 +252,10 @@ template <> struct RawPiece<float> {
 
 // scale the sums of tile `ot` by 1/size and store rows [16*ot, 16*ot+16) ∩ [0, n_out) at dst_row0 + o
 template <typename TO>
-__device__ __forceinline__ void store_tile(const floatx4_t (&D)[8], const floatx4_t &Dn, int ot, int n_out, TO *dst_c,
+__device__ __forceinline__ void store_tile(const floatx4_t (&D)[8], const floatx4_t &Dn, int ot, int n_out, TO *dst,
                                            int64_t dst_row0, int64_t row_limit, int lane) {
     const int g = lane >> 4;
+    TO *dst_c = dst + 8 * (lane & 15);   // dst is wave-uniform: only the column piece is per lane
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int o = 16 * ot + 4 * g + i;
@@ -241,7 +271,8 @@ __device__ __forceinline__ void store_tile(const floatx4_t (&D)[8], const floatx
 
 
 
-// output indices as bytes (0xFF = none) in the operand order of the membership product
+// output indices as bytes (0xFF = none) in the operand order of the membership product:
+// ob[q] byte i = index of row 16q + 4i + lane/16
 __device__ __forceinline__ void orow_to_operand_bytes(int rel_o, int lane, uint32_t (&ob)[4]) {
     const int g = lane >> 4;
     const int v = (rel_o >= 0 && rel_o < 255) ? rel_o : 255;
@@ -252,6 +283,17 @@ __device__ __forceinline__ void orow_to_operand_bytes(int rel_o, int lane, uint3
         for (int i = 0; i < 4; ++i) w |= (uint32_t)lane_gather(v, 16 * q + 4 * i + g) << (8 * i);
         ob[q] = w;
     }
+}
+// the same through 64 bytes of LDS: row r files its byte at (r % 4) * 16 + r / 4, so that the sixteen
+// bytes a lane group needs are one 16-byte read
+__device__ __forceinline__ void orow_to_operand_bytes_lds(char *lds_idx, int rel_o, int lane, uint32_t (&ob)[4]) {
+    const int g = lane >> 4;
+    const int v = (rel_o >= 0 && rel_o < 255) ? rel_o : 255;
+    reinterpret_cast<unsigned char *>(lds_idx)[(lane & 3) * 16 + (lane >> 2)] = (unsigned char)v;
+    wave_lds_fence();
+    const uint4 w = *reinterpret_cast<const uint4 *>(lds_idx + 16 * g);
+    ob[0] = w.x; ob[1] = w.y; ob[2] = w.z; ob[3] = w.w;
+    wave_lds_fence();
 }
 
 // D[j][i] += sum over rows of [index byte of row == want] * x[row][8c + j]; Dn[i] += number of such rows
@@ -280,9 +322,10 @@ __device__ __forceinline__ void membership_mfma_b(const RowRegs &x, const uint32
     }
 }
 
-// the same product with the rows read from the LDS copy made by gram_bitmatrix, 16 rows at a time
-__device__ __forceinline__ void membership_mfma_lds(const char *lds, const uint32_t (&ob)[4], int want, int q_hi, int lane,
-                                                    floatx4_t (&D)[8], floatx4_t &Dn) {
+// keys and values of a window in one sweep: the keys come back from the LDS copy made by gram_bitmatrix
+// (16 rows at a time), the values are in registers; both share the 0/1 operand
+__device__ __forceinline__ void membership_mfma_kv(const char *lds, const RowRegs &xv, const uint32_t (&ob)[4], int want,
+                                                   int q_hi, int lane, floatx4_t (&DK)[8], floatx4_t (&DV)[8], floatx4_t &Dn) {
     const int g = lane >> 4, c = lane & 15;
     const short4_t ones = {0x3F80, 0x3F80, 0x3F80, 0x3F80};
 #pragma unroll
@@ -291,7 +334,7 @@ __device__ __forceinline__ void membership_mfma_lds(const char *lds, const uint3
             uint4 r[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                r[i] = *reinterpret_cast<const uint4 *>(lds + (4 * (4 * q + i) + g) * 272 + 16 * c);
+                r[i] = *reinterpret_cast<const uint4 *>(lds + (4 * (4 * q + i) + g) * kLdsRowBytes + 16 * c);
             short4_t a;
             a[0] = (((ob[q] >> 0) & 0xFFu) == (uint32_t)want) ? (short)0x3F80 : (short)0;
             a[1] = (((ob[q] >> 8) & 0xFFu) == (uint32_t)want) ? (short)0x3F80 : (short)0;
@@ -299,12 +342,22 @@ __device__ __forceinline__ void membership_mfma_lds(const char *lds, const uint3
             a[3] = (((ob[q] >> 24) & 0xFFu) == (uint32_t)want) ? (short)0x3F80 : (short)0;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const uint32_t d0 = dword_of(r[0], j >> 1), d1 = dword_of(r[1], j >> 1);
-                const uint32_t d2 = dword_of(r[2], j >> 1), d3 = dword_of(r[3], j >> 1);
-                const uint32_t lo = (j & 1) ? pack_hi(d0, d1) : pack_lo(d0, d1);
-                const uint32_t hi = (j & 1) ? pack_hi(d2, d3) : pack_lo(d2, d3);
-                const uint2 bb = make_uint2(lo, hi);
-                D[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, __builtin_bit_cast(short4_t, bb), D[j], 0, 0, 0);
+                {
+                    const uint32_t d0 = dword_of(r[0], j >> 1), d1 = dword_of(r[1], j >> 1);
+                    const uint32_t d2 = dword_of(r[2], j >> 1), d3 = dword_of(r[3], j >> 1);
+                    const uint32_t lo = (j & 1) ? pack_hi(d0, d1) : pack_lo(d0, d1);
+                    const uint32_t hi = (j & 1) ? pack_hi(d2, d3) : pack_lo(d2, d3);
+                    const uint2 bb = make_uint2(lo, hi);
+                    DK[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, __builtin_bit_cast(short4_t, bb), DK[j], 0, 0, 0);
+                }
+                {
+                    const uint32_t d0 = dword_of(xv.r[4 * q + 0], j >> 1), d1 = dword_of(xv.r[4 * q + 1], j >> 1);
+                    const uint32_t d2 = dword_of(xv.r[4 * q + 2], j >> 1), d3 = dword_of(xv.r[4 * q + 3], j >> 1);
+                    const uint32_t lo = (j & 1) ? pack_hi(d0, d1) : pack_lo(d0, d1);
+                    const uint32_t hi = (j & 1) ? pack_hi(d2, d3) : pack_lo(d2, d3);
+                    const uint2 bb = make_uint2(lo, hi);
+                    DV[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, __builtin_bit_cast(short4_t, bb), DV[j], 0, 0, 0);
+                }
             }
             Dn = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, ones, Dn, 0, 0, 0);
         }
@@ -324,28 +377,10 @@ __device__ __forceinline__ void reload_rows_from_lds(RowRegs &x, const char *lds
 // outcome as bit m of a per-column word; an OR over the four lane groups completes the words, and lane
 // r (row order) ends up with  yes[r]: bit m set iff Sim(m, r) > tau + band   (m < r or same tile)
 //                             unsure[r]: bit m set iff the fp32 value is within the band (or not a number).
-constexpr int kLdsRowBytes = 272;                         // 256 B of keys + 16 B pad: conflict-free tile reads
-constexpr int kLdsWaveBytes = kWin * kLdsRowBytes + 256;  // + 64 reciprocal norms
-
 __device__ __forceinline__ void reload_rows_from_lds(RowRegs &x, const char *lds, int lane) {
     const int g = lane >> 4, c = lane & 15;
 #pragma unroll
     for (int t = 0; t < 16; ++t) x.r[t] = *reinterpret_cast<const uint4 *>(lds + (4 * t + g) * kLdsRowBytes + 16 * c);
-}
-
-__device__ __forceinline__ void wave_lds_fence() {
-    // LDS traffic of one wavefront executes in order; this only stops the compiler from moving
-    // accesses of other lanes' data across the hand-over point
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-}
-
-__device__ __forceinline__ uint32_t or_rows(uint32_t x) {   // OR over the four 16-lane rows, same lane position
-    auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
-    x = r[0] | r[1];
-    r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
-    return r[0] | r[1];
 }
 
 #ifdef SC_GSC_TIMING
@@ -353,15 +388,44 @@ __device__ __forceinline__ uint32_t or_rows(uint32_t x) {   // OR over the four 
 #else
 #define SC_ISTAMP(k) do {} while (0)
 #endif
+
+// Gram tiles (I, J), I <= J < NT, of the rows parked in LDS; tile k = index in the 4 x 4 upper triangle
+template <int NT>
+__device__ __forceinline__ void gram_tiles(const char *lds, int g, int c, floatx4_t (&acc)[10]) {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        short4_t a[NT];
+#pragma unroll
+        for (int I = 0; I < NT; ++I) {
+            const uint2 v = *reinterpret_cast<const uint2 *>(lds + (16 * I + c) * kLdsRowBytes + (16 * ks + 4 * g) * 2);
+            a[I] = __builtin_bit_cast(short4_t, v);
+        }
+#pragma unroll
+        for (int I = 0; I < NT; ++I)
+#pragma unroll
+            for (int J = I; J < NT; ++J) {
+                constexpr int base[4] = {0, 4, 7, 9};
+                const int k = base[I] + (J - I);
+                acc[k] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a[I], a[J], acc[k], 0, 0, 0);
+            }
+    }
+}
+
+// Outcome for lane r (row order):  yes_row: bit m set iff Sim(m, r) > tau + band (for m < r, and for the
+// m > r of r's own 16-row tile);  unsure_row: bit m set iff the fp32 value lies within the band or a
+// norm is unusable.  The common case (no pair of the window anywhere near tau) never builds the
+// unsure words: every lane tracks the smallest distance to tau it has seen instead.
 __device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, int R, float tau, int lane,
                                                uint64_t &yes_row, uint64_t &unsure_row, unsigned long long *stamps = nullptr) {
     (void)stamps;
     SC_ISTAMP(10);
     const int g = lane >> 4, c = lane & 15;
-    float *s_rinv = reinterpret_cast<float *>(lds + kWin * kLdsRowBytes);
+    float *s_rinv = reinterpret_cast<float *>(lds + kLdsRinvOff);
+    uint32_t *s_bits = reinterpret_cast<uint32_t *>(lds + kLdsBitsOff);
 #pragma unroll
     for (int t = 0; t < 16; ++t)
         *reinterpret_cast<uint4 *>(lds + (4 * t + g) * kLdsRowBytes + 16 * c) = x.r[t];
+    *reinterpret_cast<uint4 *>(s_bits + 4 * lane) = make_uint4(0u, 0u, 0u, 0u);
     wave_lds_fence();
     SC_ISTAMP(11);
 
@@ -369,23 +433,10 @@ __device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, int 
     floatx4_t acc[10];
 #pragma unroll
     for (int k = 0; k < 10; ++k) acc[k] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-        short4_t a[4];
-#pragma unroll
-        for (int I = 0; I < 4; ++I) {
-            const uint2 v = *reinterpret_cast<const uint2 *>(lds + (16 * I + c) * kLdsRowBytes + (16 * ks + 4 * g) * 2);
-            a[I] = __builtin_bit_cast(short4_t, v);
-        }
-        int k = 0;
-#pragma unroll
-        for (int I = 0; I < 4; ++I)
-#pragma unroll
-            for (int J = I; J < 4; ++J) {
-                if (J < nt) acc[k] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a[I], a[J], acc[k], 0, 0, 0);
-                ++k;
-            }
-    }
+    if (nt >= 4) gram_tiles<4>(lds, g, c, acc);
+    else if (nt == 3) gram_tiles<3>(lds, g, c, acc);
+    else if (nt == 2) gram_tiles<2>(lds, g, c, acc);
+    else gram_tiles<1>(lds, g, c, acc);
     SC_ISTAMP(12);
     // squared norms are the diagonal of the Gram matrix: tile (I, I), row 4g+i == column c
     {
@@ -399,50 +450,91 @@ __device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, int 
         }
     }
     wave_lds_fence();
-    float rn[4];
+    // sim(m, n) > t  <=>  dot * rinv_m > t * norm_n : one multiplication per pair
+    float tn[4], hn[4], ln[4], bn[4];
     floatx4_t rm[4];
+    bool bad = false;
 #pragma unroll
     for (int I = 0; I < 4; ++I) {
-        rn[I] = s_rinv[16 * I + c];
+        const float rn = s_rinv[16 * I + c];
+        const float norm = __builtin_amdgcn_rcpf(rn);
+        bad = bad || (16 * I + c < R && !(rn == rn));
+        tn[I] = tau * norm;
+        hn[I] = (tau + kFastBand) * norm;
+        ln[I] = (tau - kFastBand) * norm;
+        bn[I] = (kFastBand * 1.0001f) * norm;
         rm[I] = *reinterpret_cast<const floatx4_t *>(s_rinv + 16 * I + 4 * g);
     }
-    // per column tile J: bits m (0..63) as two dwords
-    uint32_t y[4][2], u[4][2];
+    // per column tile J: bits m (0..63) as two dwords; closest approach to tau relative to the column norm
+    uint32_t y[4][2];
+    float dmin[4];
 #pragma unroll
-    for (int J = 0; J < 4; ++J) { y[J][0] = y[J][1] = u[J][0] = u[J][1] = 0u; }
-    const float hi_t = tau + kFastBand, lo_t = tau - kFastBand;
-    const int sh = 4 * g;
+    for (int J = 0; J < 4; ++J) { y[J][0] = y[J][1] = 0u; dmin[J] = 3.0e38f; }
+    uint32_t bitc[2][4];   // this lane's bit for row 16*(I&1) + 4g + i of a 32-row half
+#pragma unroll
+    for (int hlf = 0; hlf < 2; ++hlf)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) bitc[hlf][i] = 1u << (16 * hlf + 4 * g + i);
     {
-        int k = 0;
+        constexpr int base[4] = {0, 4, 7, 9};
 #pragma unroll
         for (int I = 0; I < 4; ++I)
 #pragma unroll
             for (int J = I; J < 4; ++J) {
                 if (J < nt) {
+                    const int k = base[I] + (J - I);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const float sim = acc[k][i] * rm[I][i] * rn[J];
-                        const bool yy = sim > hi_t;
-                        const bool uu = !yy && !(sim < lo_t);
-                        const uint32_t bit = 1u << (16 * (I & 1) + i);
-                        y[J][I >> 1] |= (yy ? bit : 0u) << sh;
-                        u[J][I >> 1] |= (uu ? bit : 0u) << sh;
+                        const float t = acc[k][i] * rm[I][i];
+                        y[J][I >> 1] |= (t > hn[J]) ? bitc[I & 1][i] : 0u;
+                        dmin[J] = fminf(dmin[J], fabsf(t - tn[J]));
                     }
                 }
-                ++k;
             }
     }
     SC_ISTAMP(13);
-    // complete the words over the four lane groups, then every lane keeps the words of its own row
-    uint32_t yl = 0, yh = 0, ul = 0, uh = 0;
+    // complete the words over the four lane groups: OR into the row's words in LDS
 #pragma unroll
     for (int J = 0; J < 4; ++J) {
-        const uint32_t a0 = or_rows(y[J][0]), a1 = or_rows(y[J][1]);
-        const uint32_t b0 = or_rows(u[J][0]), b1 = or_rows(u[J][1]);
-        if (g == J) { yl = a0; yh = a1; ul = b0; uh = b1; }
+        if (J < nt) {
+            __hip_atomic_fetch_or(s_bits + 4 * (16 * J + c) + 0, y[J][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            __hip_atomic_fetch_or(s_bits + 4 * (16 * J + c) + 1, y[J][1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
     }
-    yes_row = ((uint64_t)yh << 32) | yl;
-    unsure_row = ((uint64_t)uh << 32) | ul;
+    // anything close to tau, or an unusable norm, anywhere in the window?  (rare)
+    bool close = bad;
+#pragma unroll
+    for (int J = 0; J < 4; ++J) close = close || (J < nt && !(dmin[J] > bn[J]));
+    if (ballot64(close) != 0ull) {
+        // the same products and bounds as above, so that "yes", "no" and "unsure" partition the pairs
+        constexpr int base[4] = {0, 4, 7, 9};
+#pragma unroll
+        for (int J = 0; J < 4; ++J) {
+            uint32_t u0 = 0u, u1 = 0u;
+#pragma unroll
+            for (int I = 0; I <= J; ++I) {
+                if (J < nt) {
+                    const int k = base[I] + (J - I);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float t = acc[k][i] * rm[I][i];
+                        const bool uu = !(t > hn[J]) && !(t < ln[J]);
+                        if (I < 2) u0 |= uu ? bitc[I & 1][i] : 0u; else u1 |= uu ? bitc[I & 1][i] : 0u;
+                    }
+                }
+            }
+            if (J < nt) {
+                __hip_atomic_fetch_or(s_bits + 4 * (16 * J + c) + 2, u0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_fetch_or(s_bits + 4 * (16 * J + c) + 3, u1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+        }
+    }
+    wave_lds_fence();
+    const uint4 w = *reinterpret_cast<const uint4 *>(s_bits + 4 * lane);
+    yes_row = ((uint64_t)w.y << 32) | w.x;
+    unsure_row = ((uint64_t)w.w << 32) | w.z;
+    // a pair that is unsure must not also count as a sure yes
+    yes_row &= ~unsure_row;
     wave_lds_fence();   // the LDS area is reused by the next window
 }
 
@@ -493,16 +585,15 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
     const int tasks = (M + C - 1) / C;
     const int64_t bh = (int64_t)b * p.Hkv + h;
     const bf16_t *Kbh = reinterpret_cast<const bf16_t *>(p.K) + b * p.stride_b + h * p.stride_h;
-    const bf16_t *Kc_ = Kbh + 8 * c;   // this lane's column piece
-    const bf16_t *Vc_ = reinterpret_cast<const bf16_t *>(p.V) + b * p.stride_b + h * p.stride_h + 8 * c;
+    const bf16_t *Vbh = reinterpret_cast<const bf16_t *>(p.V) + b * p.stride_b + h * p.stride_h;
     const int32_t *off = p.offsets + (int64_t)b * p.offsets_stride_b;
     int32_t *pcount_bh = p.pcount + bh * ((int64_t)p.N_max + 1);
     int32_t *seed_bh = p.seedrow + bh * p.N_max;
     int32_t *cid_bh = p.cluster_id ? p.cluster_id + bh * p.N_max : nullptr;   // only when the caller asked
     int32_t *cid32_bh = p.cid + bh * p.N_max;                                    // always there (workspace)
     int32_t *stmp_bh = p.stmp + bh * p.N_max;
-    TO *ktmp_c = reinterpret_cast<TO *>(p.ktmp) + bh * (int64_t)p.N_max * kFastD + 8 * c;
-    TO *vtmp_c = reinterpret_cast<TO *>(p.vtmp) + bh * (int64_t)p.N_max * kFastD + 8 * c;
+    TO *ktmp_c = reinterpret_cast<TO *>(p.ktmp) + bh * (int64_t)p.N_max * kFastD;
+    TO *vtmp_c = reinterpret_cast<TO *>(p.vtmp) + bh * (int64_t)p.N_max * kFastD;
     const int64_t tmp_rows = p.N_max;
     const float tau = p.tau;
 #ifdef SC_GSC_TIMING
@@ -536,7 +627,7 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                 }
                 const int nchw = idx_hi - idx;
                 RowRegs xk, xv;
-                load_rows(xk, Kc_, p.stride_n, w0, R, g);
+                load_rows(xk, row_source(Kbh, p.stride_n, w0, R, g, c));
                 // chunk range [lo, hi) of every row; a delimiter is a one-row range of its own
                 int lo = lane, hi = lane + 1;
                 bool in_chunk = false;
@@ -553,7 +644,7 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                 gram_bitmatrix(s_lds, xk, R, tau, lane, yes_row, unsure_row);
 #endif
                 // the values are not needed before the keys are merged: their loads fly meanwhile
-                load_rows(xv, Vc_, p.stride_n, w0, R, g);
+                load_rows(xv, row_source(Vbh, p.stride_n, w0, R, g, c));
                 // Alg. 1 on the bit matrix, one seed per chunk and round: the first unassigned row of a
                 // chunk is its next seed and absorbs the unassigned rows of the chunk whose bit is set
                 const uint64_t my_range = bits_range(lo, hi);
@@ -597,24 +688,15 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                 }
                 // cluster means -> provisional rows [w0, w0 + nseed): keys (back from LDS), then values
                 uint32_t ob[4];
-                orow_to_operand_bytes(my_o, lane, ob);
+                orow_to_operand_bytes_lds(s_lds + kLdsIdxOff, my_o, lane, ob);
                 const int q_hi = (R + 15) >> 4;
                 for (int ot = 0; ot * 16 < nseed; ++ot) {
-                    floatx4_t D[8], Dn = {0.f, 0.f, 0.f, 0.f};
+                    floatx4_t DK[8], DV[8], Dn = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) D[j] = Dn;
-                    membership_mfma_lds(s_lds, ob, 16 * ot + c, q_hi, lane, D, Dn);
-                    store_tile<TO>(D, Dn, ot, nseed, ktmp_c, (int64_t)w0, tmp_rows, lane);
-                }
-#ifdef SC_GSC_TIMING
-                if (first_window) { SC_GSTAMP(4); }
-#endif
-                for (int ot = 0; ot * 16 < nseed; ++ot) {
-                    floatx4_t D[8], Dn = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) D[j] = Dn;
-                    membership_mfma_b(xv, ob, 16 * ot + c, q_hi, D, Dn);
-                    store_tile<TO>(D, Dn, ot, nseed, vtmp_c, (int64_t)w0, tmp_rows, lane);
+                    for (int j = 0; j < 8; ++j) DK[j] = DV[j] = Dn;
+                    membership_mfma_kv(s_lds, xv, ob, 16 * ot + c, q_hi, lane, DK, DV, Dn);
+                    store_tile<TO>(DK, Dn, ot, nseed, ktmp_c, (int64_t)w0, tmp_rows, lane);
+                    store_tile<TO>(DV, Dn, ot, nseed, vtmp_c, (int64_t)w0, tmp_rows, lane);
                     store_sizes(Dn, ot, nseed, stmp_bh, (int64_t)w0, tmp_rows, lane);
                 }
 #ifdef SC_GSC_TIMING
@@ -631,7 +713,7 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                     const int R = min(kWin, l - rb);
                     const int t_all = (R + 3) >> 2;
                     RowRegs x;
-                    load_rows(x, Kc_, p.stride_n, start + rb, R, g);
+                    load_rows(x, row_source(Kbh, p.stride_n, start + rb, R, g, c));
                     // similarities inside the block (bit matrix) and the rows' reciprocal norms
                     uint64_t yes_row, unsure_row;
                     gram_bitmatrix(s_lds, x, R, tau, lane, yes_row, unsure_row);
@@ -682,7 +764,7 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                 const int n_out = nseeds + (closed ? 1 : 0);
                 const int l_all = l + (closed ? 1 : 0);
                 for (int src = 0; src < 2; ++src) {
-                    const bf16_t *Xc = (src == 0) ? Kc_ : Vc_;
+                    const bf16_t *Xbh = (src == 0) ? Kbh : Vbh;
                     TO *dst_c = (src == 0) ? ktmp_c : vtmp_c;
                     for (int ot = 0; ot * 16 < n_out; ++ot) {
                         floatx4_t D[8], Dn = {0.f, 0.f, 0.f, 0.f};
@@ -691,7 +773,7 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                         for (int rb = 0; rb < l_all; rb += kWin) {
                             const int R = min(kWin, l_all - rb);
                             RowRegs x;
-                            load_rows(x, Xc, p.stride_n, start + rb, R, g);
+                            load_rows(x, row_source(Xbh, p.stride_n, start + rb, R, g, c));
                             int my_o = -1;
                             if (lane < R) {
                                 const int tok = start + rb + lane;
