@@ -30,8 +30,8 @@ typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
 #ifdef SC_GSC_TIMING
 // development builds: per-wave timestamps into the unused upper half of the key staging area
-#define SC_GSTAMP(k) do { if (lane == 0) dbg[(((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 1 + wave) * 16 + (k)] = wall_clock64(); } while (0)
-#define SC_GVAL(k, v) do { if (lane == 0) dbg[(((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 1 + wave) * 16 + (k)] = (unsigned long long)(v); } while (0)
+#define SC_GSTAMP(k) do { if (threadIdx.x == 0) dbg[(((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 1 + wave) * 16 + (k)] = wall_clock64(); } while (0)
+#define SC_GVAL(k, v) do { if (threadIdx.x == 0) dbg[(((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 1 + wave) * 16 + (k)] = (unsigned long long)(v); } while (0)
 #else
 #define SC_GSTAMP(k) do {} while (0)
 #define SC_GVAL(k, v) do {} while (0)
@@ -70,7 +70,9 @@ constexpr int kLdsRowBytes = 272;                         // 256 B of keys + 16 
 constexpr int kLdsRinvOff = kWin * kLdsRowBytes;          // 64 reciprocal norms
 constexpr int kLdsBitsOff = kLdsRinvOff + 256;            // per row: yes lo/hi, unsure lo/hi (16 B)
 constexpr int kLdsIdxOff = kLdsBitsOff + kWin * 16;       // 64 output-index bytes
-constexpr int kLdsWaveBytes = kLdsIdxOff + 64;
+constexpr int kLdsCrossOff = kLdsIdxOff + 64;             // per row: carried seeds it resembles (16 yes + 16 unsure bits)
+constexpr int kLdsSeedRinvOff = kLdsCrossOff + kWin * 4;  // reciprocal norms of the first 16 seeds of a long chunk
+constexpr int kLdsWaveBytes = kLdsSeedRinvOff + 64;
 
 __device__ __forceinline__ void wave_lds_fence() {
     // LDS traffic of one wavefront executes in order; this only stops the compiler from moving
@@ -113,45 +115,12 @@ __device__ __forceinline__ void load_rows(RowRegs &x, const RowSource &rs) {
     }
 }
 
-// dot product of every row with a 16-lane-replicated piece vector; result in row order (lane r = row r)
-__device__ __forceinline__ float rows_dot(const RowRegs &x, const uint4 &piece, int t_lo, int t_hi, int c, int lane) {
-    float part[16];
-#pragma unroll
-    for (int t = 0; t < 16; ++t) part[t] = (t >= t_lo && t < t_hi) ? dot8(x.r[t], piece) : 0.f;
-    const float v = row_transpose_reduce<16>(part, c);   // lane (g, c) holds row 4c + g
-    return lane_gather(v, ((lane & 3) << 4) | (lane >> 2));
-}
-__device__ __forceinline__ float rows_norm2(const RowRegs &x, int t_hi, int c, int lane) {
-    float part[16];
-#pragma unroll
-    for (int t = 0; t < 16; ++t) part[t] = (t < t_hi) ? dot8(x.r[t], x.r[t]) : 0.f;
-    const float v = row_transpose_reduce<16>(part, c);
-    return lane_gather(v, ((lane & 3) << 4) | (lane >> 2));
-}
-
-// piece c of row i (wave-uniform i) broadcast to the four lane groups, taken from the registers
-__device__ __forceinline__ uint4 seed_piece(const RowRegs &x, int i, int c) {
-    const int src = ((i & 3) << 4) | c;
-    uint4 s = make_uint4(0, 0, 0, 0);
-#define SC_SEED_CASE(T)                                                                       \
-    case T:                                                                                   \
-        s.x = bperm_u32(x.r[T].x, src); s.y = bperm_u32(x.r[T].y, src);                       \
-        s.z = bperm_u32(x.r[T].z, src); s.w = bperm_u32(x.r[T].w, src);                       \
-        break;
-    switch (i >> 2) {
-        SC_SEED_CASE(0) SC_SEED_CASE(1) SC_SEED_CASE(2) SC_SEED_CASE(3) SC_SEED_CASE(4) SC_SEED_CASE(5)
-        SC_SEED_CASE(6) SC_SEED_CASE(7) SC_SEED_CASE(8) SC_SEED_CASE(9) SC_SEED_CASE(10) SC_SEED_CASE(11)
-        SC_SEED_CASE(12) SC_SEED_CASE(13) SC_SEED_CASE(14) SC_SEED_CASE(15)
-    }
-#undef SC_SEED_CASE
-    return s;
-}
-
 // fp64 re-evaluation of one (seed, candidate) pair by the whole wave: Eq. 2 in double precision
 __device__ __forceinline__ bool cosine_exceeds_f64_fast(const bf16_t *seed_row, const bf16_t *cand_row, float tau, int lane) {
     double dot = 0.0, ss = 0.0, cc = 0.0;
 #pragma unroll
-    for (int e = lane; e < kFastD; e += kWave) {
+    for (int k = 0; k < kFastD / kWave; ++k) {
+        const int e = (lane & (kWave - 1)) + k * kWave;
         const double s = load1_f64(seed_row + e), c = load1_f64(cand_row + e);
         dot += s * c; ss += s * s; cc += c * c;
     }
@@ -161,31 +130,9 @@ __device__ __forceinline__ bool cosine_exceeds_f64_fast(const bf16_t *seed_row, 
     return dot / (sqrt(ss) * sqrt(cc)) > (double)tau;   // NaN compares false
 }
 
-// One seed against the unassigned candidates `cmask` of the block in registers.  Returns the mask of
-// absorbed rows.  dotv / nsq are in row order.
 __device__ __forceinline__ float safe_rinv(float nsq) {
     // a norm that is zero, denormal, huge or not a number makes every cosine with that row "unsure"
     return (nsq > 1e-30f && nsq < 1e30f) ? __frsqrt_rn(nsq) : __builtin_nanf("");
-}
-// s_rinv / rinv: reciprocal norms of the seed and of the rows (row order); NaN marks an unusable norm
-__device__ __forceinline__ uint64_t absorb(const RowRegs &x, const uint4 &piece, float s_rinv, float rinv, uint64_t cmask,
-                                           int t_lo, int t_hi, float tau, const bf16_t *seed_row_ptr,
-                                           const bf16_t *block_row0_ptr, int64_t stride_n, int c, int lane) {
-    const float dotv = rows_dot(x, piece, t_lo, t_hi, c, lane);
-    const float sim = dotv * rinv * s_rinv;
-    const bool cand = (cmask >> lane) & 1ull;
-    const bool sure_yes = sim > tau + kFastBand;
-    const bool sure_no = sim < tau - kFastBand;
-    const bool unsure = !(sure_yes || sure_no);
-    bool yes = cand && !unsure && sure_yes;
-    uint64_t recheck = ballot64(cand && unsure);
-    while (recheck != 0ull) {
-        const int j = first_bit(recheck);
-        recheck &= recheck - 1ull;
-        const bool res = cosine_exceeds_f64_fast(seed_row_ptr, block_row0_ptr + (int64_t)j * stride_n, tau, lane);
-        if (lane == j) yes = res;
-    }
-    return ballot64(yes);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -364,9 +311,6 @@ __device__ __forceinline__ void membership_mfma_kv(const char *lds, const RowReg
     }
 }
 
-// the key rows parked in LDS by gram_bitmatrix, back in the 16-lanes-per-row register layout
-__device__ __forceinline__ void reload_rows_from_lds(RowRegs &x, const char *lds, int lane);
-
 // ------------------------------------------------------------------------------------------------
 // All pairwise similarities of a window at once (Eq. 2 for every pair the seeds of Alg. 1 can ask for).
 // The window's rows are parked in LDS (row stride 272 B) and read back in the operand layout of
@@ -377,12 +321,6 @@ __device__ __forceinline__ void reload_rows_from_lds(RowRegs &x, const char *lds
 // outcome as bit m of a per-column word; an OR over the four lane groups completes the words, and lane
 // r (row order) ends up with  yes[r]: bit m set iff Sim(m, r) > tau + band   (m < r or same tile)
 //                             unsure[r]: bit m set iff the fp32 value is within the band (or not a number).
-__device__ __forceinline__ void reload_rows_from_lds(RowRegs &x, const char *lds, int lane) {
-    const int g = lane >> 4, c = lane & 15;
-#pragma unroll
-    for (int t = 0; t < 16; ++t) x.r[t] = *reinterpret_cast<const uint4 *>(lds + (4 * t + g) * kLdsRowBytes + 16 * c);
-}
-
 #ifdef SC_GSC_TIMING
 #define SC_ISTAMP(k) do { if (stamps && lane == 0) stamps[k] = wall_clock64(); } while (0)
 #else
@@ -573,10 +511,9 @@ template <typename TO>
 __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscParams p) {
     __shared__ __attribute__((aligned(16))) char s_lds[kLdsWaveBytes];
     const int b = blockIdx.z, h = blockIdx.y;
-    const int lane = threadIdx.x;
+    const int lane_id = threadIdx.x;
     const int wave = 0;
     (void)wave;
-    const int g = lane >> 4, c = lane & 15;
     const int M = p.num_chunks[b];
     if (M <= 0) return;
     int n = p.seq_lens ? p.seq_lens[b] : p.N_max;
@@ -610,10 +547,16 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
         to.M = M;
         const int m0 = to.m0;
         const int nch = min(C, M - m0);
-        to.v = (lane <= nch) ? off[m0 + lane] : 0;
+        to.v = (lane_id <= nch) ? off[m0 + lane_id] : 0;
         SC_GSTAMP(1);
         int idx = 0;
         while (idx < nch) {
+            // Everything derived from the lane number is recomputed per window (and per block of a long
+            // chunk) instead of being carried in registers across the whole kernel: the optimiser cannot
+            // see through the empty asm statement.
+            int lane = lane_id;
+            asm volatile("" : "+v"(lane));
+            const int g = lane >> 4, c = lane & 15;
             const int rows_first = to.rows(idx);
             const int w0 = to.at(idx);
             if (rows_first <= kWin) {
@@ -704,42 +647,140 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
 #endif
                 idx = idx_hi;
             } else {
-                // ---------------- one chunk longer than a window: blocks of 64 rows, seeds carried along
+                // ---------------- one chunk longer than a window: one sweep over blocks of 64 rows.
+                // The first sixteen clusters live in registers across the blocks: their seeds' keys as the
+                // A operand of a (seed x row) Gram product, their key/value sums as MFMA accumulators.
+                // Clusters beyond the sixteenth (rare) take the slow way: seed by seed against the block,
+                // and a second pass over the chunk per sixteen further output rows.
                 const int start = w0;
                 const int l = to.at(idx + 1) - 1 - start;
                 const bool closed = (start + l) < n;
                 int nseeds = 0;
+                uint2 sa[8];
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) sa[ks] = make_uint2(0u, 0u);
+                floatx4_t DK[8], DV[8], Dn = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < 8; ++j) DK[j] = DV[j] = Dn;
+                float *s_rinv = reinterpret_cast<float *>(s_lds + kLdsRinvOff);
+                float *s_seed_rinv = reinterpret_cast<float *>(s_lds + kLdsSeedRinvOff);
+                uint32_t *s_cross = reinterpret_cast<uint32_t *>(s_lds + kLdsCrossOff);
                 for (int rb = 0; rb < l; rb += kWin) {
+                    int lane = lane_id;
+                    asm volatile("" : "+v"(lane));
+                    const int g = lane >> 4, c = lane & 15;
                     const int R = min(kWin, l - rb);
-                    const int t_all = (R + 3) >> 2;
-                    RowRegs x;
-                    load_rows(x, row_source(Kbh, p.stride_n, start + rb, R, g, c));
-                    // similarities inside the block (bit matrix) and the rows' reciprocal norms
+                    const int nt = (R + 15) >> 4;
+                    const bf16_t *block0 = Kbh + (int64_t)(start + rb) * p.stride_n;
                     uint64_t yes_row, unsure_row;
-                    gram_bitmatrix(s_lds, x, R, tau, lane, yes_row, unsure_row);
-                    const float rinv = reinterpret_cast<const float *>(s_lds + kWin * kLdsRowBytes)[lane];
+                    {
+                        RowRegs x;
+                        load_rows(x, row_source(Kbh, p.stride_n, start + rb, R, g, c));
+                        gram_bitmatrix(s_lds, x, R, tau, lane, yes_row, unsure_row);
+                    }
+                    RowRegs xv;
+                    load_rows(xv, row_source(Vbh, p.stride_n, start + rb, R, g, c));
                     uint64_t todo = bits_range(0, R);
                     int my_o = -1;
                     const int seeds_before = nseeds;
-                    const bf16_t *block0 = Kbh + (int64_t)(start + rb) * p.stride_n;
-                    // seeds of earlier blocks, in order: one dot product per row against the seed's key
-                    for (int s = 0; s < seeds_before && todo != 0ull; ++s) {
-                        const int srow = __hip_atomic_load(seed_bh + start + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        const bf16_t *sp = Kbh + (int64_t)(start + srow) * p.stride_n;
-                        const uint4 piece = *reinterpret_cast<const uint4 *>(sp + 8 * c);
-                        const float s_rinv = safe_rinv(row_allreduce_sum<16>(dot8(piece, piece)));
-                        const uint64_t got = absorb(x, piece, s_rinv, rinv, todo, 0, t_all, tau, sp, block0, p.stride_n, c, lane);
-                        todo &= ~got;
-                        if ((got >> lane) & 1ull) my_o = s;
+                    // carried seeds, sixteen at a time: their similarities with every row of the block are one
+                    // (seed x row) Gram product; the first group's keys sit in registers, further groups
+                    // (rare) are fetched again
+                    for (int sg = 0; sg * 16 < seeds_before && todo != 0ull; ++sg) {
+                        const int ns = min(16, seeds_before - 16 * sg);
+                        uint2 sb[8];
+                        floatx4_t rs;
+                        if (sg == 0) {
+#pragma unroll
+                            for (int ks = 0; ks < 8; ++ks) sb[ks] = sa[ks];
+                            rs = *reinterpret_cast<const floatx4_t *>(s_seed_rinv + 4 * g);
+                        } else {
+                            const int srow_c = (c < ns) ? __hip_atomic_load(seed_bh + start + 16 * sg + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+                            const bf16_t *sp = Kbh + (int64_t)(start + srow_c) * p.stride_n + 4 * g;
+#pragma unroll
+                            for (int ks = 0; ks < 8; ++ks)
+                                sb[ks] = (c < ns) ? *reinterpret_cast<const uint2 *>(sp + 16 * ks) : make_uint2(0u, 0u);
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const int sl = 16 * sg + 4 * g + i;
+                                rs[i] = (4 * g + i < ns) ? __int_as_float(__hip_atomic_load(stmp_bh + start + sl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) : 0.f;
+                            }
+                        }
+                        s_cross[lane] = 0u;
+                        wave_lds_fence();
+                        floatx4_t cx[4];
+#pragma unroll
+                        for (int J = 0; J < 4; ++J) cx[J] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int ks = 0; ks < 8; ++ks) {
+                            const short4_t a = __builtin_bit_cast(short4_t, sb[ks]);
+#pragma unroll
+                            for (int J = 0; J < 4; ++J) {
+                                if (J < nt) {
+                                    const uint2 v = *reinterpret_cast<const uint2 *>(s_lds + (16 * J + c) * kLdsRowBytes + (16 * ks + 4 * g) * 2);
+                                    cx[J] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, __builtin_bit_cast(short4_t, v), cx[J], 0, 0, 0);
+                                }
+                            }
+                        }
+#pragma unroll
+                        for (int J = 0; J < 4; ++J) {
+                            if (J < nt) {
+                                const float norm = __builtin_amdgcn_rcpf(s_rinv[16 * J + c]);
+                                const float hn = (tau + kFastBand) * norm, ln = (tau - kFastBand) * norm;
+                                uint32_t w = 0u;
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) {
+                                    const float t = cx[J][i] * rs[i];
+                                    const bool yy = t > hn;
+                                    const bool uu = !yy && !(t < ln);
+                                    w |= (yy ? 1u : 0u) << (4 * g + i);
+                                    w |= (uu ? 1u : 0u) << (16 + 4 * g + i);
+                                }
+                                __hip_atomic_fetch_or(s_cross + 16 * J + c, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                            }
+                        }
+                        wave_lds_fence();
+                        const uint32_t cw = s_cross[lane];
+                        const uint32_t valid = (1u << ns) - 1u;
+                        const bool open = (todo >> lane) & 1ull;
+                        uint32_t cyes = open ? (cw & valid) : 0u;
+                        uint32_t cuns = open ? ((cw >> 16) & valid) : 0u;
+                        // first fit over the seeds of the group; a pair inside the band is settled in fp64
+                        // when it is the first candidate of its row
+                        for (;;) {
+                            const uint32_t pend = cyes | cuns;
+                            const int f = (pend != 0u) ? (__ffs(pend) - 1) : -1;
+                            const uint64_t need = ballot64(f >= 0 && ((cuns >> (f & 31)) & 1u));
+                            if (need == 0ull) break;
+                            const int j = __builtin_amdgcn_readfirstlane(first_bit(need));
+                            const int fj = __builtin_amdgcn_readlane(f, j);
+                            const int srow = __hip_atomic_load(seed_bh + start + 16 * sg + fj, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            const bool res = cosine_exceeds_f64_fast(Kbh + (int64_t)(start + srow) * p.stride_n,
+                                                                     block0 + (int64_t)j * p.stride_n, tau, lane);
+                            if (lane == j) {
+                                cuns &= ~(1u << fj);
+                                if (res) cyes |= 1u << fj;
+                            }
+                        }
+                        if (cyes != 0u) my_o = 16 * sg + __ffs(cyes) - 1;
+                        todo &= ~ballot64(cyes != 0u);
                     }
                     // seeds inside the block, from the bit matrix
+                    int new_row = -1;   // lane (c, g): block row of the seed that takes register slot c in this block
                     while (todo != 0ull) {
                         const int i = __builtin_amdgcn_readfirstlane(first_bit(todo));
                         todo &= ~(1ull << i);
                         const int o = nseeds;
                         nseeds += 1;
-                        if (lane == 0)
+                        if (o < 16 && c == o) new_row = i;
+                        if (lane == 0) {
+                            // seed list of the chunk: row, and reciprocal norm (in the size staging area, which
+                            // gets its final contents only after the last block)
+                            const float ri = s_rinv[i];
+                            if (o < 16) s_seed_rinv[o] = ri;
                             __hip_atomic_store(seed_bh + start + o, rb + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            __hip_atomic_store(stmp_bh + start + o, __float_as_int(ri), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        }
                         const bool cand = (todo >> lane) & 1ull;
                         bool yes = cand && ((yes_row >> i) & 1ull);
                         uint64_t recheck = ballot64(cand && ((unsure_row >> i) & 1ull));
@@ -754,39 +795,66 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                         todo &= ~got;
                         if (lane == i || yes) my_o = o;
                     }
-                    // cluster index of every row; read back below through L2, by this wave only
+                    // new seeds move into their register slots (keys still parked in LDS)
+                    if (ballot64(new_row >= 0) != 0ull) {
+#pragma unroll
+                        for (int ks = 0; ks < 8; ++ks) {
+                            const uint2 v = *reinterpret_cast<const uint2 *>(s_lds + max(new_row, 0) * kLdsRowBytes + (16 * ks + 4 * g) * 2);
+                            if (new_row >= 0) sa[ks] = v;
+                        }
+                    }
+                    // cluster index of every row: the caller's output, and what the passes for clusters
+                    // beyond the sixteenth read back below (through L2, by this wave only)
                     if (lane < R) __hip_atomic_store(cid32_bh + start + rb + lane, my_o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // seed list and index stores are done
+                    // sums of the first sixteen clusters
+                    uint32_t ob[4];
+                    orow_to_operand_bytes_lds(s_lds + kLdsIdxOff, (lane < R) ? my_o : -1, lane, ob);
+                    membership_mfma_kv(s_lds, xv, ob, c, nt, lane, DK, DV, Dn);
+                    wave_lds_fence();   // the next block overwrites the parked keys and the seed tables are read above
                 }
                 if (closed && lane == 0 && cid_bh) cid_bh[start + l] = -1;
                 if (lane == 0) pcount_bh[m0 + idx] = nseeds;
-                // cluster means of keys and values; the closing delimiter takes part as output row `nseeds`
-                const int n_out = nseeds + (closed ? 1 : 0);
-                const int l_all = l + (closed ? 1 : 0);
-                for (int src = 0; src < 2; ++src) {
-                    const bf16_t *Xbh = (src == 0) ? Kbh : Vbh;
-                    TO *dst_c = (src == 0) ? ktmp_c : vtmp_c;
-                    for (int ot = 0; ot * 16 < n_out; ++ot) {
-                        floatx4_t D[8], Dn = {0.f, 0.f, 0.f, 0.f};
+                {
+                    const int n0 = min(nseeds, 16);
+                    store_tile<TO>(DK, Dn, 0, n0, ktmp_c, (int64_t)start, tmp_rows, lane);
+                    store_tile<TO>(DV, Dn, 0, n0, vtmp_c, (int64_t)start, tmp_rows, lane);
+                    store_sizes(Dn, 0, n0, stmp_bh, (int64_t)start, tmp_rows, lane);
+                }
+                if (nseeds > 16) {
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // cluster index stores are done
+                    for (int src = 0; src < 2; ++src) {
+                        const bf16_t *Xbh = (src == 0) ? Kbh : Vbh;
+                        TO *dst_c = (src == 0) ? ktmp_c : vtmp_c;
+                        for (int ot = 1; ot * 16 < nseeds; ++ot) {
+                            floatx4_t D[8], Dm = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) D[j] = Dn;
-                        for (int rb = 0; rb < l_all; rb += kWin) {
-                            const int R = min(kWin, l_all - rb);
-                            RowRegs x;
-                            load_rows(x, row_source(Xbh, p.stride_n, start + rb, R, g, c));
-                            int my_o = -1;
-                            if (lane < R) {
-                                const int tok = start + rb + lane;
-                                my_o = (tok == start + l) ? nseeds
-                                                          : __hip_atomic_load(cid32_bh + tok, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            for (int j = 0; j < 8; ++j) D[j] = Dm;
+                            for (int rb = 0; rb < l; rb += kWin) {
+                                const int R = min(kWin, l - rb);
+                                RowRegs x;
+                                load_rows(x, row_source(Xbh, p.stride_n, start + rb, R, g, c));
+                                int my_o = -1;
+                                if (lane < R)
+                                    my_o = __hip_atomic_load(cid32_bh + start + rb + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                uint32_t ob[4];
+                                orow_to_operand_bytes(my_o - 16 * ot, lane, ob);
+                                membership_mfma_b(x, ob, c, (R + 15) >> 4, D, Dm);
                             }
-                            uint32_t ob[4];
-                            orow_to_operand_bytes(my_o - 16 * ot, lane, ob);
-                            membership_mfma_b(x, ob, c, (R + 15) >> 4, D, Dn);
+                            store_tile<TO>(D, Dm, ot, nseeds, dst_c, (int64_t)start, tmp_rows, lane);
+                            if (src == 1) store_sizes(Dm, ot, nseeds, stmp_bh, (int64_t)start, tmp_rows, lane);
                         }
-                        store_tile<TO>(D, Dn, ot, n_out, dst_c, (int64_t)start, tmp_rows, lane);
-                        if (src == 1) store_sizes(Dn, ot, n_out, stmp_bh, (int64_t)start, tmp_rows, lane);
                     }
+                }
+                if (closed && start + nseeds < tmp_rows) {
+                    // the closing delimiter is output row `nseeds`: a copy with size 1
+                    if (g == 0) {
+                        float kv[8], vv[8];
+                        load8(Kbh + (int64_t)(start + l) * p.stride_n + 8 * c, kv);
+                        load8(Vbh + (int64_t)(start + l) * p.stride_n + 8 * c, vv);
+                        store8(ktmp_c + (int64_t)(start + nseeds) * kFastD + 8 * c, kv);
+                        store8(vtmp_c + (int64_t)(start + nseeds) * kFastD + 8 * c, vv);
+                    }
+                    if (lane == 0) stmp_bh[start + nseeds] = 1;
                 }
                 idx += 1;
             }
