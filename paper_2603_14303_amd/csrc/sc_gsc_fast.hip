@@ -56,6 +56,11 @@ __device__ __forceinline__ uint64_t bits_range(int lo, int hi) {   // bits [lo, 
     const uint64_t upto_lo = (lo >= 64) ? ~0ull : ((1ull << lo) - 1ull);
     return upto_hi & ~upto_lo;
 }
+__device__ __forceinline__ uint64_t bits_below(int x) {   // bits [0, x), 0 <= x <= 64, from 32-bit operations
+    const uint32_t l = (x >= 32) ? 0xFFFFFFFFu : ((1u << x) - 1u);
+    const uint32_t h = (x <= 32) ? 0u : ((x >= 64) ? 0xFFFFFFFFu : ((1u << (x - 32)) - 1u));
+    return ((uint64_t)h << 32) | l;
+}
 __device__ __forceinline__ uint32_t bperm_u32(uint32_t x, int src_lane) {
     return (uint32_t)__builtin_amdgcn_ds_bpermute(src_lane << 2, (int)x);
 }
@@ -321,6 +326,13 @@ __device__ __forceinline__ void membership_mfma_kv(const char *lds, const RowReg
 // outcome as bit m of a per-column word; an OR over the four lane groups completes the words, and lane
 // r (row order) ends up with  yes[r]: bit m set iff Sim(m, r) > tau + band   (m < r or same tile)
 //                             unsure[r]: bit m set iff the fp32 value is within the band (or not a number).
+__device__ __forceinline__ uint32_t or_rows(uint32_t x) {   // OR over the four 16-lane rows, same lane position
+    auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+    x = r[0] | r[1];
+    r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+    return r[0] | r[1];
+}
+
 #ifdef SC_GSC_TIMING
 #define SC_ISTAMP(k) do { if (stamps && lane == 0) stamps[k] = wall_clock64(); } while (0)
 #else
@@ -431,12 +443,14 @@ __device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, int 
             }
     }
     SC_ISTAMP(13);
-    // complete the words over the four lane groups: OR into the row's words in LDS
+    // complete the words over the four lane groups; lane r = 16J + c keeps the words of its own row
+    uint32_t yl = 0u, yh = 0u;
 #pragma unroll
     for (int J = 0; J < 4; ++J) {
         if (J < nt) {
-            __hip_atomic_fetch_or(s_bits + 4 * (16 * J + c) + 0, y[J][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            __hip_atomic_fetch_or(s_bits + 4 * (16 * J + c) + 1, y[J][1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            const uint32_t a0 = or_rows(y[J][0]);
+            const uint32_t a1 = (nt > 2) ? or_rows(y[J][1]) : 0u;   // rows 32.. exist only then
+            if (g == J) { yl = a0; yh = a1; }
         }
     }
     // anything close to tau, or an unusable norm, anywhere in the window?  (rare)
@@ -466,13 +480,14 @@ __device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, int 
                 __hip_atomic_fetch_or(s_bits + 4 * (16 * J + c) + 3, u1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
         }
+        wave_lds_fence();
+        const uint2 w = *reinterpret_cast<const uint2 *>(s_bits + 4 * lane + 2);
+        unsure_row = ((uint64_t)w.y << 32) | w.x;
+    } else {
+        unsure_row = 0ull;
     }
-    wave_lds_fence();
-    const uint4 w = *reinterpret_cast<const uint4 *>(s_bits + 4 * lane);
-    yes_row = ((uint64_t)w.y << 32) | w.x;
-    unsure_row = ((uint64_t)w.w << 32) | w.z;
     // a pair that is unsure must not also count as a sure yes
-    yes_row &= ~unsure_row;
+    yes_row = (((uint64_t)yh << 32) | yl) & ~unsure_row;
     wave_lds_fence();   // the LDS area is reused by the next window
 }
 
@@ -594,6 +609,24 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                 uint64_t todo = bits_range(0, R);
                 uint64_t seedmask = 0ull;
                 int my_seed = -1;
+                {
+                    // Shortcut: guess that a row is a seed iff no earlier row of its chunk resembles it.  If
+                    // every other row then resembles an earlier guessed seed (true whenever "resembles" is
+                    // transitive inside the chunks, the usual case), induction over the rows shows the guess
+                    // IS the outcome of Alg. 1: a guessed seed has no earlier similar row, hence no earlier
+                    // similar seed; any other row has an earlier similar seed and joins the first of them.
+                    const uint64_t earlier = bits_below(lane) & my_range;
+                    const bool row_ok = lane < R;
+                    const bool guess = row_ok && ((yes_row & earlier) == 0ull);
+                    const uint64_t S = ballot64(guess);
+                    const uint64_t mine = yes_row & earlier & S;
+                    const bool fine = !row_ok || (((unsure_row & earlier) == 0ull) && (guess || mine != 0ull));
+                    if (ballot64(fine) == ~0ull) {
+                        seedmask = S;
+                        my_seed = guess ? lane : (row_ok ? (__ffsll((unsigned long long)mine) - 1) : -1);
+                        todo = 0ull;
+                    }
+                }
                 while (todo != 0ull) {
                     const uint64_t mine = todo & my_range;
                     const int s = (mine != 0ull) ? (__ffsll((unsigned long long)mine) - 1) : 64;
