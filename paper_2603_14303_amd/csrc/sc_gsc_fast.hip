@@ -525,7 +525,9 @@ __device__ __forceinline__ void store_sizes(const floatx4_t &Dn, int ot, int n_o
 template <typename TO>
 __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscParams p) {
     __shared__ __attribute__((aligned(16))) char s_lds[kLdsWaveBytes];
-    const int b = blockIdx.z, h = blockIdx.y;
+    // blockIdx.z = pass * B + sequence: the workgroups of pass 0 are dispatched first and take the tasks
+    // that need more than one window, pass 1 takes the rest, so the long tasks never start last
+    const int b = blockIdx.z % p.B, h = blockIdx.y, pass = blockIdx.z / p.B;
     const int lane_id = threadIdx.x;
     const int wave = 0;
     (void)wave;
@@ -564,6 +566,10 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
         const int nch = min(C, M - m0);
         to.v = (lane_id <= nch) ? off[m0 + lane_id] : 0;
         SC_GSTAMP(1);
+        {
+            const int task_rows = to.at(nch) - to.at(0) - ((m0 + nch == M) ? 1 : 0);
+            if ((task_rows > kWin) != (pass == 0)) continue;
+        }
         int idx = 0;
         while (idx < nch) {
             // Everything derived from the lane number is recomputed per window (and per block of a long
@@ -985,13 +991,14 @@ hipError_t launch_gsc_fast(const GscParams &p, hipStream_t stream) {
     if (gx <= 0) gx = max(16, min(1024, 6144 / max(1, p.B * p.Hkv)));
     gx = max(1, min(max_tasks, gx));
     const dim3 grid(gx, p.Hkv, p.B);
+    const dim3 grid2(gx, p.Hkv, 2 * p.B);   // two passes over the tasks: long ones first
     // gsc_stages exists so that a benchmark can time each kernel of the call by itself on a workspace
     // that a complete call has filled before; anything but 7 leaves the outputs incomplete
     const int stages = tuning().gsc_stages;
     hipError_t e = hipSuccess;
     if (stages & 1) {
-        if (p.out_is_bf16) hipLaunchKernelGGL((gsc_compress_kernel<bf16_t>), grid, dim3(kFastTaskThreads), 0, stream, p);
-        else hipLaunchKernelGGL((gsc_compress_kernel<float>), grid, dim3(kFastTaskThreads), 0, stream, p);
+        if (p.out_is_bf16) hipLaunchKernelGGL((gsc_compress_kernel<bf16_t>), grid2, dim3(kFastTaskThreads), 0, stream, p);
+        else hipLaunchKernelGGL((gsc_compress_kernel<float>), grid2, dim3(kFastTaskThreads), 0, stream, p);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
