@@ -237,7 +237,10 @@ def main():
     # the kernels of the call one by one (the workspace still holds what the complete calls above left)
     stage_us = {}
     if sc.tune_get("gsc_fast_path") and w.dtype == "bf16" and d == 128:
-        for name, bit in (("gsc_compress_kernel", 1), ("gsc_scan_kernel", 2), ("gsc_relocate_kernel", 4)):
+        stages = [("gsc_compress_kernel", 1), ("gsc_relocate_kernel", 4)]
+        if N > 32768:
+            stages.insert(1, ("gsc_scan_kernel", 2))   # shorter sequences fold the scan into the relocation
+        for name, bit in stages:
             sc.tune_set("gsc_stages", bit)
             try:
                 g1 = capture(gsc_round)
@@ -273,7 +276,7 @@ def main():
         "d2d_copy_GBps": copy_gbps,
         # The call's algorithmic bytes over the duration of ALL kernels of the call (cluster + merge,
         # scan, relocation, back to back on one stream); the first of them dominates.
-        "roofline": {"kernel": "sc_gsc_merge = gsc_compress_kernel + gsc_scan_kernel + gsc_relocate_kernel",
+        "roofline": {"kernel": "sc_gsc_merge = " + " + ".join(stage_us) if stage_us else "sc_gsc_merge",
                      "bound": "hbm",
                      "achieved": gsc_bytes / (gsc_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": gsc_bytes / (gsc_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,

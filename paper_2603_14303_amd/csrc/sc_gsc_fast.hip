@@ -905,18 +905,25 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
 // ------------------------------------------------------------------------------------------------
 // Moves merged rows from their provisional position (first rows of their window / long chunk) to
 // their final position rowbase[first chunk] + o.  Pure copy: 16 lanes per row, four rows per access.
-template <typename TO>
+// INLINE_PREFIX: no scan kernel ran; every workgroup adds up the cluster counts of the chunks before
+// its task itself (a few KB from L2), and the workgroup of the last task files the total.  Worth it
+// while a sequence has a few thousand chunks: it saves a launch whose only job is that sum.
+template <typename TO, bool INLINE_PREFIX>
 __global__ __launch_bounds__(kFastTaskThreads) void gsc_relocate_kernel(GscParams p) {
     const int b = blockIdx.z, h = blockIdx.y;
     const int lane = threadIdx.x;
     const int g = lane >> 4, c = lane & 15;
     const int M = p.num_chunks[b];
-    if (M <= 0) return;
+    const int64_t bh = (int64_t)b * p.Hkv + h;
+    if (M <= 0) {
+        if (INLINE_PREFIX && blockIdx.x == 0 && lane == 0) p.comp_lens[bh] = -1;
+        return;
+    }
     const int C = p.chunks_per_item;
     const int tasks = (M + C - 1) / C;
-    const int64_t bh = (int64_t)b * p.Hkv + h;
     const int32_t *off = p.offsets + (int64_t)b * p.offsets_stride_b;
     const int32_t *rowbase_bh = p.rowbase + bh * ((int64_t)p.N_max + 2);
+    const int32_t *pcount_bh = p.pcount + bh * ((int64_t)p.N_max + 1);
     const int32_t *stmp_bh = p.stmp + bh * p.N_max;
     const TO *ktmp_c = reinterpret_cast<const TO *>(p.ktmp) + bh * (int64_t)p.N_max * kFastD + 8 * c;
     const TO *vtmp_c = reinterpret_cast<const TO *>(p.vtmp) + bh * (int64_t)p.N_max * kFastD + 8 * c;
@@ -924,6 +931,7 @@ __global__ __launch_bounds__(kFastTaskThreads) void gsc_relocate_kernel(GscParam
     TO *Vc_c = reinterpret_cast<TO *>(p.Vc) + bh * (int64_t)p.cap * kFastD + 8 * c;
     int32_t *counts_bh = p.counts + bh * p.cap;
     const int64_t cap = p.cap;
+    constexpr int NP = (int)sizeof(TO) * 8 / 16;   // 16-byte pieces per lane and row
 
     for (int task = blockIdx.x; task < tasks; task += gridDim.x) {
         TaskOffsets to;
@@ -932,7 +940,34 @@ __global__ __launch_bounds__(kFastTaskThreads) void gsc_relocate_kernel(GscParam
         const int m0 = to.m0;
         const int nch = min(C, M - m0);
         to.v = (lane <= nch) ? off[m0 + lane] : 0;
-        const int basev = (lane <= nch) ? rowbase_bh[m0 + lane] : 0;
+        int basev;
+        if (INLINE_PREFIX) {
+            // rows of the chunks before the task: every one of them is closed by a delimiter
+            int part0 = 0, part1 = 0, part2 = 0, part3 = 0;
+            int m = lane;
+            for (; m + 3 * kWave < m0; m += 4 * kWave) {
+                part0 += pcount_bh[m] & kPcountMask;
+                part1 += pcount_bh[m + kWave] & kPcountMask;
+                part2 += pcount_bh[m + 2 * kWave] & kPcountMask;
+                part3 += pcount_bh[m + 3 * kWave] & kPcountMask;
+            }
+            for (; m < m0; m += kWave) part0 += pcount_bh[m] & kPcountMask;
+            int before = (part0 + part1) + (part2 + part3);
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) before += __shfl_xor(before, d, kWave);
+            // lane j: first output row of chunk m0 + j (lane nch: one past the task)
+            int mine = (lane < nch) ? (pcount_bh[m0 + lane] & kPcountMask) + ((m0 + lane < M - 1) ? 1 : 0) : 0;
+            int incl = mine;
+#pragma unroll
+            for (int d = 1; d < kWave; d <<= 1) {
+                const int up = __shfl_up(incl, d, kWave);
+                if (lane >= d) incl += up;
+            }
+            basev = before + m0 + incl - mine;
+            if (m0 + nch == M && lane == nch) p.comp_lens[bh] = (basev <= p.cap) ? basev : -1;
+        } else {
+            basev = (lane <= nch) ? rowbase_bh[m0 + lane] : 0;
+        }
         int idx = 0;
         while (idx < nch) {
             const int src0 = to.at(idx);
@@ -949,7 +984,6 @@ __global__ __launch_bounds__(kFastTaskThreads) void gsc_relocate_kernel(GscParam
                 }
             }
             const int n_out = __builtin_amdgcn_readlane(basev, idx_hi) - (int)out0;
-            constexpr int NP = (int)sizeof(TO) * 8 / 16;   // 16-byte pieces per lane and row
             for (int o0 = 0; o0 < n_out; o0 += 16) {
                 uint4 kk[4][NP], vv[4][NP];
 #pragma unroll
@@ -1002,13 +1036,21 @@ hipError_t launch_gsc_fast(const GscParams &p, hipStream_t stream) {
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    if (stages & 2) {
+    // up to 32k tokens the relocation adds up the cluster counts before its task itself; longer sequences
+    // (more chunks to add up per workgroup) get the scan kernel
+    const bool inline_prefix = p.N_max <= 32768;
+    if ((stages & 2) && !inline_prefix) {
         e = launch_gsc_scan(p, stream);
         if (e != hipSuccess) return e;
     }
     if (stages & 4) {
-        if (p.out_is_bf16) hipLaunchKernelGGL((gsc_relocate_kernel<bf16_t>), grid, dim3(kFastTaskThreads), 0, stream, p);
-        else hipLaunchKernelGGL((gsc_relocate_kernel<float>), grid, dim3(kFastTaskThreads), 0, stream, p);
+        if (inline_prefix) {
+            if (p.out_is_bf16) hipLaunchKernelGGL((gsc_relocate_kernel<bf16_t, true>), grid, dim3(kFastTaskThreads), 0, stream, p);
+            else hipLaunchKernelGGL((gsc_relocate_kernel<float, true>), grid, dim3(kFastTaskThreads), 0, stream, p);
+        } else {
+            if (p.out_is_bf16) hipLaunchKernelGGL((gsc_relocate_kernel<bf16_t, false>), grid, dim3(kFastTaskThreads), 0, stream, p);
+            else hipLaunchKernelGGL((gsc_relocate_kernel<float, false>), grid, dim3(kFastTaskThreads), 0, stream, p);
+        }
         e = hipGetLastError();
     }
     return e;
