@@ -30,8 +30,9 @@ typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
 #ifdef SC_GSC_TIMING
 // development builds: per-wave timestamps into the unused upper half of the key staging area
-#define SC_GSTAMP(k) do { if (threadIdx.x == 0) dbg[(((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 1 + wave) * 16 + (k)] = wall_clock64(); } while (0)
-#define SC_GVAL(k, v) do { if (threadIdx.x == 0) dbg[(((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 1 + wave) * 16 + (k)] = (unsigned long long)(v); } while (0)
+// (every lane stores the same word: a lane-dependent branch here changes the control flow under study)
+#define SC_GSTAMP(k) do { dbg[(((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 1 + wave) * 16 + (k)] = wall_clock64(); } while (0)
+#define SC_GVAL(k, v) do { dbg[(((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 1 + wave) * 16 + (k)] = (unsigned long long)(v); } while (0)
 #else
 #define SC_GSTAMP(k) do {} while (0)
 #define SC_GVAL(k, v) do {} while (0)
@@ -334,7 +335,7 @@ __device__ __forceinline__ uint32_t or_rows(uint32_t x) {   // OR over the four 
 }
 
 #ifdef SC_GSC_TIMING
-#define SC_ISTAMP(k) do { if (stamps && lane == 0) stamps[k] = wall_clock64(); } while (0)
+#define SC_ISTAMP(k) do { if (stamps) stamps[k] = wall_clock64(); } while (0)
 #else
 #define SC_ISTAMP(k) do {} while (0)
 #endif
@@ -531,16 +532,21 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
     const int lane_id = threadIdx.x;
     const int wave = 0;
     (void)wave;
-    const int M = p.num_chunks[b];
-    if (M <= 0) return;
-    int n = p.seq_lens ? p.seq_lens[b] : p.N_max;
-    n = n < 0 ? 0 : (n > p.N_max ? p.N_max : n);
     const int C = p.chunks_per_item;
+    // The offsets of the workgroup's first task are requested together with the chunk count instead of
+    // after it (which offsets are meaningful is decided once the count is known; the index is clamped to
+    // the row, so the early request is always inside the array).  Most workgroups only look at one task,
+    // many only to find that it belongs to the other pass: for them this halves the time to the exit.
+    const int32_t *off = p.offsets + (int64_t)b * p.offsets_stride_b;
+    const int first_v = (lane_id <= C) ? off[min((int64_t)blockIdx.x * C + lane_id, p.offsets_stride_b - 1)] : 0;
+    const int M = __builtin_amdgcn_readfirstlane(p.num_chunks[b]);
+    if (M <= 0) return;
+    int n = p.seq_lens ? __builtin_amdgcn_readfirstlane(p.seq_lens[b]) : p.N_max;
+    n = n < 0 ? 0 : (n > p.N_max ? p.N_max : n);
     const int tasks = (M + C - 1) / C;
     const int64_t bh = (int64_t)b * p.Hkv + h;
     const bf16_t *Kbh = reinterpret_cast<const bf16_t *>(p.K) + b * p.stride_b + h * p.stride_h;
     const bf16_t *Vbh = reinterpret_cast<const bf16_t *>(p.V) + b * p.stride_b + h * p.stride_h;
-    const int32_t *off = p.offsets + (int64_t)b * p.offsets_stride_b;
     int32_t *pcount_bh = p.pcount + bh * ((int64_t)p.N_max + 1);
     int32_t *seed_bh = p.seedrow + bh * p.N_max;
     int32_t *cid_bh = p.cluster_id ? p.cluster_id + bh * p.N_max : nullptr;   // only when the caller asked
@@ -564,7 +570,8 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
         to.M = M;
         const int m0 = to.m0;
         const int nch = min(C, M - m0);
-        to.v = (lane_id <= nch) ? off[m0 + lane_id] : 0;
+        if (task == (int)blockIdx.x) to.v = (lane_id <= nch) ? first_v : 0;
+        else to.v = (lane_id <= nch) ? off[m0 + lane_id] : 0;
         SC_GSTAMP(1);
         {
             const int task_rows = to.at(nch) - to.at(0) - ((m0 + nch == M) ? 1 : 0);
