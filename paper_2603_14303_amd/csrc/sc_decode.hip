@@ -54,7 +54,7 @@ struct DecParams {
     void *O;
     int o_is_bf16;
     float *lse;
-    int32_t *tickets;     // [B*Hkv], zero between calls
+    int32_t *flags;       // [B*Hkv][kDecMaxSplits] "partial published" flags, zero between calls
     float *part;          // [B*Hkv][max_splits][G][D + 2]
     int max_splits, min_rows;
 #ifdef SC_DEC_TIMING
@@ -103,24 +103,58 @@ template <int N, int I = 0> struct BcastAll {
 // ------------------------------------------------------------------------------------------------
 // Hand-over of split partials between workgroups that may sit on different XCDs (each XCD has its own
 // L2).  Partials are written with device-coherent (write-through) stores, so publishing them needs
-// no L2 write-back: a workgroup waits for its own stores, takes a ticket with a relaxed device-scope
-// atomic, and only the workgroup holding the last ticket invalidates its caches before reading.
+// no L2 write-back: a workgroup waits for its own stores and then raises its flag with one more such
+// store.  The workgroup of the LAST split (S - 1) folds the partials: it polls the flags of the others
+// (one flag per lane, so a poll is one load), invalidates its caches and reads.  It is the last of its
+// (sequence, head) in dispatch order, so everything it waits for has been dispatched before it; the
+// wait is bounded all the same, and a wait that runs out files NaN instead of a result.
+// Flags instead of an arrival counter because device-wide atomics on one address are carried out one
+// after the other at about 100 ns each on this multi-die chip: 32 splits arriving together kept the
+// last one waiting for microseconds.
 __device__ __forceinline__ void coherent_store(float *p, float v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// returns 1 in every thread of the workgroup whose ticket is the last of the S splits
-__device__ __forceinline__ int elect_last_split(int32_t *ticket_ptr, int S, int tid, int *s_flag) {
+constexpr int kFlagPollBudget = 1 << 20;   // polls of about 0.3 us each before giving up
+// Returns 0 in the workgroups that are done after publishing, 1 in the folding workgroup once every
+// other split of the (sequence, head) is published, -1 there if the wait ran out.
+__device__ __forceinline__ int publish_or_collect(int32_t *flags_bh, int S, int split, int tid, int *s_flag) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // own partial stores have completed
     __syncthreads();
-    if (tid == 0) {
-        const int ticket = __hip_atomic_fetch_add(ticket_ptr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *s_flag = (ticket == S - 1);
-        if (ticket == S - 1) __hip_atomic_store(ticket_ptr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (split != S - 1) {
+        if (tid == 0) __hip_atomic_store(flags_bh + split, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return 0;
+    }
+    if (tid < kWave) {
+        int budget = kFlagPollBudget;
+        bool all = false;
+        while (!all && budget > 0) {
+            const int f0 = (tid < S - 1) ? __hip_atomic_load(flags_bh + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1;
+            const int f1 = (tid + kWave < S - 1) ? __hip_atomic_load(flags_bh + tid + kWave, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1;
+            all = __ballot(f0 != 0 && f1 != 0) == ~0ull;
+            budget = __builtin_amdgcn_readfirstlane(budget) - 1;
+            if (!all) __builtin_amdgcn_s_sleep(2);
+        }
+        // flags back to zero for the next call
+        if (tid < S - 1) __hip_atomic_store(flags_bh + tid, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid + kWave < S - 1) __hip_atomic_store(flags_bh + tid + kWave, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0) *s_flag = all ? 1 : -1;
     }
     __syncthreads();
-    const int last = *s_flag;
-    if (last) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // drop stale cached lines of the partial buffer
-    return last;
+    const int got = *s_flag;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // drop stale cached lines of the partial buffer
+    return got;
+}
+
+// a wait that ran out: the outputs of the (sequence, head) say so
+template <int G, int D>
+__device__ __forceinline__ void file_failure(const DecParams &p, int b, int h, int tid, int nthreads) {
+    const float bad = __builtin_nanf("");
+    for (int i = tid; i < G * D; i += nthreads) {
+        const int64_t ooff = ((int64_t)b * p.Hq + (int64_t)h * G + i / D) * D + i % D;
+        if (p.o_is_bf16) reinterpret_cast<uint16_t *>(p.O)[ooff] = (uint16_t)0x7FC0;
+        else reinterpret_cast<float *>(p.O)[ooff] = bad;
+        if (i % D == 0 && p.lse) p.lse[(int64_t)b * p.Hq + (int64_t)h * G + i / D] = bad;
+    }
 }
 
 constexpr int kPartPad = 4;   // floats after the D accumulators of a partial: m, l, 2 unused (keeps 16-byte rows)
@@ -412,10 +446,14 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
     }
 
     SC_STAMP(4);
-    // ---- the workgroup that arrives last combines all splits
-    s_last = elect_last_split(p.tickets + bh, S, tid, &s_last);
+    // ---- the workgroup of the last split folds all splits
+    const int got = publish_or_collect(p.flags + bh * kDecMaxSplits, S, split, tid, &s_last);
     SC_STAMP(5);
-    if (!s_last) return;
+    if (got == 0) return;
+    if (got < 0) {
+        file_failure<G, D>(p, b, h, tid, THREADS);
+        return;
+    }
     combine_splits<D, G, THREADS>(p, part_bh, S, b, h, tid, lane, wave, s_w, s_l2, s_ml, s_buf);
     SC_STAMP(6);
 }
@@ -575,9 +613,13 @@ __global__ __launch_bounds__(kDecThreads) void decode_generic_kernel(DecParams p
         if (e == 0) { coherent_store(dst + D, mw); coherent_store(dst + D + 1, l); }
     }
 
-    // ---- the workgroup that arrives last combines all splits
-    s_last = elect_last_split(p.tickets + bh, S, tid, &s_last);
-    if (!s_last) return;
+    // ---- the workgroup of the last split folds all splits
+    const int got = publish_or_collect(p.flags + bh * kDecMaxSplits, S, split, tid, &s_last);
+    if (got == 0) return;
+    if (got < 0) {
+        file_failure<G, D>(p, b, h, tid, kDecThreads);
+        return;
+    }
     combine_splits<D, G, kDecThreads>(p, part_bh, S, b, h, tid, lane, wave, s_w, s_l2, s_ml, s_red);
 }
 
@@ -586,7 +628,7 @@ __global__ void zero_words_kernel(int32_t *p, size_t n) {
     if (i < n) p[i] = 0;
 }
 
-size_t decode_workspace_state_bytes(int B, int Hkv) { return align_up((size_t)B * Hkv * 4, 256); }
+size_t decode_workspace_state_bytes(int B, int Hkv) { return align_up((size_t)B * Hkv * kDecMaxSplits * 4, 256); }
 
 static int clamp_splits() { return max(1, min(kDecMaxSplits, tuning().decode_max_splits)); }   // knob <= 0: automatic
 
@@ -641,7 +683,7 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream) {
     p.scale_log2 = a.scale * kLog2e;
     p.O = a.O; p.o_is_bf16 = a.o_dtype == DType::BF16;
     p.lse = a.lse;
-    p.tickets = reinterpret_cast<int32_t *>(a.ws);
+    p.flags = reinterpret_cast<int32_t *>(a.ws);
     p.part = reinterpret_cast<float *>(reinterpret_cast<char *>(a.ws) + decode_workspace_state_bytes(a.B, a.Hkv));
 #ifdef SC_DEC_TIMING
     p.dbg = reinterpret_cast<unsigned long long *>(a.lse);   // development builds borrow the lse pointer
