@@ -145,11 +145,15 @@ sc_status sc_gsc_merge(const void *K, const void *V, sc_dtype in_dtype,
  *   lse             device f32 [B, Hq] or NULL; natural-log-sum-exp of the biased logits
  *
  *   ws              workspace of sc_decode_attn_workspace_bytes; unlike the other workspaces it carries
- *                   state: its first bytes are split-K arrival counters that must be ZERO when a call
- *                   starts.  Zero them once with sc_decode_attn_init_workspace (or any memset) after
+ *                   state: it starts with one "partial published" flag per (sequence, KV head, split),
+ *                   which must be ZERO when a call starts.  Zero them once with
+ *                   sc_decode_attn_init_workspace (or a memset of the whole workspace) after
  *                   allocating; every call leaves them zero again, so the workspace can be reused
  *                   by stream-ordered calls without further care.  Two calls that overlap in time
- *                   need two workspaces.
+ *                   need two workspaces.  The workgroup that folds the splits of a (sequence, head)
+ *                   waits for those flags for a bounded time; should the wait ever run out (it
+ *                   cannot while workgroups start in grid order), that head group's O and lse are
+ *                   filled with NaN rather than with a wrong result.
  *
  * Host errors: NULL required pointer, sizes <= 0, Hq not a multiple of Hkv or Hq/Hkv > 8,
  * d not in {64,128}, bad dtype, workspace too small.
