@@ -112,7 +112,7 @@ sc_status sc_gsc_merge(const void *K, const void *V, sc_dtype in_dtype, int64_t 
     if (cap <= 0) return SC_ERR_CAPACITY;
     if (!dtype_ok(in_dtype) || !dtype_ok(out_dtype)) return SC_ERR_UNSUPPORTED;
     if (d != 64 && d != 128) return SC_ERR_UNSUPPORTED;
-    if (Hkv > 65535 || B > 32767) return SC_ERR_UNSUPPORTED;   // grid dimensions (the fast path uses 2 * B)
+    if (Hkv > 65535 || B > 65535 || (long long)B * Hkv > (1 << 24)) return SC_ERR_UNSUPPORTED;   // grid sizes
     const size_t es = elem_size(in_dtype);
     if (stride_n < d || stride_h < 0 || stride_b < 0) return SC_ERR_INVALID_ARG;
     if ((stride_n * es) % 16 || (stride_h * es) % 16 || (stride_b * es) % 16) return SC_ERR_INVALID_ARG;

@@ -526,9 +526,17 @@ __device__ __forceinline__ void store_sizes(const floatx4_t &Dn, int ot, int n_o
 template <typename TO>
 __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscParams p) {
     __shared__ __attribute__((aligned(16))) char s_lds[kLdsWaveBytes];
-    // blockIdx.z = pass * B + sequence: the workgroups of pass 0 are dispatched first and take the tasks
-    // that need more than one window, pass 1 takes the rest, so the long tasks never start last
-    const int b = blockIdx.z % p.B, h = blockIdx.y, pass = blockIdx.z / p.B;
+    // One-dimensional grid: workgroup id = (pass * grid_x + x) * (B * Hkv) + (sequence, head).  The
+    // workgroups of pass 0 are dispatched first and take the tasks that need more than one window, pass 1
+    // takes the rest, so the long tasks never start last.  Inside a pass the task index x varies slowest:
+    // the workgroups beyond a sequence's last task (the host cannot know how many chunks there are) then
+    // come in one burst at the end of the pass instead of between the heads.
+    const int n_bh_grid = p.B * p.Hkv;
+    const int per_pass = p.grid_x * n_bh_grid;
+    const int pass = (int)blockIdx.x / per_pass;
+    const int rem_id = (int)blockIdx.x - pass * per_pass;
+    const int wg_x = rem_id / n_bh_grid, bh_id = rem_id - wg_x * n_bh_grid;
+    const int b = bh_id / p.Hkv, h = bh_id - b * p.Hkv;
     const int lane_id = threadIdx.x;
     const int wave = 0;
     (void)wave;
@@ -538,7 +546,7 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
     // the row, so the early request is always inside the array).  Most workgroups only look at one task,
     // many only to find that it belongs to the other pass: for them this halves the time to the exit.
     const int32_t *off = p.offsets + (int64_t)b * p.offsets_stride_b;
-    const int first_v = (lane_id <= C) ? off[min((int64_t)blockIdx.x * C + lane_id, p.offsets_stride_b - 1)] : 0;
+    const int first_v = (lane_id <= C) ? off[min((int64_t)wg_x * C + lane_id, p.offsets_stride_b - 1)] : 0;
     const int M = __builtin_amdgcn_readfirstlane(p.num_chunks[b]);
     if (M <= 0) return;
     int n = p.seq_lens ? __builtin_amdgcn_readfirstlane(p.seq_lens[b]) : p.N_max;
@@ -564,13 +572,13 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
 #endif
     SC_GSTAMP(0);
 
-    for (int task = blockIdx.x; task < tasks; task += gridDim.x) {
+    for (int task = wg_x; task < tasks; task += p.grid_x) {
         TaskOffsets to;
         to.m0 = task * C;
         to.M = M;
         const int m0 = to.m0;
         const int nch = min(C, M - m0);
-        if (task == (int)blockIdx.x) to.v = (lane_id <= nch) ? first_v : 0;
+        if (task == wg_x) to.v = (lane_id <= nch) ? first_v : 0;
         else to.v = (lane_id <= nch) ? off[m0 + lane_id] : 0;
         SC_GSTAMP(1);
         {
@@ -917,13 +925,16 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
 // while a sequence has a few thousand chunks: it saves a launch whose only job is that sum.
 template <typename TO, bool INLINE_PREFIX>
 __global__ __launch_bounds__(kFastTaskThreads) void gsc_relocate_kernel(GscParams p) {
-    const int b = blockIdx.z, h = blockIdx.y;
+    // one-dimensional grid, task index slowest (see the compress kernel)
+    const int n_bh_grid = p.B * p.Hkv;
+    const int wg_x = (int)blockIdx.x / n_bh_grid, bh_id = (int)blockIdx.x - wg_x * n_bh_grid;
+    const int b = bh_id / p.Hkv, h = bh_id - b * p.Hkv;
     const int lane = threadIdx.x;
     const int g = lane >> 4, c = lane & 15;
     const int M = p.num_chunks[b];
     const int64_t bh = (int64_t)b * p.Hkv + h;
     if (M <= 0) {
-        if (INLINE_PREFIX && blockIdx.x == 0 && lane == 0) p.comp_lens[bh] = -1;
+        if (INLINE_PREFIX && wg_x == 0 && lane == 0) p.comp_lens[bh] = -1;
         return;
     }
     const int C = p.chunks_per_item;
@@ -940,7 +951,7 @@ __global__ __launch_bounds__(kFastTaskThreads) void gsc_relocate_kernel(GscParam
     const int64_t cap = p.cap;
     constexpr int NP = (int)sizeof(TO) * 8 / 16;   // 16-byte pieces per lane and row
 
-    for (int task = blockIdx.x; task < tasks; task += gridDim.x) {
+    for (int task = wg_x; task < tasks; task += p.grid_x) {
         TaskOffsets to;
         to.m0 = task * C;
         to.M = M;
@@ -1031,15 +1042,17 @@ hipError_t launch_gsc_fast(const GscParams &p, hipStream_t stream) {
     int gx = tuning().gsc_grid_x;
     if (gx <= 0) gx = max(16, min(1024, 6144 / max(1, p.B * p.Hkv)));
     gx = max(1, min(max_tasks, gx));
-    const dim3 grid(gx, p.Hkv, p.B);
-    const dim3 grid2(gx, p.Hkv, 2 * p.B);   // two passes over the tasks: long ones first
+    GscParams pc = p;
+    pc.grid_x = gx;
+    const dim3 grid2((unsigned)(2 * gx * p.Hkv * p.B));   // two passes over the tasks: long ones first
+    const dim3 grid1((unsigned)(gx * p.Hkv * p.B));
     // gsc_stages exists so that a benchmark can time each kernel of the call by itself on a workspace
     // that a complete call has filled before; anything but 7 leaves the outputs incomplete
     const int stages = tuning().gsc_stages;
     hipError_t e = hipSuccess;
     if (stages & 1) {
-        if (p.out_is_bf16) hipLaunchKernelGGL((gsc_compress_kernel<bf16_t>), grid2, dim3(kFastTaskThreads), 0, stream, p);
-        else hipLaunchKernelGGL((gsc_compress_kernel<float>), grid2, dim3(kFastTaskThreads), 0, stream, p);
+        if (p.out_is_bf16) hipLaunchKernelGGL((gsc_compress_kernel<bf16_t>), grid2, dim3(kFastTaskThreads), 0, stream, pc);
+        else hipLaunchKernelGGL((gsc_compress_kernel<float>), grid2, dim3(kFastTaskThreads), 0, stream, pc);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -1052,11 +1065,11 @@ hipError_t launch_gsc_fast(const GscParams &p, hipStream_t stream) {
     }
     if (stages & 4) {
         if (inline_prefix) {
-            if (p.out_is_bf16) hipLaunchKernelGGL((gsc_relocate_kernel<bf16_t, true>), grid, dim3(kFastTaskThreads), 0, stream, p);
-            else hipLaunchKernelGGL((gsc_relocate_kernel<float, true>), grid, dim3(kFastTaskThreads), 0, stream, p);
+            if (p.out_is_bf16) hipLaunchKernelGGL((gsc_relocate_kernel<bf16_t, true>), grid1, dim3(kFastTaskThreads), 0, stream, pc);
+            else hipLaunchKernelGGL((gsc_relocate_kernel<float, true>), grid1, dim3(kFastTaskThreads), 0, stream, pc);
         } else {
-            if (p.out_is_bf16) hipLaunchKernelGGL((gsc_relocate_kernel<bf16_t, false>), grid, dim3(kFastTaskThreads), 0, stream, p);
-            else hipLaunchKernelGGL((gsc_relocate_kernel<float, false>), grid, dim3(kFastTaskThreads), 0, stream, p);
+            if (p.out_is_bf16) hipLaunchKernelGGL((gsc_relocate_kernel<bf16_t, false>), grid1, dim3(kFastTaskThreads), 0, stream, pc);
+            else hipLaunchKernelGGL((gsc_relocate_kernel<float, false>), grid1, dim3(kFastTaskThreads), 0, stream, pc);
         }
         e = hipGetLastError();
     }

@@ -31,6 +31,7 @@ struct GscParams {
     void *vtmp;           // [B, Hkv, N_max, d] merged values at provisional rows (fast path)
     int32_t *stmp;        // [B, Hkv, N_max]   cluster sizes at provisional rows (fast path)
     int chunks_per_item;
+    int grid_x;           // fast path: workgroups per pass and (sequence, head) of the compress kernel
 };
 
 hipError_t launch_gsc_scan(const GscParams &p, hipStream_t stream);
