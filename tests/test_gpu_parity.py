@@ -177,3 +177,25 @@ def test_repeatable_bit_for_bit():
         torch.cuda.synchronize()
         # split partials are combined in a fixed order, so the result does not depend on arrival order
         assert torch.equal(O0, O1)
+
+
+@pytest.mark.parametrize("knobs", [
+    dict(gsc_chunks_per_task=1), dict(gsc_chunks_per_task=3, gsc_grid_x=16), dict(gsc_chunks_per_task=5),
+    dict(gsc_chunks_per_task=32, gsc_grid_x=4), dict(gsc_grid_x=7), dict(gsc_fast_path=0),
+    dict(gsc_fast_path=0, gsc_chunks_per_item=3, gsc_grid_x=5),
+])
+def test_launch_shape_knobs_do_not_change_results(knobs):
+    # other task sizes, grids narrower than the task count (workgroups then walk several tasks) and the
+    # generic kernels on the fast path's inputs: same integers, merged rows within the same bounds
+    w = wl.get_workload("long128k")
+    case = build_case(w, 0.7, n_max=5000 + 11, heads=2)
+    old = {k: sc.tune_get(k) for k in knobs}
+    try:
+        for k, v in knobs.items():
+            sc.tune_set(k, v)
+        out = g.check_compress(case)
+        errs = g.check_decode(case, out, range(2), q_heads=2 * w.group)
+    finally:
+        for k, v in old.items():
+            sc.tune_set(k, v)
+    print(knobs, "merge_err %.2e" % out["worst_merge_err"], "decode", errs)
