@@ -931,15 +931,17 @@ __global__ __launch_bounds__(kFastTaskThreads) void gsc_relocate_kernel(GscParam
     const int b = bh_id / p.Hkv, h = bh_id - b * p.Hkv;
     const int lane = threadIdx.x;
     const int g = lane >> 4, c = lane & 15;
-    const int M = p.num_chunks[b];
+    const int C = p.chunks_per_item;
+    const int32_t *off = p.offsets + (int64_t)b * p.offsets_stride_b;
+    // offsets of the first task requested together with the chunk count (index clamped to the row)
+    const int first_v = (lane <= C) ? off[min((int64_t)wg_x * C + lane, p.offsets_stride_b - 1)] : 0;
+    const int M = __builtin_amdgcn_readfirstlane(p.num_chunks[b]);
     const int64_t bh = (int64_t)b * p.Hkv + h;
     if (M <= 0) {
         if (INLINE_PREFIX && wg_x == 0 && lane == 0) p.comp_lens[bh] = -1;
         return;
     }
-    const int C = p.chunks_per_item;
     const int tasks = (M + C - 1) / C;
-    const int32_t *off = p.offsets + (int64_t)b * p.offsets_stride_b;
     const int32_t *rowbase_bh = p.rowbase + bh * ((int64_t)p.N_max + 2);
     const int32_t *pcount_bh = p.pcount + bh * ((int64_t)p.N_max + 1);
     const int32_t *stmp_bh = p.stmp + bh * p.N_max;
@@ -957,7 +959,8 @@ __global__ __launch_bounds__(kFastTaskThreads) void gsc_relocate_kernel(GscParam
         to.M = M;
         const int m0 = to.m0;
         const int nch = min(C, M - m0);
-        to.v = (lane <= nch) ? off[m0 + lane] : 0;
+        if (task == wg_x) to.v = (lane <= nch) ? first_v : 0;
+        else to.v = (lane <= nch) ? off[m0 + lane] : 0;
         int basev;
         if (INLINE_PREFIX) {
             // rows of the chunks before the task: every one of them is closed by a delimiter
