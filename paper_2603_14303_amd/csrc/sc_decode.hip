@@ -138,11 +138,15 @@ __device__ __forceinline__ int publish_or_collect(int32_t *flags_bh, int S, int 
         if (tid < S - 1) __hip_atomic_store(flags_bh + tid, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (tid + kWave < S - 1) __hip_atomic_store(flags_bh + tid + kWave, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (tid == 0) *s_flag = all ? 1 : -1;
+        // Drop stale cached lines of the partial buffer.  One wavefront does it for the workgroup: the
+        // caches concerned (the CU's vector cache, the XCD's L2) are shared by all of its wavefronts, the
+        // barrier below orders their loads behind it, and every further wavefront issuing the same
+        // invalidation costs a third of a microsecond in a queue per XCD (12 wavefronts x 4 folding
+        // workgroups per XCD used to add 20 us to a call with 32 (sequence, head) pairs).
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     }
     __syncthreads();
-    const int got = *s_flag;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // drop stale cached lines of the partial buffer
-    return got;
+    return *s_flag;
 }
 
 // a wait that ran out: the outputs of the (sequence, head) say so
@@ -196,6 +200,7 @@ __device__ __forceinline__ void combine_splits(const DecParams &p, const float *
         s_l2[i] = __builtin_nontemporal_load(src + 1);
     }
     __syncthreads();
+    SC_STAMP(7);
     for (int hh = wave; hh < G; hh += NWAVES) {
         float mx = -INFINITY;
         for (int s = lane; s < S; s += kWave) mx = fmaxf(mx, s_w[s * G + hh]);
@@ -213,6 +218,7 @@ __device__ __forceinline__ void combine_splits(const DecParams &p, const float *
         if (lane == 0) { s_ml[2 * hh] = mx; s_ml[2 * hh + 1] = lt; }
     }
     __syncthreads();
+    SC_STAMP(8);
     for (int h0 = 0; h0 < G; h0 += HB) {
         float4 acc[HB];
 #pragma unroll
@@ -237,6 +243,7 @@ __device__ __forceinline__ void combine_splits(const DecParams &p, const float *
                 *reinterpret_cast<float4 *>(s_red + ((rs * HB + hh) * D + 4 * q4)) = acc[hh];
         }
         __syncthreads();
+        SC_STAMP(9);
         for (int i = tid; i < HB * D; i += NTHREADS) {
             const int hh = i / D, e = i % D;
             if (h0 + hh < G) {

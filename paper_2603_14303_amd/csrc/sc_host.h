@@ -57,7 +57,7 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream);
 // tuning knobs (read by the launchers; set through sc_tune_set)
 struct Tuning {
     int decode_max_splits = 0;      // split-K workgroups per (sequence, KV head); <= 0 picks it from B*Hkv
-    int decode_min_rows = 384;      // rows of the merged cache a split should at least get
+    int decode_min_rows = 192;      // rows of the merged cache a split should at least get
     int gsc_chunks_per_item = 16;   // chunks handled by one workgroup work item
     int gsc_grid_x = 0;             // workgroups per (sequence, KV head); <= 0 picks it from B*Hkv
     int gsc_chunks_per_task = 2;    // fast path: chunks handled by one single-wave workgroup
