@@ -438,7 +438,8 @@ hipError_t launch_gsc_merge(const GscMergeArgs &a, hipStream_t stream) {
     p.cid = a.cluster_id ? a.cluster_id : ws_cid;
     p.cluster_id = a.cluster_id;
 
-    if (a.in_dtype == DType::BF16 && a.d == 128 && tuning().gsc_fast_path) {
+    // (the fast path addresses a window of rows with 32-bit byte offsets: 64 rows of stride_n elements)
+    if (a.in_dtype == DType::BF16 && a.d == 128 && tuning().gsc_fast_path && a.stride_n <= (int64_t(1) << 22)) {
         p.chunks_per_item = max(1, min(kMaxChunksPerItem, tuning().gsc_chunks_per_task));
         return launch_gsc_fast(p, stream);
     }
