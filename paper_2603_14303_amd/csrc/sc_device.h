@@ -155,9 +155,35 @@ __device__ __forceinline__ int lane_gather(int x, int src_lane) {
 __device__ __forceinline__ uint64_t ballot64(bool pred) { return __ballot(pred); }
 __device__ __forceinline__ int first_bit(uint64_t m) { return __ffsll((unsigned long long)m) - 1; }
 
+// fp64 sum over the wave, every lane gets the total: DPP moves inside the rows of 16 lanes and row
+// swaps across them, on the two halves of the value (a __shfl_xor butterfly on doubles is twelve trips
+// through the LDS crossbar)
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double x) {
+    const unsigned long long u = __builtin_bit_cast(unsigned long long, x);
+    const unsigned lo = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)u, CTRL, 0xf, 0xf, true);
+    const unsigned hi = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)(u >> 32), CTRL, 0xf, 0xf, true);
+    return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+}
 __device__ __forceinline__ double wave_allreduce_sum(double x) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
+    x += dpp_f64<kDppQuadXor1>(x);
+    x += dpp_f64<kDppQuadXor2>(x);
+    x += dpp_f64<kDppHalfMirror>(x);
+    x += dpp_f64<kDppMirror>(x);
+    {
+        const unsigned long long u = __builtin_bit_cast(unsigned long long, x);
+        const auto l = __builtin_amdgcn_permlane16_swap((unsigned)u, (unsigned)u, false, false);
+        const auto h = __builtin_amdgcn_permlane16_swap((unsigned)(u >> 32), (unsigned)(u >> 32), false, false);
+        x = __builtin_bit_cast(double, ((unsigned long long)h[0] << 32) | l[0]) +
+            __builtin_bit_cast(double, ((unsigned long long)h[1] << 32) | l[1]);
+    }
+    {
+        const unsigned long long u = __builtin_bit_cast(unsigned long long, x);
+        const auto l = __builtin_amdgcn_permlane32_swap((unsigned)u, (unsigned)u, false, false);
+        const auto h = __builtin_amdgcn_permlane32_swap((unsigned)(u >> 32), (unsigned)(u >> 32), false, false);
+        x = __builtin_bit_cast(double, ((unsigned long long)h[0] << 32) | l[0]) +
+            __builtin_bit_cast(double, ((unsigned long long)h[1] << 32) | l[1]);
+    }
     return x;
 }
 
