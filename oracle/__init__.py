@@ -159,3 +159,54 @@ def decode_attn(Q, Kc, Vc, counts, comp_lens, scale: Optional[float] = None):
                 hq = h * G + g
                 O[b, hq], L[b, hq] = decode_head(Q[b, hq], kc, vc, cn, int(comp_lens[b, h]), scale)
     return O, L
+
+
+# ------------------------------------------------- decode-time growth (the paper leaves it open, Sec. 2.1)
+def decode_attn_tail(Q, Kc, Vc, counts, comp_lens, Kt, Vt, tail_lens, scale: Optional[float] = None):
+    """Eq. 4 over the merged cache followed by an uncompressed tail of new tokens.
+
+    Kt, Vt [B, Hkv, tail_cap, d]; tail_lens [B].  A token that has not been merged is a cluster of
+    one (s = 1, ln s = 0), exactly like a delimiter row of the merged cache, so the definition is
+    Eq. 4 over the rows [merged rows of (b, h)] ++ [first tail_lens[b] tail rows of (b, h)].
+    """
+    Q = np.asarray(Q)
+    B, Hq, d = Q.shape
+    Hkv = Kc.shape[1]
+    G = Hq // Hkv
+    O = np.zeros((B, Hq, d), dtype=np.float64)
+    L = np.zeros((B, Hq), dtype=np.float64)
+    for b in range(B):
+        t = int(tail_lens[b])
+        for h in range(Hkv):
+            nc = int(comp_lens[b, h])
+            k_all = np.concatenate([_f64(Kc[b, h, :nc]), _f64(Kt[b, h, :t])], axis=0)
+            v_all = np.concatenate([_f64(Vc[b, h, :nc]), _f64(Vt[b, h, :t])], axis=0)
+            s_all = np.concatenate([np.asarray(counts[b, h, :nc], dtype=np.int32), np.ones((t,), dtype=np.int32)])
+            for g in range(G):
+                hq = h * G + g
+                O[b, hq], L[b, hq] = decode_head(Q[b, hq], k_all, v_all, s_all, nc + t, scale)
+    return O, L
+
+
+def append_head(state, K_new, V_new, offsets_new: np.ndarray, tau: float, cap: int):
+    """Compress a further stretch of tokens of one (sequence, head) and append its rows.
+
+    `state` is a dict(Kc, Vc, counts, n_rows) as returned by compress_head (arrays of at least `cap`
+    rows are not required: they are copied).  Chunks never interact (Alg. 1 runs per chunk), so the
+    rows of the new stretch are those of compress_head on the stretch alone, placed after the
+    existing n_rows rows.  Returns a new dict(Kc, Vc, counts, n_rows) with `cap` rows of storage;
+    n_rows is the true total even if it exceeds cap (rows beyond cap are dropped).
+    """
+    new = compress_head(K_new, V_new, offsets_new, tau, cap=max(1, np.asarray(K_new).shape[0]))
+    d = np.asarray(K_new).shape[1]
+    Kc = np.zeros((cap, d), dtype=np.float64)
+    Vc = np.zeros((cap, d), dtype=np.float64)
+    counts = np.zeros((cap,), dtype=np.int32)
+    n0 = int(state["n_rows"])
+    keep0 = min(n0, cap)
+    Kc[:keep0], Vc[:keep0], counts[:keep0] = state["Kc"][:keep0], state["Vc"][:keep0], state["counts"][:keep0]
+    keep1 = max(0, min(new["n_rows"], cap - n0))
+    Kc[n0:n0 + keep1], Vc[n0:n0 + keep1] = new["Kc"][:keep1], new["Vc"][:keep1]
+    counts[n0:n0 + keep1] = new["counts"][:keep1]
+    return dict(Kc=Kc, Vc=Vc, counts=counts, n_rows=n0 + int(new["n_rows"]))
+

@@ -346,6 +346,66 @@ def test_decode_gqa_head_mapping():
             assert np.allclose(O[b, hq], softmax(z) @ Vc[b, h, :n], atol=1e-13)
 
 
+# ------------------------------------------------------------------ decode-time growth
+def test_decode_tail_is_attention_over_cache_plus_new_tokens():
+    rng = np.random.default_rng(11)
+    B, Hkv, G, d, cap, tcap = 2, 2, 3, 16, 10, 7
+    Q = rng.standard_normal((B, Hkv * G, d))
+    Kc, Vc = rng.standard_normal((B, Hkv, cap, d)), rng.standard_normal((B, Hkv, cap, d))
+    Kt, Vt = rng.standard_normal((B, Hkv, tcap, d)), rng.standard_normal((B, Hkv, tcap, d))
+    counts = rng.integers(1, 6, (B, Hkv, cap)).astype(np.int32)
+    lens = np.array([[10, 4], [0, 7]], dtype=np.int32)
+    tails = np.array([5, 0], dtype=np.int32)
+    O, L = oracle.decode_attn_tail(Q, Kc, Vc, counts, lens, Kt, Vt, tails)
+    for b in range(B):
+        for hq in range(Hkv * G):
+            h, n, t = hq // G, lens[b, hq // G], tails[b]
+            # written out with scipy: merged rows carry ln s, new tokens carry nothing
+            z = np.concatenate([Kc[b, h, :n] @ Q[b, hq] / np.sqrt(d) + np.log(counts[b, h, :n]),
+                                Kt[b, h, :t] @ Q[b, hq] / np.sqrt(d)])
+            vv = np.concatenate([Vc[b, h, :n], Vt[b, h, :t]])
+            if n + t == 0:
+                assert (O[b, hq] == 0).all() and L[b, hq] == -np.inf
+            else:
+                assert np.allclose(O[b, hq], softmax(z) @ vv, atol=1e-13)
+                assert abs(L[b, hq] - logsumexp(z)) < 1e-12
+    # no tail at all: the plain call
+    O0, L0 = oracle.decode_attn(Q, Kc, Vc, counts, lens)
+    O1, L1 = oracle.decode_attn_tail(Q, Kc, Vc, counts, lens, Kt, Vt, np.zeros(B, np.int32))
+    assert np.array_equal(O0, O1) and np.array_equal(L0, L1)
+    # tail only, nothing merged: textbook attention over the new tokens
+    O2, _ = oracle.decode_attn_tail(Q, Kc, Vc, counts, np.zeros((B, Hkv), np.int32), Kt, Vt, np.full(B, tcap, np.int32))
+    for b in range(B):
+        for hq in range(Hkv * G):
+            want = reference_attention(Q[b, hq], Kt[b, hq // G], Vt[b, hq // G], 1.0 / np.sqrt(d))
+            assert np.allclose(O2[b, hq], want, atol=1e-13)
+
+
+def test_append_equals_compressing_the_whole_sequence_when_cut_at_a_delimiter():
+    # Alg. 1 never looks across a delimiter, so compressing a prefix that ends with a delimiter and then
+    # appending the rest must give the rows of compressing everything at once.
+    w = wl.get_workload("tiny")
+    mask = wl.delimiter_mask(w, 0)
+    n = len(mask)
+    K, V = wl.keys_values(w, 0, 0, 0, mask, n)
+    tau = 0.7
+    off = oracle.segment(mask)
+    whole = oracle.compress_head(K, V, off, tau)
+    delims = np.nonzero(mask)[0]
+    for cut_at in (delims[0], delims[len(delims) // 2], delims[-1]):
+        cut = int(cut_at) + 1                                  # first token after the delimiter
+        head = oracle.compress_head(K[:cut], V[:cut], oracle.segment(mask[:cut]), tau)
+        # the prefix ends with a delimiter, so its last chunk (after it) is empty and adds no row
+        both = oracle.append_head(head, K[cut:], V[cut:], oracle.segment(mask[cut:]), tau, cap=n)
+        assert both["n_rows"] == whole["n_rows"]
+        r = whole["n_rows"]
+        assert np.array_equal(both["counts"][:r], whole["counts"][:r])
+        assert np.array_equal(both["Kc"][:r], whole["Kc"][:r]) and np.array_equal(both["Vc"][:r], whole["Vc"][:r])
+    # capacity: the total is reported even when rows are dropped
+    small = oracle.append_head(head, K[cut:], V[cut:], oracle.segment(mask[cut:]), tau, cap=head["n_rows"] + 1)
+    assert small["n_rows"] == whole["n_rows"] and small["counts"][head["n_rows"]] == whole["counts"][head["n_rows"]]
+
+
 # ------------------------------------------------------------------ end to end
 def test_pipeline_at_tau_one_is_full_cache_attention():
     w = wl.get_workload("tiny")
