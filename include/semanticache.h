@@ -168,6 +168,46 @@ sc_status sc_decode_attn(const void *Q, sc_dtype q_dtype,
                          void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * Decode-time growth.  The paper compresses the prefill cache once and leaves open what happens to the
+ * tokens that arrive afterwards (Sec. 2.1 treats the cache as given).  These two calls follow from
+ * its definitions without adding any: a token that has not been merged is a cluster of one, exactly
+ * like a delimiter row (Sec. 2.4: s holds the cluster sizes, ln 1 = 0), and Alg. 1 never looks across
+ * a delimiter (Sec. 2.3), so a stretch of new tokens that is cut at delimiters can be compressed by
+ * itself and its rows appended.
+ *
+ * sc_decode_attn_tail — sc_decode_attn over the rows of the merged cache followed by the first
+ * tail_lens[b] rows of an uncompressed tail, which attend with size 1:
+ *     rows of (b, h) = Kc[b,h,0..comp_lens[b,h])  ++  Kt[b,h,0..tail_lens[b]).
+ *   Kt, Vt          device [B, Hkv, tail_cap, d] of kv_dtype, contiguous, 16-byte aligned
+ *   tail_lens       device i32 [B] (clamped to [0, tail_cap])
+ * Everything else, the workspace included (same size query, same flags), as for sc_decode_attn.
+ *
+ * sc_gsc_merge_append — sc_gsc_merge of a further stretch of tokens whose rows are written behind the
+ * rows already present: row r of the stretch's result goes to row base_lens[b,h] + r of Kc/Vc/counts,
+ * and comp_lens[b,h] = base_lens[b,h] + (rows of the stretch), or -1 if that exceeds cap or
+ * base_lens[b,h] is already negative or beyond cap (then nothing is written).  K, V, seq_lens,
+ * offsets, num_chunks describe the stretch alone (its own sc_segment call, positions counted from its
+ * first token).  If every earlier stretch ended with a delimiter, the result equals one sc_gsc_merge of
+ * the whole sequence up to summation order.  base_lens is device i32 [B, Hkv] and must not be the
+ * same array as comp_lens (all workgroups read the one while the other is written).
+ */
+sc_status sc_decode_attn_tail(const void *Q, sc_dtype q_dtype,
+                              const void *Kc, const void *Vc, sc_dtype kv_dtype, int cap,
+                              const int32_t *counts, const int32_t *comp_lens,
+                              const void *Kt, const void *Vt, int tail_cap, const int32_t *tail_lens,
+                              int B, int Hq, int Hkv, int d, float scale,
+                              void *O, sc_dtype o_dtype, float *lse,
+                              void *ws, size_t ws_bytes, void *stream);
+sc_status sc_gsc_merge_append(const void *K, const void *V, sc_dtype in_dtype,
+                              int64_t stride_b, int64_t stride_h, int64_t stride_n,
+                              const int32_t *seq_lens, const int32_t *offsets, int64_t offsets_stride_b,
+                              const int32_t *num_chunks,
+                              int B, int Hkv, int N_max, int d, float tau,
+                              void *Kc, void *Vc, sc_dtype out_dtype, int cap,
+                              int32_t *counts, const int32_t *base_lens, int32_t *comp_lens, int32_t *cluster_id,
+                              void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
  * Launch-shape knobs for experiments (process-wide, not thread-safe; results never depend on them
  * beyond floating-point summation order).  Keys:
  *   "decode_max_splits"    split-K workgroups per (sequence, KV head); <= 0 = chosen from B*Hkv

@@ -60,6 +60,12 @@ def load_library() -> ctypes.CDLL:
     lib.sc_decode_attn.restype = i32
     lib.sc_decode_attn.argtypes = [vp, i32, vp, vp, i32, i32, vp, vp, i32, i32, i32, i32, f32,
                                    vp, i32, vp, vp, sz, vp]
+    lib.sc_decode_attn_tail.restype = i32
+    lib.sc_decode_attn_tail.argtypes = [vp, i32, vp, vp, i32, i32, vp, vp, vp, vp, i32, vp, i32, i32, i32, i32, f32,
+                                        vp, i32, vp, vp, sz, vp]
+    lib.sc_gsc_merge_append.restype = i32
+    lib.sc_gsc_merge_append.argtypes = [vp, vp, i32, i64, i64, i64, vp, vp, i64, vp, i32, i32, i32, i32, f32,
+                                        vp, vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -69,6 +75,7 @@ EXPORTED = [
     "sc_segment_workspace_bytes", "sc_segment",
     "sc_gsc_merge_workspace_bytes", "sc_gsc_merge",
     "sc_decode_attn_workspace_bytes", "sc_decode_attn_init_workspace", "sc_decode_attn",
+    "sc_decode_attn_tail", "sc_gsc_merge_append",
 ]
 
 
@@ -157,8 +164,12 @@ def gsc_merge_workspace(B: int, Hkv: int, N_max: int, d: int, device) -> Workspa
 
 def sc_gsc_merge(K, V, offsets, num_chunks, tau: float, seq_lens=None, cap: Optional[int] = None,
                  out_dtype=None, Kc=None, Vc=None, counts=None, comp_lens=None, cluster_id=None,
-                 want_cluster_id: bool = False, workspace: Optional[Workspace] = None):
-    """K, V [B, Hkv, N_max, d] (device, last dim contiguous) -> (Kc, Vc, counts, comp_lens, cluster_id)."""
+                 want_cluster_id: bool = False, workspace: Optional[Workspace] = None, base_lens=None):
+    """K, V [B, Hkv, N_max, d] (device, last dim contiguous) -> (Kc, Vc, counts, comp_lens, cluster_id).
+
+    With base_lens [B, Hkv] (sc_gsc_merge_append) the rows are written behind the base_lens[b, h] rows
+    that Kc, Vc, counts already hold, and comp_lens (a different tensor) receives the new totals.
+    """
     torch = _torch()
     lib = load_library()
     _require_cuda(K, V, offsets, num_chunks, seq_lens, Kc, Vc, counts, comp_lens, cluster_id)
@@ -183,6 +194,17 @@ def sc_gsc_merge(K, V, offsets, num_chunks, tau: float, seq_lens=None, cap: Opti
     for t in (Kc, Vc, counts, comp_lens):
         if not t.is_contiguous():
             raise SemantiCacheError("outputs must be contiguous")
+    if base_lens is not None:
+        _require_cuda(base_lens)
+        if Kc.shape[2] != cap or not base_lens.is_contiguous():
+            raise SemantiCacheError("append needs the existing Kc/Vc/counts (cap rows) and a contiguous base_lens")
+        st = lib.sc_gsc_merge_append(_ptr(K), _ptr(V), _dtype_code(K), K.stride(0), K.stride(1), K.stride(2),
+                                     _ptr(seq_lens), _ptr(offsets), offsets.stride(0), _ptr(num_chunks),
+                                     B, H, N, d, float(tau), _ptr(Kc), _ptr(Vc), _dtype_code(Kc), cap,
+                                     _ptr(counts), _ptr(base_lens), _ptr(comp_lens), _ptr(cluster_id),
+                                     workspace.ptr, workspace.nbytes, _stream())
+        _check(st, "sc_gsc_merge_append")
+        return Kc, Vc, counts, comp_lens, cluster_id
     st = lib.sc_gsc_merge(_ptr(K), _ptr(V), _dtype_code(K), K.stride(0), K.stride(1), K.stride(2),
                           _ptr(seq_lens), _ptr(offsets), offsets.stride(0), _ptr(num_chunks),
                           B, H, N, d, float(tau), _ptr(Kc), _ptr(Vc), _dtype_code(Kc), cap,
@@ -199,8 +221,12 @@ def decode_attn_workspace(B: int, Hq: int, Hkv: int, cap: int, d: int, device) -
 
 
 def sc_decode_attn(Q, Kc, Vc, counts, comp_lens, scale: float = 0.0, O=None, lse=None, want_lse: bool = False,
-                   workspace: Optional[Workspace] = None):
-    """Q [B, Hq, d]; Kc, Vc [B, Hkv, cap, d]; counts [B, Hkv, cap]; comp_lens [B, Hkv] -> (O [B, Hq, d], lse)."""
+                   workspace: Optional[Workspace] = None, Kt=None, Vt=None, tail_lens=None):
+    """Q [B, Hq, d]; Kc, Vc [B, Hkv, cap, d]; counts [B, Hkv, cap]; comp_lens [B, Hkv] -> (O [B, Hq, d], lse).
+
+    With Kt, Vt [B, Hkv, tail_cap, d] and tail_lens [B] (sc_decode_attn_tail) the first tail_lens[b]
+    rows of the uncompressed tail attend behind the merged rows, with size 1.
+    """
     torch = _torch()
     lib = load_library()
     _require_cuda(Q, Kc, Vc, counts, comp_lens, O, lse)
@@ -215,6 +241,20 @@ def sc_decode_attn(Q, Kc, Vc, counts, comp_lens, scale: float = 0.0, O=None, lse
         lse = torch.empty((B, Hq), dtype=torch.float32, device=Q.device)
     if workspace is None:
         workspace = decode_attn_workspace(B, Hq, Hkv, cap, d, Q.device)
+    if Kt is not None:
+        _require_cuda(Kt, Vt, tail_lens)
+        if Kt.shape != Vt.shape or Kt.dtype != Kc.dtype or Vt.dtype != Kc.dtype or Kt.dim() != 4 or \
+                Kt.shape[:2] != Kc.shape[:2] or Kt.shape[3] != d:
+            raise SemantiCacheError("Kt, Vt must be [B, Hkv, tail_cap, d] of the cache's dtype")
+        for t in (Kt, Vt, tail_lens):
+            if not t.is_contiguous():
+                raise SemantiCacheError("inputs must be contiguous")
+        st = lib.sc_decode_attn_tail(_ptr(Q), _dtype_code(Q), _ptr(Kc), _ptr(Vc), _dtype_code(Kc), cap, _ptr(counts),
+                                     _ptr(comp_lens), _ptr(Kt), _ptr(Vt), int(Kt.shape[2]), _ptr(tail_lens),
+                                     B, Hq, Hkv, d, float(scale), _ptr(O), _dtype_code(O), _ptr(lse),
+                                     workspace.ptr, workspace.nbytes, _stream())
+        _check(st, "sc_decode_attn_tail")
+        return O, lse
     st = lib.sc_decode_attn(_ptr(Q), _dtype_code(Q), _ptr(Kc), _ptr(Vc), _dtype_code(Kc), cap, _ptr(counts),
                             _ptr(comp_lens), B, Hq, Hkv, d, float(scale), _ptr(O), _dtype_code(O), _ptr(lse),
                             workspace.ptr, workspace.nbytes, _stream())

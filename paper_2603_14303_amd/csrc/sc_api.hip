@@ -102,12 +102,14 @@ size_t sc_gsc_merge_workspace_bytes(int B, int Hkv, int N_max, int d) {
     return gsc_merge_workspace_bytes(B, Hkv, N_max, d);
 }
 
-sc_status sc_gsc_merge(const void *K, const void *V, sc_dtype in_dtype, int64_t stride_b, int64_t stride_h,
-                       int64_t stride_n, const int32_t *seq_lens, const int32_t *offsets, int64_t offsets_stride_b,
-                       const int32_t *num_chunks, int B, int Hkv, int N_max, int d, float tau, void *Kc, void *Vc,
-                       sc_dtype out_dtype, int cap, int32_t *counts, int32_t *comp_lens, int32_t *cluster_id,
-                       void *ws, size_t ws_bytes, void *stream) {
+static sc_status gsc_common(const void *K, const void *V, sc_dtype in_dtype, int64_t stride_b, int64_t stride_h,
+                            int64_t stride_n, const int32_t *seq_lens, const int32_t *offsets, int64_t offsets_stride_b,
+                            const int32_t *num_chunks, int B, int Hkv, int N_max, int d, float tau, void *Kc, void *Vc,
+                            sc_dtype out_dtype, int cap, int32_t *counts, const int32_t *base_lens, bool append,
+                            int32_t *comp_lens, int32_t *cluster_id, void *ws, size_t ws_bytes, void *stream) {
     if (!K || !V || !offsets || !num_chunks || !Kc || !Vc || !counts || !comp_lens) return SC_ERR_INVALID_ARG;
+    // every workgroup reads the old length while one of them files the new one
+    if (append && (!base_lens || base_lens == comp_lens || !aligned4(base_lens))) return SC_ERR_INVALID_ARG;
     if (B <= 0 || Hkv <= 0 || N_max <= 0) return SC_ERR_INVALID_ARG;
     if (cap <= 0) return SC_ERR_CAPACITY;
     if (!dtype_ok(in_dtype) || !dtype_ok(out_dtype)) return SC_ERR_UNSUPPORTED;
@@ -130,7 +132,29 @@ sc_status sc_gsc_merge(const void *K, const void *V, sc_dtype in_dtype, int64_t 
     a.B = B; a.Hkv = Hkv; a.N_max = N_max; a.d = d; a.tau = tau;
     a.Kc = Kc; a.Vc = Vc; a.out_dtype = static_cast<DType>(out_dtype); a.cap = cap;
     a.counts = counts; a.comp_lens = comp_lens; a.cluster_id = cluster_id; a.ws = ws;
+    a.base_lens = append ? base_lens : nullptr;
     return runtime_status(launch_gsc_merge(a, static_cast<hipStream_t>(stream)));
+}
+
+sc_status sc_gsc_merge(const void *K, const void *V, sc_dtype in_dtype, int64_t stride_b, int64_t stride_h,
+                       int64_t stride_n, const int32_t *seq_lens, const int32_t *offsets, int64_t offsets_stride_b,
+                       const int32_t *num_chunks, int B, int Hkv, int N_max, int d, float tau, void *Kc, void *Vc,
+                       sc_dtype out_dtype, int cap, int32_t *counts, int32_t *comp_lens, int32_t *cluster_id,
+                       void *ws, size_t ws_bytes, void *stream) {
+    return gsc_common(K, V, in_dtype, stride_b, stride_h, stride_n, seq_lens, offsets, offsets_stride_b, num_chunks, B, Hkv,
+                      N_max, d, tau, Kc, Vc, out_dtype, cap, counts, nullptr, false, comp_lens, cluster_id, ws, ws_bytes,
+                      stream);
+}
+
+sc_status sc_gsc_merge_append(const void *K, const void *V, sc_dtype in_dtype, int64_t stride_b, int64_t stride_h,
+                              int64_t stride_n, const int32_t *seq_lens, const int32_t *offsets,
+                              int64_t offsets_stride_b, const int32_t *num_chunks, int B, int Hkv, int N_max, int d,
+                              float tau, void *Kc, void *Vc, sc_dtype out_dtype, int cap, int32_t *counts,
+                              const int32_t *base_lens, int32_t *comp_lens, int32_t *cluster_id, void *ws,
+                              size_t ws_bytes, void *stream) {
+    return gsc_common(K, V, in_dtype, stride_b, stride_h, stride_n, seq_lens, offsets, offsets_stride_b, num_chunks, B, Hkv,
+                      N_max, d, tau, Kc, Vc, out_dtype, cap, counts, base_lens, true, comp_lens, cluster_id, ws, ws_bytes,
+                      stream);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -146,18 +170,23 @@ sc_status sc_decode_attn_init_workspace(void *ws, size_t ws_bytes, int B, int Hk
     return runtime_status(launch_decode_init_workspace(ws, state, static_cast<hipStream_t>(stream)));
 }
 
-sc_status sc_decode_attn(const void *Q, sc_dtype q_dtype, const void *Kc, const void *Vc, sc_dtype kv_dtype, int cap,
-                         const int32_t *counts, const int32_t *comp_lens, int B, int Hq, int Hkv, int d, float scale,
-                         void *O, sc_dtype o_dtype, float *lse, void *ws, size_t ws_bytes, void *stream) {
+static sc_status decode_common(const void *Q, sc_dtype q_dtype, const void *Kc, const void *Vc, sc_dtype kv_dtype, int cap,
+                               const int32_t *counts, const int32_t *comp_lens, const void *Kt, const void *Vt,
+                               int tail_cap, const int32_t *tail_lens, bool with_tail, int B, int Hq, int Hkv, int d,
+                               float scale, void *O, sc_dtype o_dtype, float *lse, void *ws, size_t ws_bytes,
+                               void *stream) {
     if (!Q || !Kc || !Vc || !counts || !comp_lens || !O) return SC_ERR_INVALID_ARG;
+    if (with_tail && (!Kt || !Vt || !tail_lens)) return SC_ERR_INVALID_ARG;
     if (B <= 0 || Hq <= 0 || Hkv <= 0) return SC_ERR_INVALID_ARG;
-    if (cap <= 0) return SC_ERR_CAPACITY;
+    if (cap <= 0 || (with_tail && tail_cap <= 0)) return SC_ERR_CAPACITY;
+    if (with_tail && (int64_t)cap + tail_cap > INT32_MAX) return SC_ERR_CAPACITY;
     if (!dtype_ok(q_dtype) || !dtype_ok(kv_dtype) || !dtype_ok(o_dtype)) return SC_ERR_UNSUPPORTED;
     if (d != 64 && d != 128) return SC_ERR_UNSUPPORTED;
     if (Hq % Hkv) return SC_ERR_UNSUPPORTED;
     if (Hq / Hkv > 8) return SC_ERR_UNSUPPORTED;
     if (Hkv > 65535 || B > 65535) return SC_ERR_UNSUPPORTED;
     if (!aligned16(Q) || !aligned16(Kc) || !aligned16(Vc) || !aligned4(O)) return SC_ERR_INVALID_ARG;
+    if (with_tail && (!aligned16(Kt) || !aligned16(Vt) || !aligned4(tail_lens))) return SC_ERR_INVALID_ARG;
     if (!aligned4(counts) || !aligned4(comp_lens) || (lse && !aligned4(lse))) return SC_ERR_INVALID_ARG;
     if (scale != scale) return SC_ERR_INVALID_ARG;
     const size_t need = decode_workspace_bytes(B, Hq, Hkv, cap, d);
@@ -167,10 +196,26 @@ sc_status sc_decode_attn(const void *Q, sc_dtype q_dtype, const void *Kc, const 
     a.Q = Q; a.q_dtype = static_cast<DType>(q_dtype);
     a.Kc = Kc; a.Vc = Vc; a.kv_dtype = static_cast<DType>(kv_dtype); a.cap = cap;
     a.counts = counts; a.comp_lens = comp_lens;
+    if (with_tail) { a.Kt = Kt; a.Vt = Vt; a.tail_lens = tail_lens; a.tail_cap = tail_cap; }
     a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.d = d;
     a.scale = (scale == 0.f) ? 1.0f / sqrtf((float)d) : scale;
     a.O = O; a.o_dtype = static_cast<DType>(o_dtype); a.lse = lse; a.ws = ws;
     return runtime_status(launch_decode(a, static_cast<hipStream_t>(stream)));
+}
+
+sc_status sc_decode_attn(const void *Q, sc_dtype q_dtype, const void *Kc, const void *Vc, sc_dtype kv_dtype, int cap,
+                         const int32_t *counts, const int32_t *comp_lens, int B, int Hq, int Hkv, int d, float scale,
+                         void *O, sc_dtype o_dtype, float *lse, void *ws, size_t ws_bytes, void *stream) {
+    return decode_common(Q, q_dtype, Kc, Vc, kv_dtype, cap, counts, comp_lens, nullptr, nullptr, 0, nullptr, false, B, Hq,
+                         Hkv, d, scale, O, o_dtype, lse, ws, ws_bytes, stream);
+}
+
+sc_status sc_decode_attn_tail(const void *Q, sc_dtype q_dtype, const void *Kc, const void *Vc, sc_dtype kv_dtype, int cap,
+                              const int32_t *counts, const int32_t *comp_lens, const void *Kt, const void *Vt,
+                              int tail_cap, const int32_t *tail_lens, int B, int Hq, int Hkv, int d, float scale,
+                              void *O, sc_dtype o_dtype, float *lse, void *ws, size_t ws_bytes, void *stream) {
+    return decode_common(Q, q_dtype, Kc, Vc, kv_dtype, cap, counts, comp_lens, Kt, Vt, tail_cap, tail_lens, true, B, Hq,
+                         Hkv, d, scale, O, o_dtype, lse, ws, ws_bytes, stream);
 }
 
 }  // extern "C"

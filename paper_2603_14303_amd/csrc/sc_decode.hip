@@ -49,6 +49,9 @@ struct DecParams {
     const void *Kc, *Vc;
     int cap;
     const int32_t *counts, *comp_lens;
+    const void *Kt, *Vt;           // uncompressed tail [B, Hkv, tail_cap, D] (same element type), or NULL
+    const int32_t *tail_lens;      // [B] tokens in the tail
+    int tail_cap;
     int B, Hq, Hkv;
     float scale_log2;     // scale * log2(e)
     void *O;
@@ -270,7 +273,9 @@ template <int G> struct FastShape {
     static constexpr int U = 4;                       // wave-wide loads of K (and of V) per step
 };
 
-template <int D, int G>
+// TAIL: the rows of a (sequence, KV head) are its merged rows followed by the first tail_lens[b] rows of
+// the uncompressed tail; a tail row is a cluster of one (bias ln 1 = 0).
+template <int D, int G, bool TAIL>
 __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecParams p) {
     static_assert(D == 128, "16 lanes per row");
     constexpr int LPR = 16;
@@ -302,7 +307,8 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // scalar: keeps the row loop wave-uniform
     const int g = lane / LPR, c = lane % LPR;
     const int64_t bh = (int64_t)b * p.Hkv + h;
-    const int rows_total = min(max(p.comp_lens[bh], 0), p.cap);
+    const int rows_c = min(max(p.comp_lens[bh], 0), p.cap);
+    const int rows_total = rows_c + (TAIL ? min(max(p.tail_lens[b], 0), p.tail_cap) : 0);
     const int S = splits_for(rows_total, p.max_splits, p.min_rows);
     if (split >= S) return;
     // contiguous row range of this split, a multiple of the block step except for the last one
@@ -313,6 +319,8 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
     const bf16_t *Kbh = reinterpret_cast<const bf16_t *>(p.Kc) + bh * (int64_t)p.cap * D + 8 * c;
     const bf16_t *Vbh = reinterpret_cast<const bf16_t *>(p.Vc) + bh * (int64_t)p.cap * D + 8 * c;
     const int32_t *cnt_bh = p.counts + bh * (int64_t)p.cap;
+    const bf16_t *Ktbh = TAIL ? reinterpret_cast<const bf16_t *>(p.Kt) + bh * (int64_t)p.tail_cap * D + 8 * c : nullptr;
+    const bf16_t *Vtbh = TAIL ? reinterpret_cast<const bf16_t *>(p.Vt) + bh * (int64_t)p.tail_cap * D + 8 * c : nullptr;
 
     uint4 kb[U], vb[U];
     int cb[U];
@@ -320,7 +328,11 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int row = base + u * RPW + g;
-            if (row < r1) {
+            if (TAIL && row >= rows_c && row < r1) {
+                kb[u] = *reinterpret_cast<const uint4 *>(Ktbh + (int64_t)(row - rows_c) * D);
+                vb[u] = *reinterpret_cast<const uint4 *>(Vtbh + (int64_t)(row - rows_c) * D);
+                cb[u] = 1;
+            } else if (row < r1) {
                 kb[u] = *reinterpret_cast<const uint4 *>(Kbh + (int64_t)row * D);
                 vb[u] = *reinterpret_cast<const uint4 *>(Vbh + (int64_t)row * D);
                 cb[u] = cnt_bh[row];
@@ -490,7 +502,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_generic_kernel(DecParams p
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // scalar: keeps the row loop wave-uniform
     const int g = lane / LPR, c = lane % LPR;
     const int64_t bh = (int64_t)b * p.Hkv + h;
-    const int rows_total = min(max(p.comp_lens[bh], 0), p.cap);
+    const int rows_c = min(max(p.comp_lens[bh], 0), p.cap);
+    // merged rows, then the uncompressed tail (if the call has one): a tail row is a cluster of one
+    const int rows_total = rows_c + (p.Kt ? min(max(p.tail_lens[b], 0), p.tail_cap) : 0);
     const int S = splits_for(rows_total, p.max_splits, p.min_rows);
     if (split >= S) return;
     // contiguous row range of this split, a multiple of the block step except for the last one
@@ -501,6 +515,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_generic_kernel(DecParams p
     const T *Kbh = reinterpret_cast<const T *>(p.Kc) + bh * (int64_t)p.cap * D;
     const T *Vbh = reinterpret_cast<const T *>(p.Vc) + bh * (int64_t)p.cap * D;
     const int32_t *cnt_bh = p.counts + bh * (int64_t)p.cap;
+    const T *Ktbh = reinterpret_cast<const T *>(p.Kt) + bh * (int64_t)p.tail_cap * D;
+    const T *Vtbh = reinterpret_cast<const T *>(p.Vt) + bh * (int64_t)p.tail_cap * D;
 
     // query pieces of the G heads, pre-multiplied by scale*log2(e)
     float q[G][8];
@@ -530,7 +546,11 @@ __global__ __launch_bounds__(kDecThreads) void decode_generic_kernel(DecParams p
         for (int u = 0; u < kDecUnroll; ++u) {
             const int row = base + u * RPW + g;
             ok[u] = row < r1;
-            if (ok[u]) {
+            if (ok[u] && row >= rows_c) {
+                load8(Ktbh + (int64_t)(row - rows_c) * D + 8 * c, kk[u]);
+                load8(Vtbh + (int64_t)(row - rows_c) * D + 8 * c, vv[u]);
+                bias[u] = 0.f;
+            } else if (ok[u]) {
                 load8(Kbh + (int64_t)row * D + 8 * c, kk[u]);
                 load8(Vbh + (int64_t)row * D + 8 * c, vv[u]);
                 bias[u] = __log2f((float)cnt_bh[row]);
@@ -658,7 +678,8 @@ static hipError_t launch_g(const DecParams &p, hipStream_t stream) {
     const dim3 grid(p.max_splits, p.Hkv, p.B);
     if constexpr (D == 128 && sizeof(T) == 2) {
         if (p.q_is_bf16) {
-            hipLaunchKernelGGL((decode_bf16_kernel<D, G>), grid, dim3(FastShape<G>::THREADS), 0, stream, p);
+            if (p.Kt) hipLaunchKernelGGL((decode_bf16_kernel<D, G, true>), grid, dim3(FastShape<G>::THREADS), 0, stream, p);
+            else hipLaunchKernelGGL((decode_bf16_kernel<D, G, false>), grid, dim3(FastShape<G>::THREADS), 0, stream, p);
             return hipGetLastError();
         }
     }
@@ -686,6 +707,7 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream) {
     p.Q = a.Q; p.q_is_bf16 = a.q_dtype == DType::BF16;
     p.Kc = a.Kc; p.Vc = a.Vc; p.cap = a.cap;
     p.counts = a.counts; p.comp_lens = a.comp_lens;
+    p.Kt = a.Kt; p.Vt = a.Vt; p.tail_lens = a.tail_lens; p.tail_cap = a.Kt ? a.tail_cap : 0;
     p.B = a.B; p.Hq = a.Hq; p.Hkv = a.Hkv;
     p.scale_log2 = a.scale * kLog2e;
     p.O = a.O; p.o_is_bf16 = a.o_dtype == DType::BF16;
@@ -702,7 +724,7 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream) {
     int splits = clamp_splits();
     if (tuning().decode_max_splits <= 0) splits = max(2, min(32, 256 / max(1, a.B * a.Hkv)));
     // never more splits than the capacity can feed
-    const int by_cap = (a.cap + p.min_rows - 1) / p.min_rows;
+    const int by_cap = (a.cap + p.tail_cap + p.min_rows - 1) / p.min_rows;
     p.max_splits = max(1, min(splits, by_cap));
     const int G = a.Hq / a.Hkv;
     if (a.kv_dtype == DType::BF16)

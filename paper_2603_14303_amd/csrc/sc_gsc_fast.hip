@@ -923,7 +923,9 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
 // INLINE_PREFIX: no scan kernel ran; every workgroup adds up the cluster counts of the chunks before
 // its task itself (a few KB from L2), and the workgroup of the last task files the total.  Worth it
 // while a sequence has a few thousand chunks: it saves a launch whose only job is that sum.
-template <typename TO, bool INLINE_PREFIX>
+// APPEND: the rows go behind the base_lens[b, h] rows the outputs already hold (with the scan kernel in
+// between, its row bases already include them).
+template <typename TO, bool INLINE_PREFIX, bool APPEND>
 __global__ __launch_bounds__(kFastTaskThreads) void gsc_relocate_kernel(GscParams p) {
     // one-dimensional grid, task index slowest (see the compress kernel)
     const int n_bh_grid = p.B * p.Hkv;
@@ -952,6 +954,8 @@ __global__ __launch_bounds__(kFastTaskThreads) void gsc_relocate_kernel(GscParam
     int32_t *counts_bh = p.counts + bh * p.cap;
     const int64_t cap = p.cap;
     constexpr int NP = (int)sizeof(TO) * 8 / 16;   // 16-byte pieces per lane and row
+    bool base_bad = false;
+    const int base_rows = (INLINE_PREFIX && APPEND) ? gsc_base_rows(p, bh, base_bad) : 0;
 
     for (int task = wg_x; task < tasks; task += p.grid_x) {
         TaskOffsets to;
@@ -984,8 +988,8 @@ __global__ __launch_bounds__(kFastTaskThreads) void gsc_relocate_kernel(GscParam
                 const int up = __shfl_up(incl, d, kWave);
                 if (lane >= d) incl += up;
             }
-            basev = before + m0 + incl - mine;
-            if (m0 + nch == M && lane == nch) p.comp_lens[bh] = (basev <= p.cap) ? basev : -1;
+            basev = base_rows + before + m0 + incl - mine;
+            if (m0 + nch == M && lane == nch) p.comp_lens[bh] = (!base_bad && basev <= p.cap) ? basev : -1;
         } else {
             basev = (lane <= nch) ? rowbase_bh[m0 + lane] : 0;
         }
@@ -1068,11 +1072,16 @@ hipError_t launch_gsc_fast(const GscParams &p, hipStream_t stream) {
     }
     if (stages & 4) {
         if (inline_prefix) {
-            if (p.out_is_bf16) hipLaunchKernelGGL((gsc_relocate_kernel<bf16_t, true>), grid1, dim3(kFastTaskThreads), 0, stream, pc);
-            else hipLaunchKernelGGL((gsc_relocate_kernel<float, true>), grid1, dim3(kFastTaskThreads), 0, stream, pc);
+            if (p.base_lens) {
+                if (p.out_is_bf16) hipLaunchKernelGGL((gsc_relocate_kernel<bf16_t, true, true>), grid1, dim3(kFastTaskThreads), 0, stream, pc);
+                else hipLaunchKernelGGL((gsc_relocate_kernel<float, true, true>), grid1, dim3(kFastTaskThreads), 0, stream, pc);
+            } else {
+                if (p.out_is_bf16) hipLaunchKernelGGL((gsc_relocate_kernel<bf16_t, true, false>), grid1, dim3(kFastTaskThreads), 0, stream, pc);
+                else hipLaunchKernelGGL((gsc_relocate_kernel<float, true, false>), grid1, dim3(kFastTaskThreads), 0, stream, pc);
+            }
         } else {
-            if (p.out_is_bf16) hipLaunchKernelGGL((gsc_relocate_kernel<bf16_t, false>), grid1, dim3(kFastTaskThreads), 0, stream, pc);
-            else hipLaunchKernelGGL((gsc_relocate_kernel<float, false>), grid1, dim3(kFastTaskThreads), 0, stream, pc);
+            if (p.out_is_bf16) hipLaunchKernelGGL((gsc_relocate_kernel<bf16_t, false, false>), grid1, dim3(kFastTaskThreads), 0, stream, pc);
+            else hipLaunchKernelGGL((gsc_relocate_kernel<float, false, false>), grid1, dim3(kFastTaskThreads), 0, stream, pc);
         }
         e = hipGetLastError();
     }

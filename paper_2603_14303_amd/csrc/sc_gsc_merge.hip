@@ -190,7 +190,8 @@ __global__ __launch_bounds__(kGscThreads) void gsc_assign_kernel(GscParams p) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// rowbase[m] = sum_{m' < m} (pcount[m'] + [chunk m' is closed by a delimiter]); comp_lens = total.
+// rowbase[m] = rows already present + sum_{m' < m} (pcount[m'] + [chunk m' is closed by a delimiter]);
+// comp_lens = total.
 __global__ __launch_bounds__(256) void gsc_scan_kernel(GscParams p) {
     __shared__ int s_wave[4];
     __shared__ int s_total;
@@ -205,7 +206,8 @@ __global__ __launch_bounds__(256) void gsc_scan_kernel(GscParams p) {
     const int32_t *pcount_bh = p.pcount + bh * ((int64_t)p.N_max + 1);
     int32_t *rowbase_bh = p.rowbase + bh * ((int64_t)p.N_max + 2);
     constexpr int kItems = 4;
-    int running = 0;
+    bool base_bad;
+    int running = gsc_base_rows(p, bh, base_bad);
     for (int base = 0; base < M; base += 256 * kItems) {
         int v[kItems];
         int sum = 0;
@@ -241,7 +243,7 @@ __global__ __launch_bounds__(256) void gsc_scan_kernel(GscParams p) {
     }
     if (tid == 0) {
         rowbase_bh[M] = running;
-        p.comp_lens[bh] = (running <= p.cap) ? running : -1;
+        p.comp_lens[bh] = (!base_bad && running <= p.cap) ? running : -1;
     }
 }
 
@@ -418,6 +420,7 @@ hipError_t launch_gsc_merge(const GscMergeArgs &a, hipStream_t stream) {
     p.out_is_bf16 = (a.out_dtype == DType::BF16) ? 1 : 0;
     p.cap = a.cap;
     p.counts = a.counts; p.comp_lens = a.comp_lens;
+    p.base_lens = a.base_lens;
     p.chunks_per_item = max(1, min(kMaxChunksPerItem, tuning().gsc_chunks_per_item));
 
     const size_t bh = (size_t)a.B * a.Hkv;

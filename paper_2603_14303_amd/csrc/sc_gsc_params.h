@@ -22,6 +22,7 @@ struct GscParams {
     int out_is_bf16;
     int cap;
     int32_t *counts, *comp_lens;
+    const int32_t *base_lens;   // [B, Hkv] rows already in Kc/Vc/counts (append mode), or NULL for none
     int32_t *cid;         // [B, Hkv, N_max]   cluster index of every token (caller's buffer or workspace)
     int32_t *cluster_id;  // the caller's buffer, or NULL if not requested
     int32_t *seedrow;     // [B, Hkv, N_max]   seed positions of a chunk that spans several blocks
@@ -33,6 +34,14 @@ struct GscParams {
     int chunks_per_item;
     int grid_x;           // fast path: workgroups per pass and (sequence, head) of the compress kernel
 };
+
+// rows already present in the outputs of (sequence, head) bh; an overflowed or impossible state counts as
+// a full cache, so that nothing more is written and the new length is filed as -1
+__device__ __forceinline__ int gsc_base_rows(const GscParams &p, int64_t bh, bool &bad) {
+    const int raw = p.base_lens ? p.base_lens[bh] : 0;
+    bad = raw < 0 || raw > p.cap;
+    return bad ? p.cap : raw;
+}
 
 hipError_t launch_gsc_scan(const GscParams &p, hipStream_t stream);
 hipError_t launch_gsc_fast(const GscParams &p, hipStream_t stream);

@@ -29,6 +29,7 @@ struct GscMergeArgs {
     DType out_dtype;
     int cap;
     int32_t *counts, *comp_lens, *cluster_id;
+    const int32_t *base_lens = nullptr;   // append mode: rows already in the outputs, [B, Hkv]
     void *ws;
 };
 size_t gsc_merge_workspace_bytes(int B, int Hkv, int N_max, int d);
@@ -42,6 +43,9 @@ struct DecodeArgs {
     DType kv_dtype;
     int cap;
     const int32_t *counts, *comp_lens;
+    const void *Kt = nullptr, *Vt = nullptr;   // uncompressed tail [B, Hkv, tail_cap, d], or none
+    const int32_t *tail_lens = nullptr;
+    int tail_cap = 0;
     int B, Hq, Hkv, d;
     float scale;
     void *O;

@@ -125,6 +125,46 @@ def test_decode_rejects_bad_arguments(lib):
     assert lib.sc_decode_attn_init_workspace(FAKE, 4096, 0, 2, None) == 1
 
 
+def test_decode_tail_rejects_bad_arguments(lib):
+    f = lib.sc_decode_attn_tail
+    need = lib.sc_decode_attn_workspace_bytes(1, 8, 2, 512, 128)
+    ok = dict(Q=FAKE, qdt=1, Kc=FAKE, Vc=FAKE, kdt=1, cap=512, counts=FAKE, clens=FAKE, Kt=FAKE, Vt=FAKE, tcap=64,
+              tlens=FAKE, B=1, Hq=8, Hkv=2, d=128, scale=0.0, O=FAKE, odt=1, lse=None, ws=FAKE, wsb=need)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["Q"], a["qdt"], a["Kc"], a["Vc"], a["kdt"], a["cap"], a["counts"], a["clens"], a["Kt"], a["Vt"],
+                 a["tcap"], a["tlens"], a["B"], a["Hq"], a["Hkv"], a["d"], a["scale"], a["O"], a["odt"], a["lse"],
+                 a["ws"], a["wsb"], None)
+    for k in ("Q", "Kc", "Vc", "counts", "clens", "O", "Kt", "Vt", "tlens"):
+        assert call(**{k: None}) == 1, k
+    assert call(tcap=0) == 3 and call(cap=0) == 3
+    assert call(cap=2**31 - 10, tcap=64) == 3        # cap + tail_cap must stay a 32-bit row index
+    assert call(Kt=FAKE + 8) == 1
+    assert call(d=80) == 2 and call(Hq=9) == 2
+    assert call(ws=None) == 4 and call(wsb=16) == 4
+
+
+def test_gsc_merge_append_rejects_bad_arguments(lib):
+    f = lib.sc_gsc_merge_append
+    need = lib.sc_gsc_merge_workspace_bytes(1, 2, 1024, 64)
+    ok = dict(K=FAKE, V=FAKE, idt=0, sb=2 * 1024 * 64, sh=1024 * 64, sn=64, lens=None, off=FAKE, ostride=1026,
+              nch=FAKE, B=1, H=2, N=1024, d=64, tau=0.7, Kc=FAKE, Vc=FAKE, odt=0, cap=4096, counts=FAKE,
+              base=FAKE + 256, clens=FAKE, cid=None, ws=FAKE, wsb=need)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["K"], a["V"], a["idt"], a["sb"], a["sh"], a["sn"], a["lens"], a["off"], a["ostride"], a["nch"],
+                 a["B"], a["H"], a["N"], a["d"], a["tau"], a["Kc"], a["Vc"], a["odt"], a["cap"], a["counts"],
+                 a["base"], a["clens"], a["cid"], a["ws"], a["wsb"], None)
+    for k in ("K", "V", "off", "nch", "Kc", "Vc", "counts", "clens", "base"):
+        assert call(**{k: None}) == 1, k
+    assert call(base=FAKE) == 1             # the old and the new lengths must be different arrays
+    assert call(base=FAKE + 2) == 1
+    assert call(cap=0) == 3 and call(d=96) == 2
+    assert call(ws=None) == 4 and call(wsb=need - 1) == 4
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
     with pytest.raises(sc.SemantiCacheError):
