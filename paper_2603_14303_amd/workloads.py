@@ -31,7 +31,7 @@ import numpy as np
 
 __all__ = [
     "Workload", "WORKLOADS", "get_workload", "round_to_bf16", "bf16_bits",
-    "seq_lens", "delimiter_mask", "keys_values", "redraw_chunk_keys", "queries",
+    "seq_lens", "delimiter_mask", "variant_mask", "keys_values", "redraw_chunk_keys", "queries",
 ]
 
 
@@ -145,6 +145,24 @@ def delimiter_mask(w: Workload, b: int, n: Optional[int] = None) -> np.ndarray:
             break
         pos = int(p[-1])
     return mask
+
+
+def variant_mask(kind: str, delimiters: np.ndarray, n: int, block: int = 64) -> np.ndarray:
+    """Chunk boundaries of the paper's chunking ablation (Sec. 3.4, Table 4) for a sequence of n tokens.
+
+    "delimiters": the mask itself.  "fixed": every block-th token closes a chunk, wherever the real
+    delimiters are (chunks of block - 1 tokens plus the closing token).  "global": no boundary at
+    all, the whole sequence is one chunk.  Keys and values are always drawn from the real
+    delimiter structure; only the boundaries handed to the segmentation change.
+    """
+    if kind == "delimiters":
+        return delimiters.copy()
+    out = np.zeros_like(delimiters)
+    if kind == "fixed":
+        out[block - 1:n:block] = 1
+    elif kind != "global":
+        raise ValueError("unknown chunking %r" % (kind,))
+    return out
 
 
 def _chunk_ids(mask: np.ndarray, n: int) -> Tuple[np.ndarray, int]:

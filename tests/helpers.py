@@ -18,12 +18,15 @@ NEAR_TAU = 1e-6
 
 def build_case(w: wl.Workload, tau: float, layer: int = 0, n_max: int | None = None,
                batch: int | None = None, exclude_near: bool = True, heads: int | None = None,
-               sample=None, workers: int = 8):
+               sample=None, workers: int = 8, chunking: str = "delimiters"):
     """Generate one layer of workload w (optionally truncated) and its oracle compression.
 
     sample: None = the oracle runs on every (sequence, head); else a list of (b, h) pairs: all
     inputs are still generated (the kernels run on the full shape) but the oracle, and the
     re-draw of near-threshold chunks, only cover the listed pairs.
+
+    chunking: "delimiters" (the workload's mask), "fixed" (a boundary every 64 tokens) or "global" (one
+    chunk): the keys and values keep the structure of the real delimiters, the boundaries change.
 
     Returns a dict with numpy arrays:
       mask u8 [B, N], seq_lens i32 [B], K, V f32 [B, Hkv, N, d] (bf16-exact for bf16 workloads),
@@ -43,11 +46,13 @@ def build_case(w: wl.Workload, tau: float, layer: int = 0, n_max: int | None = N
     mask = np.zeros((B, N), dtype=np.uint8)
     K = np.zeros((B, H, N, d), dtype=np.float32)
     V = np.zeros((B, H, N, d), dtype=np.float32)
+    key_mask = np.zeros((B, N), dtype=np.uint8)     # the delimiters that shape the keys and values
     offsets = []
     for b in range(B):
         n = int(lens[b])
         full = wl.delimiter_mask(w, b, n=min(n, w.n_max))
-        mask[b, :n] = full[:n]
+        key_mask[b, :n] = full[:n]
+        mask[b] = wl.variant_mask(chunking, key_mask[b], n)
         offsets.append(oracle.segment(mask[b], n))
     wanted = None if sample is None else set((int(b), int(h)) for b, h in sample)
 
@@ -55,7 +60,7 @@ def build_case(w: wl.Workload, tau: float, layer: int = 0, n_max: int | None = N
         b, h = bh
         n = int(lens[b])
         off = offsets[b]
-        k, v = wl.keys_values(w, layer, b, h, mask[b], n)
+        k, v = wl.keys_values(w, layer, b, h, key_mask[b], n)
         K[b, h, :n], V[b, h, :n] = k, v
         if wanted is not None and bh not in wanted:
             return bh, None, 0
