@@ -210,3 +210,14 @@ def append_head(state, K_new, V_new, offsets_new: np.ndarray, tau: float, cap: i
     counts[n0:n0 + keep1] = new["counts"][:keep1]
     return dict(Kc=Kc, Vc=Vc, counts=counts, n_rows=n0 + int(new["n_rows"]))
 
+
+# ------------------------------------------------- Eq. 4 with several query rows (Q in R^{n x d}, Sec. 2.4)
+def multi_attn(Q, Kc, Vc, counts, comp_lens, scale: Optional[float] = None):
+    """Q [nq, B, Hq, d]: every query row attends to the whole merged cache of its KV head (no mask).
+
+    Eq. 4 is row-wise in Q, so this is decode_attn once per query row.  Returns (O [nq, B, Hq, d], lse [nq, B, Hq]).
+    """
+    Q = np.asarray(Q)
+    outs = [decode_attn(Q[j], Kc, Vc, counts, comp_lens, scale) for j in range(Q.shape[0])]
+    return np.stack([o for o, _ in outs]), np.stack([l for _, l in outs])
+

@@ -406,6 +406,26 @@ def test_append_equals_compressing_the_whole_sequence_when_cut_at_a_delimiter():
     assert small["n_rows"] == whole["n_rows"] and small["counts"][head["n_rows"]] == whole["counts"][head["n_rows"]]
 
 
+def test_multi_query_attention_is_the_matrix_form_of_eq4():
+    # A = softmax(Q Kc^T / sqrt(d) + log s) Vc with Q a matrix (Sec. 2.4), written with numpy matrices
+    rng = np.random.default_rng(21)
+    nq, B, Hkv, G, d, cap = 5, 2, 2, 3, 16, 11
+    Q = rng.standard_normal((nq, B, Hkv * G, d))
+    Kc, Vc = rng.standard_normal((B, Hkv, cap, d)), rng.standard_normal((B, Hkv, cap, d))
+    counts = rng.integers(1, 6, (B, Hkv, cap)).astype(np.int32)
+    lens = np.array([[11, 3], [7, 0]], dtype=np.int32)
+    O, L = oracle.multi_attn(Q, Kc, Vc, counts, lens)
+    for b in range(B):
+        for hq in range(Hkv * G):
+            h, n = hq // G, lens[b, hq // G]
+            if n == 0:
+                assert (O[:, b, hq] == 0).all() and np.isneginf(L[:, b, hq]).all()
+                continue
+            Z = Q[:, b, hq] @ Kc[b, h, :n].T / np.sqrt(d) + np.log(counts[b, h, :n])[None, :]
+            assert np.allclose(O[:, b, hq], softmax(Z, axis=1) @ Vc[b, h, :n], atol=1e-13)
+            assert np.allclose(L[:, b, hq], logsumexp(Z, axis=1), atol=1e-12)
+
+
 # ------------------------------------------------------------------ end to end
 def test_pipeline_at_tau_one_is_full_cache_attention():
     w = wl.get_workload("tiny")
