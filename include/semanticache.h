@@ -208,6 +208,32 @@ sc_status sc_gsc_merge_append(const void *K, const void *V, sc_dtype in_dtype,
                               void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * sc_multi_attn — Eq. 4 for several query rows at once (Sec. 2.4 states it for Q in R^{n x d}): every
+ * query row attends to the whole merged cache of its KV head, no mask between the rows (they are all
+ * later than the cache):
+ *     O[j,b,hq] = softmax_t( Q[j,b,hq] . Kc[b,h,t] * scale + ln(counts[b,h,t]) ) Vc[b,h,t].
+ * For a handful of speculative or freshly arrived tokens.
+ *
+ *   Q               device [nq, B, Hq, d] of q_dtype, contiguous (query-major, so that one row of the
+ *                   call has the layout of an sc_decode_attn query)
+ *   nq              number of query rows, 1..4096
+ *   Kc, Vc, counts, comp_lens, scale    as for sc_decode_attn
+ *   O               device [nq, B, Hq, d] of o_dtype;  lse  device f32 [nq, B, Hq] or NULL
+ *   ws              sc_multi_attn_workspace_bytes(B, Hq, Hkv, nq, cap, d) bytes; carries no state
+ *
+ * bf16 queries and cache with d = 128 run on the matrix cores (probabilities are rounded to bf16
+ * before they multiply the values, fp32 accumulation); every other combination goes row by row through
+ * the sc_decode_attn kernels.  Host errors as for sc_decode_attn, plus nq out of range.
+ */
+size_t sc_multi_attn_workspace_bytes(int B, int Hq, int Hkv, int nq, int cap, int d);
+sc_status sc_multi_attn(const void *Q, sc_dtype q_dtype, int nq,
+                        const void *Kc, const void *Vc, sc_dtype kv_dtype, int cap,
+                        const int32_t *counts, const int32_t *comp_lens,
+                        int B, int Hq, int Hkv, int d, float scale,
+                        void *O, sc_dtype o_dtype, float *lse,
+                        void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
  * Launch-shape knobs for experiments (process-wide, not thread-safe; results never depend on them
  * beyond floating-point summation order).  Keys:
  *   "decode_max_splits"    split-K workgroups per (sequence, KV head); <= 0 = chosen from B*Hkv

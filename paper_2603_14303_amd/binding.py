@@ -66,6 +66,11 @@ def load_library() -> ctypes.CDLL:
     lib.sc_gsc_merge_append.restype = i32
     lib.sc_gsc_merge_append.argtypes = [vp, vp, i32, i64, i64, i64, vp, vp, i64, vp, i32, i32, i32, i32, f32,
                                         vp, vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.sc_multi_attn_workspace_bytes.restype = sz
+    lib.sc_multi_attn_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32]
+    lib.sc_multi_attn.restype = i32
+    lib.sc_multi_attn.argtypes = [vp, i32, i32, vp, vp, i32, i32, vp, vp, i32, i32, i32, i32, f32,
+                                  vp, i32, vp, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -76,6 +81,7 @@ EXPORTED = [
     "sc_gsc_merge_workspace_bytes", "sc_gsc_merge",
     "sc_decode_attn_workspace_bytes", "sc_decode_attn_init_workspace", "sc_decode_attn",
     "sc_decode_attn_tail", "sc_gsc_merge_append",
+    "sc_multi_attn_workspace_bytes", "sc_multi_attn",
 ]
 
 
@@ -260,3 +266,28 @@ def sc_decode_attn(Q, Kc, Vc, counts, comp_lens, scale: float = 0.0, O=None, lse
                             workspace.ptr, workspace.nbytes, _stream())
     _check(st, "sc_decode_attn")
     return O, lse
+
+
+def sc_multi_attn(Q, Kc, Vc, counts, comp_lens, scale: float = 0.0, O=None, lse=None, want_lse: bool = False,
+                  workspace: Optional[Workspace] = None):
+    """Q [nq, B, Hq, d] -> (O [nq, B, Hq, d], lse [nq, B, Hq]): every query row over the whole merged cache."""
+    torch = _torch()
+    lib = load_library()
+    _require_cuda(Q, Kc, Vc, counts, comp_lens, O, lse)
+    nq, B, Hq, d = Q.shape
+    _, Hkv, cap, _ = Kc.shape
+    for t in (Q, Kc, Vc, counts, comp_lens):
+        if not t.is_contiguous():
+            raise SemantiCacheError("inputs must be contiguous")
+    if O is None:
+        O = torch.empty((nq, B, Hq, d), dtype=Q.dtype, device=Q.device)
+    if lse is None and want_lse:
+        lse = torch.empty((nq, B, Hq), dtype=torch.float32, device=Q.device)
+    if workspace is None:
+        workspace = Workspace(lib.sc_multi_attn_workspace_bytes(B, Hq, Hkv, nq, cap, d), Q.device)
+    st = lib.sc_multi_attn(_ptr(Q), _dtype_code(Q), nq, _ptr(Kc), _ptr(Vc), _dtype_code(Kc), cap, _ptr(counts),
+                           _ptr(comp_lens), B, Hq, Hkv, d, float(scale), _ptr(O), _dtype_code(O), _ptr(lse),
+                           workspace.ptr, workspace.nbytes, _stream())
+    _check(st, "sc_multi_attn")
+    return O, lse
+

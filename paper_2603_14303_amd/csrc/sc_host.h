@@ -58,6 +58,25 @@ size_t decode_workspace_state_bytes(int B, int Hkv);
 hipError_t launch_decode_init_workspace(void *ws, size_t state_bytes, hipStream_t stream);
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream);
 
+// ---- sc_multi_attn
+struct MultiArgs {
+    const void *Q;            // [nq, B, Hq, d]
+    DType q_dtype;
+    int nq;
+    const void *Kc, *Vc;
+    DType kv_dtype;
+    int cap;
+    const int32_t *counts, *comp_lens;
+    int B, Hq, Hkv, d;
+    float scale;
+    void *O;                  // [nq, B, Hq, d]
+    DType o_dtype;
+    float *lse;               // [nq, B, Hq] or NULL
+    void *ws;
+};
+size_t multi_workspace_bytes(int B, int Hq, int Hkv, int nq, int cap, int d);
+hipError_t launch_multi(const MultiArgs &a, hipStream_t stream);
+
 // tuning knobs (read by the launchers; set through sc_tune_set)
 struct Tuning {
     int decode_max_splits = 0;      // split-K workgroups per (sequence, KV head); <= 0 picks it from B*Hkv

@@ -1,0 +1,366 @@
+// sc_multi_attn: Proportional Attention for a block of query rows (paper Sec. 2.4, Eq. 4 with
+// Q in R^{n x d}):   O[j] = softmax(Q[j] K_c^T * scale + ln s) V_c   for every query row j, no mask.
+//
+// Fast path (bf16 queries and cache, d = 128) on the matrix cores.  The query rows that share a KV head
+// -- (query j, head g of the group), nq * G of them -- are cut into blocks of 32 = two MFMA tiles; a
+// workgroup of four wavefronts owns one block and one contiguous range of cache rows (split-K), its
+// wavefronts take alternate 32-row steps of that range.  Per step and wavefront:
+//   * S^T = K_c Q^T with v_mfma_f32_16x16x16_bf16: the cache rows are the A operand, the query rows the
+//     B operand, both loaded straight from memory in operand layout (lane l: row l%16, 16-byte piece
+//     l/16 + 4j of the row; the contraction index may be permuted freely as long as both sides agree).
+//     The result lands with the query row on l%16 and four cache rows per lane, which is exactly the A
+//     layout of the second product, so the probabilities never move between lanes.
+//   * scale, + log2(size) bias, online softmax per query row (exp2 domain): in-lane over the lane's
+//     cache rows, then over the four lane groups with two row swaps.
+//   * O += P V with the same MFMA, P rounded to bf16 (the running sum adds the rounded values), V rows
+//     loaded 16 bytes per lane and regrouped with v_perm into the B operand (column 8c + j on lane c).
+// The four wavefronts fold through LDS, the workgroup writes one partial (acc[128], m, l) per query
+// row, and a second small kernel folds the splits.  Two launches instead of a hand-over inside the
+// kernel: the call is for several rows at once, a few microseconds of launch matter less than for
+// single-row decode.
+//
+// Everything else (fp32, d = 64) goes row by row through the decode kernels.
+#include "sc_device.h"
+#include "sc_host.h"
+
+namespace sc {
+
+typedef short mq_short4 __attribute__((ext_vector_type(4)));
+typedef float mq_float4 __attribute__((ext_vector_type(4)));
+
+constexpr int kMqD = 128;
+constexpr int kMqRows = 32;                       // query rows per workgroup
+constexpr int kMqWaves = 4;
+constexpr int kMqThreads = kMqWaves * kWave;
+constexpr int kMqStep = 32;                       // cache rows per wavefront and softmax update
+constexpr int kMqBlockStep = kMqStep * kMqWaves;
+constexpr int kMqMaxSplits = 64;
+constexpr int kMqPart = kMqD + 4;                 // floats per partial row: acc[128], m, l, pad
+constexpr float kMqLog2e = 1.4426950408889634f;
+constexpr float kMqLn2 = 0.6931471805599453f;
+
+struct MqParams {
+    const bf16_t *Q;          // [nq, B, Hq, 128]
+    const bf16_t *Kc, *Vc;    // [B, Hkv, cap, 128]
+    const int32_t *counts, *comp_lens;
+    int nq, cap, B, Hq, Hkv, G;
+    float scale_log2;
+    float *part;              // [B*Hkv*row_blocks][max_splits][32][kMqPart]
+    int row_blocks, max_splits, min_rows;
+    void *O;                  // [nq, B, Hq, 128]
+    int o_is_bf16;
+    float *lse;               // [nq, B, Hq] or NULL
+};
+
+__device__ __forceinline__ int mq_splits_for(int rows, int max_splits, int min_rows) {
+    const int s = (rows + min_rows - 1) / min_rows;
+    return s < 1 ? 1 : (s > max_splits ? max_splits : s);
+}
+__device__ __forceinline__ uint32_t mq_pack_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
+__device__ __forceinline__ uint32_t mq_pack_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
+__device__ __forceinline__ uint32_t mq_dword(const uint4 &v, int j) {   // j is a compile-time constant after unrolling
+    return j == 0 ? v.x : (j == 1 ? v.y : (j == 2 ? v.z : v.w));
+}
+__device__ __forceinline__ mq_short4 mq_op(uint32_t lo, uint32_t hi) {
+    const uint2 u = make_uint2(lo, hi);
+    return __builtin_bit_cast(mq_short4, u);
+}
+// max / sum over the four 16-lane rows of a wavefront, same position in the row
+__device__ __forceinline__ float mq_rows_max(float x) {
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float mq_rows_sum(float x) {
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float mq_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__global__ __launch_bounds__(kMqThreads) void multi_attn_kernel(MqParams p) {
+    __shared__ __attribute__((aligned(16))) float s_acc[kMqRows * kMqD];
+    __shared__ float s_m[kMqWaves][kMqRows];
+    __shared__ float s_l[kMqWaves][kMqRows];
+
+    const int split = blockIdx.x;
+    const int rb = (int)blockIdx.y / p.Hkv, h = (int)blockIdx.y - rb * p.Hkv;
+    const int b = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int c = lane & 15, kq = lane >> 4;
+    const int64_t bh = (int64_t)b * p.Hkv + h;
+    // (made scalar explicitly: the row loop below holds wave-wide operations and must not diverge)
+    const int rows_total = __builtin_amdgcn_readfirstlane(min(max(p.comp_lens[bh], 0), p.cap));
+    const int S = mq_splits_for(rows_total, p.max_splits, p.min_rows);
+    if (split >= S) return;
+    int per = (rows_total + S - 1) / S;
+    per = (per + kMqBlockStep - 1) / kMqBlockStep * kMqBlockStep;
+    const int r0 = min(split * per, rows_total), r1 = min(r0 + per, rows_total);
+
+    const bf16_t *Kbh = p.Kc + bh * (int64_t)p.cap * kMqD;
+    const bf16_t *Vbh = p.Vc + bh * (int64_t)p.cap * kMqD;
+    const int32_t *cnt_bh = p.counts + bh * (int64_t)p.cap;
+
+    // query rows of the block as B operands: lane (c, kq) holds pieces kq, kq + 4, kq + 8, kq + 12 of row c
+    uint4 qop[2][4];
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        const int R = rb * kMqRows + qt * 16 + c;
+        const bool valid = R < p.nq * p.G;
+        const int j = valid ? R / p.G : 0;
+        const int g = valid ? R - j * p.G : 0;
+        const bf16_t *qp = p.Q + (((int64_t)j * p.B + b) * p.Hq + (int64_t)h * p.G + g) * kMqD;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+            qop[qt][jj] = valid ? *reinterpret_cast<const uint4 *>(qp + 8 * (kq + 4 * jj)) : make_uint4(0, 0, 0, 0);
+    }
+
+    float m_run[2] = {-INFINITY, -INFINITY};   // per query row (qt, c), identical on the four lane groups
+    float l_run[2] = {0.f, 0.f};               // this lane's share (its cache rows) of the row's sum
+    mq_float4 o[2][8];                         // o[qt][jn][i]: query row qt*16 + 4kq + i, column 8c + jn
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+        for (int jn = 0; jn < 8; ++jn) o[qt][jn] = mq_float4{0.f, 0.f, 0.f, 0.f};
+
+    for (int base = r0 + wave * kMqStep; base < r1; base += kMqBlockStep) {
+        uint4 kop[2][4], vr[2][4];
+        int cnt[2][4];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int row0 = base + 16 * t;
+            const int krow = row0 + c;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+                kop[t][jj] = (krow < r1) ? *reinterpret_cast<const uint4 *>(Kbh + (int64_t)krow * kMqD + 8 * (kq + 4 * jj))
+                                         : make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int vrow = row0 + 4 * kq + i;
+                vr[t][i] = (vrow < r1) ? *reinterpret_cast<const uint4 *>(Vbh + (int64_t)vrow * kMqD + 8 * c)
+                                       : make_uint4(0, 0, 0, 0);
+                cnt[t][i] = (vrow < r1) ? cnt_bh[vrow] : 0;
+            }
+        }
+        // ---- logits: z[t][qt][i] for cache row base + 16t + 4kq + i and query row qt*16 + c
+        float z[2][2][4];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int qt = 0; qt < 2; ++qt) {
+                mq_float4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    s = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(mq_op(kop[t][jj].x, kop[t][jj].y),
+                                                                 mq_op(qop[qt][jj].x, qop[qt][jj].y), s, 0, 0, 0);
+                    s = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(mq_op(kop[t][jj].z, kop[t][jj].w),
+                                                                 mq_op(qop[qt][jj].z, qop[qt][jj].w), s, 0, 0, 0);
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    z[t][qt][i] = (cnt[t][i] > 0) ? fmaf(s[i], p.scale_log2, __log2f((float)cnt[t][i])) : -INFINITY;
+            }
+        // ---- online softmax per query row
+        mq_short4 pa[2][2];
+        float alpha[2];
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) mx = fmaxf(mx, z[t][qt][i]);
+            mx = mq_rows_max(mx);
+            const float m_new = fmaxf(m_run[qt], mx);
+            const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+            alpha[qt] = mq_exp2(m_run[qt] - m_safe);
+            m_run[qt] = m_new;
+            float psum = 0.f;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const uint32_t p01 = pack_bf16x2(mq_exp2(z[t][qt][0] - m_safe), mq_exp2(z[t][qt][1] - m_safe));
+                const uint32_t p23 = pack_bf16x2(mq_exp2(z[t][qt][2] - m_safe), mq_exp2(z[t][qt][3] - m_safe));
+                psum += (bf16_lo(p01) + bf16_hi(p01)) + (bf16_lo(p23) + bf16_hi(p23));
+                pa[t][qt] = mq_op(p01, p23);
+            }
+            l_run[qt] = fmaf(l_run[qt], alpha[qt], psum);
+        }
+        // ---- rescale the accumulators when a maximum moved (their rows are 4kq + i, the factors sit on lane row)
+        if (__ballot(alpha[0] != 1.0f || alpha[1] != 1.0f) != 0ull) {
+#pragma unroll
+            for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float a = __shfl(alpha[qt], 4 * kq + i, kWave);
+#pragma unroll
+                    for (int jn = 0; jn < 8; ++jn) o[qt][jn][i] *= a;
+                }
+        }
+        // ---- O += P V
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int jn = 0; jn < 8; ++jn) {
+                const uint32_t d0 = mq_dword(vr[t][0], jn >> 1), d1 = mq_dword(vr[t][1], jn >> 1);
+                const uint32_t d2 = mq_dword(vr[t][2], jn >> 1), d3 = mq_dword(vr[t][3], jn >> 1);
+                const uint32_t lo = (jn & 1) ? mq_pack_hi(d0, d1) : mq_pack_lo(d0, d1);
+                const uint32_t hi = (jn & 1) ? mq_pack_hi(d2, d3) : mq_pack_lo(d2, d3);
+                const mq_short4 bb = mq_op(lo, hi);
+#pragma unroll
+                for (int qt = 0; qt < 2; ++qt)
+                    o[qt][jn] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa[t][qt], bb, o[qt][jn], 0, 0, 0);
+            }
+    }
+
+    // ---- fold the four wavefronts through LDS
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        const float lw = mq_rows_sum(l_run[qt]);
+        if (kq == 0) { s_m[wave][qt * 16 + c] = m_run[qt]; s_l[wave][qt * 16 + c] = lw; }
+    }
+    __syncthreads();
+    float f[2][4];      // this wavefront's factor for query rows qt*16 + 4kq + i
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = qt * 16 + 4 * kq + i;
+            float mw = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < kMqWaves; ++w) mw = fmaxf(mw, s_m[w][row]);
+            const float m_safe = (mw == -INFINITY) ? 0.f : mw;
+            f[qt][i] = mq_exp2(s_m[wave][row] - m_safe);
+        }
+    for (int w = 0; w < kMqWaves; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int row = qt * 16 + 4 * kq + i;
+#pragma unroll
+                    for (int jn = 0; jn < 8; ++jn) {
+                        const float v = o[qt][jn][i] * f[qt][i];
+                        float *dst = s_acc + row * kMqD + 8 * c + jn;
+                        *dst = (w == 0) ? v : *dst + v;
+                    }
+                }
+        }
+        __syncthreads();
+    }
+    // ---- this split's partial
+    float *part = p.part + (((bh * p.row_blocks + rb) * (int64_t)p.max_splits + split) * kMqRows) * kMqPart;
+    for (int i = tid; i < kMqRows * kMqD / 4; i += kMqThreads) {
+        const int row = i / (kMqD / 4), q4 = i % (kMqD / 4);
+        *reinterpret_cast<float4 *>(part + (int64_t)row * kMqPart + 4 * q4) =
+            *reinterpret_cast<const float4 *>(s_acc + row * kMqD + 4 * q4);
+    }
+    if (tid < kMqRows) {
+        float mw = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kMqWaves; ++w) mw = fmaxf(mw, s_m[w][tid]);
+        const float m_safe = (mw == -INFINITY) ? 0.f : mw;
+        float l = 0.f;
+#pragma unroll
+        for (int w = 0; w < kMqWaves; ++w) l = fmaf(s_l[w][tid], mq_exp2(s_m[w][tid] - m_safe), l);
+        part[(int64_t)tid * kMqPart + kMqD] = mw;
+        part[(int64_t)tid * kMqPart + kMqD + 1] = l;
+    }
+}
+
+// One workgroup of 128 threads per query row of a (sequence, KV head): thread = output column.
+__global__ __launch_bounds__(kMqD) void multi_attn_combine_kernel(MqParams p) {
+    const int R = blockIdx.x;                 // query row inside the (sequence, KV head): j * G + g
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int col = threadIdx.x;
+    const int64_t bh = (int64_t)b * p.Hkv + h;
+    const int rows_total = min(max(p.comp_lens[bh], 0), p.cap);
+    const int S = mq_splits_for(rows_total, p.max_splits, p.min_rows);
+    const int rb = R / kMqRows, row = R - rb * kMqRows;
+    const float *part = p.part + (((bh * p.row_blocks + rb) * (int64_t)p.max_splits) * kMqRows + row) * kMqPart;
+    const int64_t split_stride = (int64_t)kMqRows * kMqPart;
+    float mx = -INFINITY;
+    for (int s = 0; s < S; ++s) mx = fmaxf(mx, part[s * split_stride + kMqD]);
+    const float m_safe = (mx == -INFINITY) ? 0.f : mx;
+    float acc = 0.f, l = 0.f;
+    for (int s = 0; s < S; ++s) {
+        const float wgt = mq_exp2(part[s * split_stride + kMqD] - m_safe);
+        acc = fmaf(part[s * split_stride + col], wgt, acc);
+        l = fmaf(part[s * split_stride + kMqD + 1], wgt, l);
+    }
+    const int j = R / p.G, g = R - j * p.G;
+    const int64_t orow = ((int64_t)j * p.B + b) * p.Hq + (int64_t)h * p.G + g;
+    const float out = (l > 0.f) ? acc / l : 0.f;
+    if (p.o_is_bf16) reinterpret_cast<uint16_t *>(p.O)[orow * kMqD + col] = (uint16_t)f32_to_bf16(out);
+    else reinterpret_cast<float *>(p.O)[orow * kMqD + col] = out;
+    if (p.lse && col == 0) p.lse[orow] = (l > 0.f) ? (mx + __log2f(l)) * kMqLn2 : -INFINITY;
+}
+
+// ------------------------------------------------------------------------------------------------
+static void mq_shape(int B, int Hq, int Hkv, int nq, int cap, int &row_blocks, int &max_splits, int &min_rows) {
+    const int G = Hq / Hkv;
+    row_blocks = (nq * G + kMqRows - 1) / kMqRows;
+    min_rows = 256;
+    // enough workgroups to cover the 256 CUs about twice, never more splits than the capacity can feed
+    const int want = (512 + B * Hkv * row_blocks - 1) / (B * Hkv * row_blocks);
+    const int by_cap = (cap + min_rows - 1) / min_rows;
+    max_splits = max(1, min(min(kMqMaxSplits, want), by_cap));
+}
+
+static bool mq_fast(const MultiArgs &a) {
+    return a.d == kMqD && a.q_dtype == DType::BF16 && a.kv_dtype == DType::BF16;
+}
+
+size_t multi_workspace_bytes(int B, int Hq, int Hkv, int nq, int cap, int d) {
+    int rb, ms, mr;
+    mq_shape(B, Hq, Hkv, nq, cap, rb, ms, mr);
+    const size_t fast = align_up((size_t)B * Hkv * rb * ms * kMqRows * kMqPart * 4, 256);
+    const size_t generic = decode_workspace_bytes(B, Hq, Hkv, cap, d);
+    return fast > generic ? fast : generic;
+}
+
+hipError_t launch_multi(const MultiArgs &a, hipStream_t stream) {
+    if (!mq_fast(a)) {
+        // row by row through the decode kernels; their workspace starts with flags that must be zero
+        hipError_t e = launch_decode_init_workspace(a.ws, decode_workspace_state_bytes(a.B, a.Hkv), stream);
+        if (e != hipSuccess) return e;
+        const size_t q_es = a.q_dtype == DType::BF16 ? 2 : 4, o_es = a.o_dtype == DType::BF16 ? 2 : 4;
+        const size_t per = (size_t)a.B * a.Hq * a.d;
+        for (int j = 0; j < a.nq; ++j) {
+            DecodeArgs d;
+            d.Q = reinterpret_cast<const char *>(a.Q) + j * per * q_es;
+            d.q_dtype = a.q_dtype;
+            d.Kc = a.Kc; d.Vc = a.Vc; d.kv_dtype = a.kv_dtype; d.cap = a.cap;
+            d.counts = a.counts; d.comp_lens = a.comp_lens;
+            d.B = a.B; d.Hq = a.Hq; d.Hkv = a.Hkv; d.d = a.d;
+            d.scale = a.scale;
+            d.O = reinterpret_cast<char *>(a.O) + j * per * o_es;
+            d.o_dtype = a.o_dtype;
+            d.lse = a.lse ? a.lse + (size_t)j * a.B * a.Hq : nullptr;
+            d.ws = a.ws;
+            e = launch_decode(d, stream);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
+    MqParams p;
+    p.Q = reinterpret_cast<const bf16_t *>(a.Q);
+    p.Kc = reinterpret_cast<const bf16_t *>(a.Kc);
+    p.Vc = reinterpret_cast<const bf16_t *>(a.Vc);
+    p.counts = a.counts; p.comp_lens = a.comp_lens;
+    p.nq = a.nq; p.cap = a.cap; p.B = a.B; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
+    p.scale_log2 = a.scale * kMqLog2e;
+    p.part = reinterpret_cast<float *>(a.ws);
+    mq_shape(a.B, a.Hq, a.Hkv, a.nq, a.cap, p.row_blocks, p.max_splits, p.min_rows);
+    p.O = a.O; p.o_is_bf16 = a.o_dtype == DType::BF16; p.lse = a.lse;
+    hipLaunchKernelGGL(multi_attn_kernel, dim3(p.max_splits, p.row_blocks * a.Hkv, a.B), dim3(kMqThreads), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(multi_attn_combine_kernel, dim3(a.nq * p.G, a.Hkv, a.B), dim3(kMqD), 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace sc

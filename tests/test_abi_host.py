@@ -165,6 +165,26 @@ def test_gsc_merge_append_rejects_bad_arguments(lib):
     assert call(ws=None) == 4 and call(wsb=need - 1) == 4
 
 
+def test_multi_attn_rejects_bad_arguments(lib):
+    f = lib.sc_multi_attn
+    need = lib.sc_multi_attn_workspace_bytes(1, 8, 2, 16, 512, 128)
+    assert need > 0 and lib.sc_multi_attn_workspace_bytes(1, 8, 2, 0, 512, 128) == 0
+    assert lib.sc_multi_attn_workspace_bytes(1, 8, 2, 16, 512, 64) >= lib.sc_decode_attn_workspace_bytes(1, 8, 2, 512, 64)
+    ok = dict(Q=FAKE, qdt=1, nq=16, Kc=FAKE, Vc=FAKE, kdt=1, cap=512, counts=FAKE, clens=FAKE, B=1, Hq=8, Hkv=2,
+              d=128, scale=0.0, O=FAKE, odt=1, lse=None, ws=FAKE, wsb=need)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["Q"], a["qdt"], a["nq"], a["Kc"], a["Vc"], a["kdt"], a["cap"], a["counts"], a["clens"], a["B"],
+                 a["Hq"], a["Hkv"], a["d"], a["scale"], a["O"], a["odt"], a["lse"], a["ws"], a["wsb"], None)
+    for k in ("Q", "Kc", "Vc", "counts", "clens", "O"):
+        assert call(**{k: None}) == 1, k
+    assert call(nq=0) == 1 and call(B=0) == 1
+    assert call(nq=5000) == 2 and call(d=80) == 2 and call(Hq=9) == 2
+    assert call(cap=0) == 3
+    assert call(ws=None) == 4 and call(wsb=need - 1) == 4
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
     with pytest.raises(sc.SemantiCacheError):

@@ -1,0 +1,81 @@
+"""GPU parity for sc_multi_attn (Eq. 4 with a matrix of query rows, Sec. 2.4) against the CPU oracle.
+
+Same bounds as for single-row decode on the same cache: <= 4e-3 * max(1, |O|) with bf16 output (the
+matrix-core path also rounds the probabilities to bf16, relative 2^-9 per term), 2e-5 with fp32 output
+through the row-by-row path; lse <= 1e-3."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2603_14303_amd import binding as sc
+from paper_2603_14303_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import gpu_common as g
+
+
+def _round_like(x, bf16):
+    return wl.round_to_bf16(x.astype(np.float32)) if bf16 else x.astype(np.float32)
+
+
+@pytest.mark.parametrize("bf16,d,Hkv,G,B,cap,nq", [
+    (True, 128, 8, 4, 1, 6000, 16),      # two row blocks per KV head, many splits
+    (True, 128, 4, 7, 3, 1500, 5),       # 35 rows: a full block and a ragged one, G does not divide 32
+    (True, 128, 2, 1, 2, 300, 1),        # a single query row (one lane of a tile in use)
+    (True, 128, 2, 8, 1, 40, 9),         # cache shorter than one step
+    (False, 64, 2, 2, 2, 300, 3),        # row by row through the decode kernels, fp32
+])
+def test_multi_attn_against_oracle(bf16, d, Hkv, G, B, cap, nq):
+    rng = np.random.default_rng(500 + cap + nq)
+    Hq = Hkv * G
+    Q = _round_like(rng.standard_normal((nq, B, Hq, d)), bf16)
+    Kc, Vc = _round_like(rng.standard_normal((B, Hkv, cap, d)), bf16), _round_like(rng.standard_normal((B, Hkv, cap, d)), bf16)
+    counts = rng.integers(1, 40, (B, Hkv, cap)).astype(np.int32)
+    lens = rng.integers(cap // 2, cap + 1, (B, Hkv)).astype(np.int32)
+    lens[0, 0] = cap
+    lens[-1, -1] = 0
+    dQ, dKc, dVc = g.to_device(Q, bf16), g.to_device(Kc, bf16), g.to_device(Vc, bf16)
+    dcounts, dlens = torch.from_numpy(counts).to(g.DEV), torch.from_numpy(lens).to(g.DEV)
+    want_O, want_L = oracle.multi_attn(Q, Kc, Vc, counts, lens)
+    tol = 4e-3 if bf16 else 2e-5
+    for trial in range(2):       # twice on one workspace: it carries no state
+        if trial == 0:
+            ws = sc.Workspace(sc.load_library().sc_multi_attn_workspace_bytes(B, Hq, Hkv, nq, cap, d), g.DEV)
+        O, lse = sc.sc_multi_attn(dQ, dKc, dVc, dcounts, dlens, want_lse=True, workspace=ws)
+        torch.cuda.synchronize()
+        got = O.float().cpu().numpy().astype(np.float64)
+        err = np.abs(got - want_O) / np.maximum(1.0, np.abs(want_O))
+        assert err.max() <= tol, (trial, err.max(), np.unravel_index(err.argmax(), err.shape))
+        got_l = lse.cpu().numpy().astype(np.float64)
+        finite = np.isfinite(want_L)
+        assert np.array_equal(np.isneginf(got_l), np.isneginf(want_L))
+        assert np.abs(got_l[finite] - want_L[finite]).max() <= 1e-3
+    # one query row of the call is what sc_decode_attn gives for that row (same cache, same tolerance)
+    Od, _ = sc.sc_decode_attn(dQ[nq - 1].contiguous(), dKc, dVc, dcounts, dlens)
+    torch.cuda.synchronize()
+    diff = (Od.float() - O[nq - 1].float()).abs().max().item()
+    assert diff <= 2 * tol * max(1.0, float(np.abs(want_O).max())), diff
+
+
+def test_multi_attn_on_a_compressed_layer():
+    # the real pipeline: compress a truncated layer, then 8 query rows over it; fp32 output to see the
+    # kernel's own error against the oracle on the same cache
+    from helpers import build_case
+    w = wl.get_workload("layer32k")
+    case = build_case(w, 0.7, n_max=4096 + 37, heads=3)
+    out = g.run_compress(case, torch.bfloat16)
+    nq, Hq = 8, 3 * w.group
+    Q = np.stack([wl.queries(w, 0, s)[:1, :Hq] for s in range(nq)])
+    dQ = g.to_device(Q, True)
+    O32 = torch.empty((nq, 1, Hq, w.head_dim), dtype=torch.float32, device=g.DEV)
+    O, lse = sc.sc_multi_attn(dQ, out["Kc"], out["Vc"], out["counts"], out["comp_lens"], O=O32, want_lse=True)
+    torch.cuda.synchronize()
+    gK, gV = out["Kc"].float().cpu().numpy(), out["Vc"].float().cpu().numpy()
+    want_O, want_L = oracle.multi_attn(Q, gK, gV, out["counts"].cpu().numpy(), out["comp_lens"].cpu().numpy())
+    err = np.abs(O.cpu().numpy() - want_O).max()
+    assert err <= 4e-3 * max(1.0, np.abs(want_O).max()), err
+    assert np.abs(lse.cpu().numpy() - want_L).max() <= 1e-3
+    print("multi_attn on compressed layer: err %.2e" % err)
