@@ -126,25 +126,33 @@ __global__ __launch_bounds__(kMqThreads) void multi_attn_kernel(MqParams p) {
 #pragma unroll
         for (int jn = 0; jn < 8; ++jn) o[qt][jn] = mq_float4{0.f, 0.f, 0.f, 0.f};
 
-    for (int base = r0 + wave * kMqStep; base < r1; base += kMqBlockStep) {
+    // one step of loads: the keys of 32 cache rows in operand layout, their values 16 bytes per lane, sizes
+    struct StepRegs {
         uint4 kop[2][4], vr[2][4];
         int cnt[2][4];
+    };
+    auto load_step = [&](int base, StepRegs &x) {
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const int row0 = base + 16 * t;
             const int krow = row0 + c;
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj)
-                kop[t][jj] = (krow < r1) ? *reinterpret_cast<const uint4 *>(Kbh + (int64_t)krow * kMqD + 8 * (kq + 4 * jj))
-                                         : make_uint4(0, 0, 0, 0);
+                x.kop[t][jj] = (krow < r1) ? *reinterpret_cast<const uint4 *>(Kbh + (int64_t)krow * kMqD + 8 * (kq + 4 * jj))
+                                           : make_uint4(0, 0, 0, 0);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int vrow = row0 + 4 * kq + i;
-                vr[t][i] = (vrow < r1) ? *reinterpret_cast<const uint4 *>(Vbh + (int64_t)vrow * kMqD + 8 * c)
-                                       : make_uint4(0, 0, 0, 0);
-                cnt[t][i] = (vrow < r1) ? cnt_bh[vrow] : 0;
+                x.vr[t][i] = (vrow < r1) ? *reinterpret_cast<const uint4 *>(Vbh + (int64_t)vrow * kMqD + 8 * c)
+                                         : make_uint4(0, 0, 0, 0);
+                x.cnt[t][i] = (vrow < r1) ? cnt_bh[vrow] : 0;
             }
         }
+    };
+    auto compute_step = [&](const StepRegs &x) {
+        const auto &kop = x.kop;
+        const auto &vr = x.vr;
+        const auto &cnt = x.cnt;
         // ---- logits: z[t][qt][i] for cache row base + 16t + 4kq + i and query row qt*16 + c
         float z[2][2][4];
 #pragma unroll
@@ -213,6 +221,22 @@ __global__ __launch_bounds__(kMqThreads) void multi_attn_kernel(MqParams p) {
                 for (int qt = 0; qt < 2; ++qt)
                     o[qt][jn] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa[t][qt], bb, o[qt][jn], 0, 0, 0);
             }
+    };
+    // two register sets: the loads of the next step fly while this one is computed
+    {
+        StepRegs xa, xb;
+        int base = r0 + wave * kMqStep;
+        if (base < r1) load_step(base, xa);
+        while (base < r1) {
+            const int next = base + kMqBlockStep;
+            if (next < r1) load_step(next, xb);
+            compute_step(xa);
+            if (next >= r1) break;
+            const int next2 = next + kMqBlockStep;
+            if (next2 < r1) load_step(next2, xa);
+            compute_step(xb);
+            base = next2;
+        }
     }
 
     // ---- fold the four wavefronts through LDS
@@ -271,8 +295,13 @@ __global__ __launch_bounds__(kMqThreads) void multi_attn_kernel(MqParams p) {
     }
 }
 
-// One workgroup of 128 threads per query row of a (sequence, KV head): thread = output column.
+// One workgroup of 128 threads per query row of a (sequence, KV head).  The (m, l) of all splits are
+// fetched in one trip by the first wavefront (one split per lane) and turned into weights; then every
+// thread adds up its output column over the splits, sixteen independent loads at a time.
 __global__ __launch_bounds__(kMqD) void multi_attn_combine_kernel(MqParams p) {
+    static_assert(kMqMaxSplits <= kWave, "one split per lane of the first wavefront");
+    __shared__ float s_w[kMqMaxSplits];
+    __shared__ float s_ml[2];
     const int R = blockIdx.x;                 // query row inside the (sequence, KV head): j * G + g
     const int h = blockIdx.y, b = blockIdx.z;
     const int col = threadIdx.x;
@@ -282,15 +311,30 @@ __global__ __launch_bounds__(kMqD) void multi_attn_combine_kernel(MqParams p) {
     const int rb = R / kMqRows, row = R - rb * kMqRows;
     const float *part = p.part + (((bh * p.row_blocks + rb) * (int64_t)p.max_splits) * kMqRows + row) * kMqPart;
     const int64_t split_stride = (int64_t)kMqRows * kMqPart;
-    float mx = -INFINITY;
-    for (int s = 0; s < S; ++s) mx = fmaxf(mx, part[s * split_stride + kMqD]);
-    const float m_safe = (mx == -INFINITY) ? 0.f : mx;
-    float acc = 0.f, l = 0.f;
-    for (int s = 0; s < S; ++s) {
-        const float wgt = mq_exp2(part[s * split_stride + kMqD] - m_safe);
-        acc = fmaf(part[s * split_stride + col], wgt, acc);
-        l = fmaf(part[s * split_stride + kMqD + 1], wgt, l);
+    if (col < kWave) {
+        const float m = (col < S) ? part[col * split_stride + kMqD] : -INFINITY;
+        const float l = (col < S) ? part[col * split_stride + kMqD + 1] : 0.f;
+        float mx = m;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+        const float m_safe = (mx == -INFINITY) ? 0.f : mx;
+        const float wgt = mq_exp2(m - m_safe);
+        float lt = l * wgt;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) lt += __shfl_xor(lt, off, kWave);
+        s_w[col] = wgt;
+        if (col == 0) { s_ml[0] = mx; s_ml[1] = lt; }
     }
+    __syncthreads();
+    float acc = 0.f;
+    for (int s0 = 0; s0 < S; s0 += 16) {
+        float v[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) v[k] = (s0 + k < S) ? part[(s0 + k) * split_stride + col] : 0.f;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) acc = fmaf(v[k], (s0 + k < S) ? s_w[s0 + k] : 0.f, acc);
+    }
+    const float mx = s_ml[0], l = s_ml[1];
     const int j = R / p.G, g = R - j * p.G;
     const int64_t orow = ((int64_t)j * p.B + b) * p.Hq + (int64_t)h * p.G + g;
     const float out = (l > 0.f) ? acc / l : 0.f;
