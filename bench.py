@@ -282,6 +282,19 @@ def main():
     added = (lens_new[0] - bufs[0]["lens"]).cpu().numpy()
     assert (added > 0).all() and (lens_new[0] <= cap).all().item(), added
 
+    # several query rows at once over the merged cache (Eq. 4 with a matrix Q), e.g. speculative tokens
+    NQ = 8
+    Qm = torch.stack([t["Q"][s] for s in range(NQ)]).contiguous()
+    Om = torch.empty_like(Qm)
+    ws_m = sc.Workspace(sc.load_library().sc_multi_attn_workspace_bytes(B, Hq, H, NQ, cap, d), dev)
+
+    def multi_only(i):
+        for s in range(8):
+            c = bufs[(i + 1 + s) % N_CACHE_BUFS]
+            sc.sc_multi_attn(Qm, c["Kc"], c["Vc"], c["counts"], c["lens"], O=Om, workspace=ws_m)
+
+    multi_ms = timed([capture(lambda i=i: multi_only(i)) for i in range(2)], 8, 8)
+
     e = 2
     gsc_bytes = 2 * n_tokens * H * d * e + rows * (2 * d * e + 4) + n_tokens + 4 * (M + B)
     dec_bytes = rows * (2 * d * e + 4) + 2 * B * Hq * d * e
@@ -321,6 +334,10 @@ def main():
     out["growth"] = {"tail_tokens": T, "decode_tail_us": dec_tail_ms * 1e3,
                      "decode_tail_GBps": tail_bytes / (dec_tail_ms * 1e-3) / 1e9,
                      "segment_plus_append_us": append_ms * 1e3, "rows_appended_per_head": added.ravel().tolist()}
+    multi_bytes = rows * (2 * d * e + 4) + 2 * NQ * B * Hq * d * e
+    out["multi_query"] = {"query_rows": NQ, "sc_multi_attn_us": multi_ms * 1e3,
+                          "GBps": multi_bytes / (multi_ms * 1e-3) / 1e9,
+                          "vs_row_by_row_decode": NQ * dec_call_ms / multi_ms}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline(w, host, tau)
     print(json.dumps(out))
