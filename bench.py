@@ -106,6 +106,9 @@ def main():
     ap.add_argument("--workload", default="layer32k")
     ap.add_argument("--tau", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the calls that widen the path (tail attention, append, several query rows); "
+                         "off by default so that a profile of the default command holds the main kernels only")
     ap.add_argument("--eager", action="store_true", help="launch every call from Python instead of replaying HIP graphs")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -253,47 +256,48 @@ def main():
     copy_ms = timed([capture(lambda i=i: copy_only(i)) for i in range(N_KV_COPIES)], 40, 1)
     copy_gbps = 2 * t["K"][0].numel() * 2 / (copy_ms * 1e-3) / 1e9
 
-    # decode-time growth: T new tokens per sequence sit uncompressed behind the merged cache (attended
-    # with size 1), then get compressed and appended
-    T = 256
-    Kt, Vt = t["K"][0][:, :, :T].contiguous(), t["V"][0][:, :, :T].contiguous()
-    tail_lens = torch.full((B,), T, dtype=torch.int32, device=dev)
-    tmask = t["mask"][:, :T].contiguous()
-    toff = torch.empty((B, T + 2), dtype=torch.int32, device=dev)
-    tnch = torch.empty((B,), dtype=torch.int32, device=dev)
-    ws_t = sc.gsc_merge_workspace(B, H, T, d, dev)
-    lens_new = [torch.empty_like(c["lens"]) for c in bufs]
+    if args.extras:
+        # decode-time growth: T new tokens per sequence sit uncompressed behind the merged cache (attended
+        # with size 1), then get compressed and appended
+        T = 256
+        Kt, Vt = t["K"][0][:, :, :T].contiguous(), t["V"][0][:, :, :T].contiguous()
+        tail_lens = torch.full((B,), T, dtype=torch.int32, device=dev)
+        tmask = t["mask"][:, :T].contiguous()
+        toff = torch.empty((B, T + 2), dtype=torch.int32, device=dev)
+        tnch = torch.empty((B,), dtype=torch.int32, device=dev)
+        ws_t = sc.gsc_merge_workspace(B, H, T, d, dev)
+        lens_new = [torch.empty_like(c["lens"]) for c in bufs]
 
-    def dec_tail_only(i):
-        for s in range(w.decode_steps):
-            c = bufs[(i + 1 + s) % N_CACHE_BUFS]
-            sc.sc_decode_attn(t["Q"][s], c["Kc"], c["Vc"], c["counts"], c["lens"], O=O, workspace=ws_d,
-                              Kt=Kt, Vt=Vt, tail_lens=tail_lens)
+        def dec_tail_only(i):
+            for s in range(w.decode_steps):
+                c = bufs[(i + 1 + s) % N_CACHE_BUFS]
+                sc.sc_decode_attn(t["Q"][s], c["Kc"], c["Vc"], c["counts"], c["lens"], O=O, workspace=ws_d,
+                                  Kt=Kt, Vt=Vt, tail_lens=tail_lens)
 
-    def append_round():
-        # rows go behind the existing ones; the old lengths stay in place, so every replay does the same work
-        for i, c in enumerate(bufs):
-            sc.sc_segment(tmask, tail_lens, offsets=toff, num_chunks=tnch)
-            sc.sc_gsc_merge(Kt, Vt, toff, tnch, tau, seq_lens=tail_lens, cap=cap, Kc=c["Kc"], Vc=c["Vc"],
-                            counts=c["counts"], comp_lens=lens_new[i], base_lens=c["lens"], workspace=ws_t)
+        def append_round():
+            # rows go behind the existing ones; the old lengths stay in place, so every replay does the same work
+            for i, c in enumerate(bufs):
+                sc.sc_segment(tmask, tail_lens, offsets=toff, num_chunks=tnch)
+                sc.sc_gsc_merge(Kt, Vt, toff, tnch, tau, seq_lens=tail_lens, cap=cap, Kc=c["Kc"], Vc=c["Vc"],
+                                counts=c["counts"], comp_lens=lens_new[i], base_lens=c["lens"], workspace=ws_t)
 
-    dec_tail_ms = timed([capture(lambda i=i: dec_tail_only(i)) for i in range(4)], 16, w.decode_steps)
-    append_ms = timed([capture(append_round)], 10, N_CACHE_BUFS)
-    added = (lens_new[0] - bufs[0]["lens"]).cpu().numpy()
-    assert (added > 0).all() and (lens_new[0] <= cap).all().item(), added
+        dec_tail_ms = timed([capture(lambda i=i: dec_tail_only(i)) for i in range(4)], 16, w.decode_steps)
+        append_ms = timed([capture(append_round)], 10, N_CACHE_BUFS)
+        added = (lens_new[0] - bufs[0]["lens"]).cpu().numpy()
+        assert (added > 0).all() and (lens_new[0] <= cap).all().item(), added
 
-    # several query rows at once over the merged cache (Eq. 4 with a matrix Q), e.g. speculative tokens
-    NQ = 8
-    Qm = torch.stack([t["Q"][s] for s in range(NQ)]).contiguous()
-    Om = torch.empty_like(Qm)
-    ws_m = sc.Workspace(sc.load_library().sc_multi_attn_workspace_bytes(B, Hq, H, NQ, cap, d), dev)
+        # several query rows at once over the merged cache (Eq. 4 with a matrix Q), e.g. speculative tokens
+        NQ = 8
+        Qm = torch.stack([t["Q"][s] for s in range(NQ)]).contiguous()
+        Om = torch.empty_like(Qm)
+        ws_m = sc.Workspace(sc.load_library().sc_multi_attn_workspace_bytes(B, Hq, H, NQ, cap, d), dev)
 
-    def multi_only(i):
-        for s in range(8):
-            c = bufs[(i + 1 + s) % N_CACHE_BUFS]
-            sc.sc_multi_attn(Qm, c["Kc"], c["Vc"], c["counts"], c["lens"], O=Om, workspace=ws_m)
+        def multi_only(i):
+            for s in range(8):
+                c = bufs[(i + 1 + s) % N_CACHE_BUFS]
+                sc.sc_multi_attn(Qm, c["Kc"], c["Vc"], c["counts"], c["lens"], O=Om, workspace=ws_m)
 
-    multi_ms = timed([capture(lambda i=i: multi_only(i)) for i in range(2)], 8, 8)
+        multi_ms = timed([capture(lambda i=i: multi_only(i)) for i in range(2)], 8, 8)
 
     e = 2
     gsc_bytes = 2 * n_tokens * H * d * e + rows * (2 * d * e + 4) + n_tokens + 4 * (M + B)
@@ -330,14 +334,15 @@ def main():
                             "traffic": tr["decode_bytes"] if tr else None,
                             "algorithmic_bytes": dec_bytes, "us": dec_call_ms * 1e3},
     }
-    tail_bytes = dec_bytes + B * H * T * 2 * d * e
-    out["growth"] = {"tail_tokens": T, "decode_tail_us": dec_tail_ms * 1e3,
-                     "decode_tail_GBps": tail_bytes / (dec_tail_ms * 1e-3) / 1e9,
-                     "segment_plus_append_us": append_ms * 1e3, "rows_appended_per_head": added.ravel().tolist()}
-    multi_bytes = rows * (2 * d * e + 4) + 2 * NQ * B * Hq * d * e
-    out["multi_query"] = {"query_rows": NQ, "sc_multi_attn_us": multi_ms * 1e3,
-                          "GBps": multi_bytes / (multi_ms * 1e-3) / 1e9,
-                          "vs_row_by_row_decode": NQ * dec_call_ms / multi_ms}
+    if args.extras:
+        tail_bytes = dec_bytes + B * H * T * 2 * d * e
+        out["growth"] = {"tail_tokens": T, "decode_tail_us": dec_tail_ms * 1e3,
+                         "decode_tail_GBps": tail_bytes / (dec_tail_ms * 1e-3) / 1e9,
+                         "segment_plus_append_us": append_ms * 1e3, "rows_appended_per_head": added.ravel().tolist()}
+        multi_bytes = rows * (2 * d * e + 4) + 2 * NQ * B * Hq * d * e
+        out["multi_query"] = {"query_rows": NQ, "sc_multi_attn_us": multi_ms * 1e3,
+                              "GBps": multi_bytes / (multi_ms * 1e-3) / 1e9,
+                              "vs_row_by_row_decode": NQ * dec_call_ms / multi_ms}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline(w, host, tau)
     print(json.dumps(out))
