@@ -1,20 +1,23 @@
 // sc_decode_attn: Proportional Attention for one decode step (paper Sec. 2.4, Eq. 4):
 //     O = softmax(q K_c^T * scale + ln s) V_c   per (sequence, query head), GQA-grouped.
+// sc_decode_attn_tail: the same over the merged rows followed by an uncompressed tail of new tokens,
+// which attend as clusters of one (ln 1 = 0).
 //
-// Split-K.  The rows of one (sequence, KV head) are cut into S contiguous ranges, one workgroup of
-// four wavefronts each; the G query heads that share the KV head are handled together so K_c/V_c
-// are read once.  A row is spread over d/8 neighbouring lanes (16-byte pieces, fully coalesced), a
-// wave-wide load covers 64/(d/8) rows, and one "step" of a wave is U such loads of K_c and of V_c,
-// double-buffered in registers so the next step's loads are in flight while this one is computed.
+// Split-K.  The rows of one (sequence, KV head) are cut into S contiguous ranges, one workgroup each;
+// the G query heads that share the KV head are handled together so K_c/V_c are read once.  A row is
+// spread over d/8 neighbouring lanes (16-byte pieces, fully coalesced), a wave-wide load covers
+// 64/(d/8) rows, and one "step" of a wave is U such loads of K_c and of V_c; the next step's loads
+// are requested as soon as the current step's registers are free.
 //
-// Fast kernel (bf16 cache and query, d = 128).  Per step and lane: U*GP partial dot products
-// (GP = G padded to 1/2/4/8; bf16 pairs go through v_dot2_f32_bf16), a transposed DPP reduction that
-// leaves ONE (row, head) score per lane, the online-softmax update done once per score by its owner
-// lane (exp2 domain, log2(size) bias), and a ds_swizzle broadcast of the 16 probabilities back to
-// the lanes that hold the value pieces.  Partials (running max, sum, fp32 accumulator) are folded
-// across lane groups and waves, written to the workspace, and the workgroup that arrives last
-// (ticket counter) folds the S partials into O with all 256 threads.  The ticket is reset by that
-// workgroup, so a workspace that was zeroed once stays ready for the next call.
+// Fast kernel (bf16 cache and query, d = 128; 12 wavefronts per workgroup, 8 for G > 4).  Per step and
+// lane: U*GP partial dot products (GP = G padded to 4 or 8; bf16 pairs go through v_dot2_f32_bf16), a
+// transposed DPP reduction that leaves ONE (row, head) score per lane, the online-softmax update done
+// once per score by its owner lane (exp2 domain, log2(size) bias), and a ds_swizzle broadcast of the 16
+// probabilities back to the lanes that hold the value pieces.  Partials (running max, sum, fp32
+// accumulator) are folded across lane groups and wavefronts and written to the workspace with
+// device-coherent stores; every split but the last then raises its flag, the workgroup of the last
+// split waits for the flags (bounded), folds the S partials into O and leaves the flags at zero, so
+// a workspace that was zeroed once stays ready for the next call.
 //
 // Generic kernel (d = 64, fp32 caches or queries): same split-K scheme, plain DPP all-reduce.
 #include "sc_device.h"

@@ -57,6 +57,15 @@ __device__ __forceinline__ void store8(float *p, const float (&x)[8]) {
 __device__ __forceinline__ double load1_f64(const bf16_t *p) { return (double)__uint_as_float((uint32_t)p->bits << 16); }
 __device__ __forceinline__ double load1_f64(const float *p) { return (double)*p; }
 
+// ------------------------------------------------------------------ bf16 pairs of two rows -> MFMA operand words
+// A lane that holds the same two columns of two rows (a, b: one dword each) gets the words
+// (column 0 of a, column 0 of b) and (column 1 of a, column 1 of b): v_perm_b32, one instruction each.
+__device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
+__device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
+__device__ __forceinline__ uint32_t dword_of(const uint4 &v, int j) {   // j compile-time after unrolling
+    return j == 0 ? v.x : (j == 1 ? v.y : (j == 2 ? v.z : v.w));
+}
+
 // ------------------------------------------------------------------ cross-lane moves (DPP)
 // Symmetric lane pairings inside a row of 16 lanes; all lanes of the wave must be active.
 constexpr int kDppQuadXor1 = 0xB1;      // quad_perm [1,0,3,2]

@@ -65,11 +65,6 @@ __device__ __forceinline__ uint64_t bits_below(int x) {   // bits [0, x), 0 <= x
 __device__ __forceinline__ uint32_t bperm_u32(uint32_t x, int src_lane) {
     return (uint32_t)__builtin_amdgcn_ds_bpermute(src_lane << 2, (int)x);
 }
-__device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
-__device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
-__device__ __forceinline__ uint32_t dword_of(const uint4 &v, int j) {   // j compile-time after unrolling
-    return j == 0 ? v.x : (j == 1 ? v.y : (j == 2 ? v.z : v.w));
-}
 
 // LDS layout of a wavefront
 constexpr int kLdsRowBytes = 272;                         // 256 B of keys + 16 B pad: conflict-free tile reads

@@ -56,11 +56,6 @@ __device__ __forceinline__ int mq_splits_for(int rows, int max_splits, int min_r
     const int s = (rows + min_rows - 1) / min_rows;
     return s < 1 ? 1 : (s > max_splits ? max_splits : s);
 }
-__device__ __forceinline__ uint32_t mq_pack_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
-__device__ __forceinline__ uint32_t mq_pack_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
-__device__ __forceinline__ uint32_t mq_dword(const uint4 &v, int j) {   // j is a compile-time constant after unrolling
-    return j == 0 ? v.x : (j == 1 ? v.y : (j == 2 ? v.z : v.w));
-}
 __device__ __forceinline__ mq_short4 mq_op(uint32_t lo, uint32_t hi) {
     const uint2 u = make_uint2(lo, hi);
     return __builtin_bit_cast(mq_short4, u);
@@ -212,10 +207,10 @@ __global__ __launch_bounds__(kMqThreads) void multi_attn_kernel(MqParams p) {
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int jn = 0; jn < 8; ++jn) {
-                const uint32_t d0 = mq_dword(vr[t][0], jn >> 1), d1 = mq_dword(vr[t][1], jn >> 1);
-                const uint32_t d2 = mq_dword(vr[t][2], jn >> 1), d3 = mq_dword(vr[t][3], jn >> 1);
-                const uint32_t lo = (jn & 1) ? mq_pack_hi(d0, d1) : mq_pack_lo(d0, d1);
-                const uint32_t hi = (jn & 1) ? mq_pack_hi(d2, d3) : mq_pack_lo(d2, d3);
+                const uint32_t d0 = dword_of(vr[t][0], jn >> 1), d1 = dword_of(vr[t][1], jn >> 1);
+                const uint32_t d2 = dword_of(vr[t][2], jn >> 1), d3 = dword_of(vr[t][3], jn >> 1);
+                const uint32_t lo = (jn & 1) ? pack_hi(d0, d1) : pack_lo(d0, d1);
+                const uint32_t hi = (jn & 1) ? pack_hi(d2, d3) : pack_lo(d2, d3);
                 const mq_short4 bb = mq_op(lo, hi);
 #pragma unroll
                 for (int qt = 0; qt < 2; ++qt)
