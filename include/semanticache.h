@@ -238,6 +238,8 @@ sc_status sc_multi_attn(const void *Q, sc_dtype q_dtype, int nq,
  * beyond floating-point summation order).  Keys:
  *   "decode_max_splits"    split-K workgroups per (sequence, KV head); <= 0 = chosen from B*Hkv
  *   "decode_min_rows"      rows of the merged cache a split should at least get
+ *   "decode_mfma_min_group" sc_decode_attn (bf16, d = 128, no tail): query heads per KV head from which the
+ *                          matrix-core kernel of sc_multi_attn is used for the single row; 9 = never
  *   "gsc_fast_path"        0 forces the generic kernels even for bf16 / d = 128
  *   "gsc_chunks_per_task"  fast path: chunks handled by one single-wave workgroup task (1..32)
  *   "gsc_chunks_per_item"  generic path: chunks per work item

@@ -54,6 +54,7 @@ int sc_tune_set(const char *key, int value) {
     Tuning &t = tuning();
     if (!strcmp(key, "decode_max_splits")) t.decode_max_splits = value;
     else if (!strcmp(key, "decode_min_rows")) t.decode_min_rows = value;
+    else if (!strcmp(key, "decode_mfma_min_group")) t.decode_mfma_min_group = value;
     else if (!strcmp(key, "gsc_chunks_per_item")) t.gsc_chunks_per_item = value;
     else if (!strcmp(key, "gsc_grid_x")) t.gsc_grid_x = value;
     else if (!strcmp(key, "gsc_fast_path")) t.gsc_fast_path = value;
@@ -68,6 +69,7 @@ int sc_tune_get(const char *key) {
     const Tuning &t = tuning();
     if (!strcmp(key, "decode_max_splits")) return t.decode_max_splits;
     if (!strcmp(key, "decode_min_rows")) return t.decode_min_rows;
+    if (!strcmp(key, "decode_mfma_min_group")) return t.decode_mfma_min_group;
     if (!strcmp(key, "gsc_chunks_per_item")) return t.gsc_chunks_per_item;
     if (!strcmp(key, "gsc_grid_x")) return t.gsc_grid_x;
     if (!strcmp(key, "gsc_fast_path")) return t.gsc_fast_path;

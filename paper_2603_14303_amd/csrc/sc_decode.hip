@@ -663,10 +663,11 @@ size_t decode_workspace_state_bytes(int B, int Hkv) { return align_up((size_t)B 
 static int clamp_splits() { return max(1, min(kDecMaxSplits, tuning().decode_max_splits)); }   // knob <= 0: automatic
 
 size_t decode_workspace_bytes(int B, int Hq, int Hkv, int cap, int d) {
-    (void)cap;
     const int G = Hq / Hkv;
     // sized for the largest split count the tuning knob may take, so the knob never invalidates a workspace
-    return decode_workspace_state_bytes(B, Hkv) + align_up((size_t)B * Hkv * kDecMaxSplits * G * (d + kPartPad) * 4, 256);
+    const size_t split_k = align_up((size_t)B * Hkv * kDecMaxSplits * G * (d + kPartPad) * 4, 256);
+    const size_t mfma = (d == 128) ? multi_fast_workspace_bytes(B, Hq, Hkv, 1, cap) : 0;   // see launch_decode
+    return decode_workspace_state_bytes(B, Hkv) + (split_k > mfma ? split_k : mfma);
 }
 
 hipError_t launch_decode_init_workspace(void *ws, size_t state_bytes, hipStream_t stream) {
@@ -706,6 +707,22 @@ static hipError_t launch_td(const DecParams &p, int G, hipStream_t stream) {
 }
 
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream) {
+    // Wide head groups: the VALU kernel spends 4*d flops per head and row on the vector units and becomes
+    // issue-bound (0.36-0.46 of peak bandwidth at G = 7); the matrix-core kernel for blocks of query
+    // rows treats the G heads as one 16-row tile and streams faster there.  Its partials go behind the
+    // flags, which it neither needs nor touches.
+    if (a.kv_dtype == DType::BF16 && a.q_dtype == DType::BF16 && a.d == 128 && !a.Kt &&
+        a.Hq / a.Hkv >= tuning().decode_mfma_min_group) {
+        MultiArgs m;
+        m.Q = a.Q; m.q_dtype = a.q_dtype; m.nq = 1;
+        m.Kc = a.Kc; m.Vc = a.Vc; m.kv_dtype = a.kv_dtype; m.cap = a.cap;
+        m.counts = a.counts; m.comp_lens = a.comp_lens;
+        m.B = a.B; m.Hq = a.Hq; m.Hkv = a.Hkv; m.d = a.d;
+        m.scale = a.scale;
+        m.O = a.O; m.o_dtype = a.o_dtype; m.lse = a.lse;
+        m.ws = reinterpret_cast<char *>(a.ws) + decode_workspace_state_bytes(a.B, a.Hkv);
+        return launch_multi_fast(m, stream);
+    }
     DecParams p;
     p.Q = a.Q; p.q_is_bf16 = a.q_dtype == DType::BF16;
     p.Kc = a.Kc; p.Vc = a.Vc; p.cap = a.cap;

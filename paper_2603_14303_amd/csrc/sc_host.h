@@ -76,11 +76,15 @@ struct MultiArgs {
 };
 size_t multi_workspace_bytes(int B, int Hq, int Hkv, int nq, int cap, int d);
 hipError_t launch_multi(const MultiArgs &a, hipStream_t stream);
+// matrix-core path alone (bf16, d = 128): partials in a.ws, no state
+size_t multi_fast_workspace_bytes(int B, int Hq, int Hkv, int nq, int cap);
+hipError_t launch_multi_fast(const MultiArgs &a, hipStream_t stream);
 
 // tuning knobs (read by the launchers; set through sc_tune_set)
 struct Tuning {
     int decode_max_splits = 0;      // split-K workgroups per (sequence, KV head); <= 0 picks it from B*Hkv
     int decode_min_rows = 192;      // rows of the merged cache a split should at least get
+    int decode_mfma_min_group = 5;  // query heads per KV head from which single-row decode runs on the matrix-core kernel (9 = never)
     int gsc_chunks_per_item = 16;   // chunks handled by one workgroup work item
     int gsc_grid_x = 0;             // workgroups per (sequence, KV head); <= 0 picks it from B*Hkv
     int gsc_chunks_per_task = 2;    // fast path: chunks handled by one single-wave workgroup

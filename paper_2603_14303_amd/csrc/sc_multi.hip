@@ -29,7 +29,7 @@ typedef short mq_short4 __attribute__((ext_vector_type(4)));
 typedef float mq_float4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMqD = 128;
-constexpr int kMqRows = 32;                       // query rows per workgroup
+constexpr int kMqRows = 32;                       // query rows per workgroup at most (two MFMA tiles)
 constexpr int kMqWaves = 4;
 constexpr int kMqThreads = kMqWaves * kWave;
 constexpr int kMqStep = 32;                       // cache rows per wavefront and softmax update
@@ -47,6 +47,7 @@ struct MqParams {
     float scale_log2;
     float *part;              // [B*Hkv*row_blocks][max_splits][32][kMqPart]
     int row_blocks, max_splits, min_rows;
+    int block_rows;           // query rows per workgroup: 16 (one MFMA tile) when nq * G <= 16, else 32
     void *O;                  // [nq, B, Hq, 128]
     int o_is_bf16;
     float *lse;               // [nq, B, Hq] or NULL
@@ -75,10 +76,13 @@ __device__ __forceinline__ float mq_rows_sum(float x) {
 }
 __device__ __forceinline__ float mq_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-__global__ __launch_bounds__(kMqThreads) void multi_attn_kernel(MqParams p) {
-    __shared__ __attribute__((aligned(16))) float s_acc[kMqRows * kMqD];
-    __shared__ float s_m[kMqWaves][kMqRows];
-    __shared__ float s_l[kMqWaves][kMqRows];
+// QT: MFMA tiles of query rows per workgroup (1 or 2)
+template <int QT>
+__global__ __launch_bounds__(kMqThreads, QT == 1 ? 2 : 1) void multi_attn_kernel(MqParams p) {
+    constexpr int kRows = 16 * QT;
+    __shared__ __attribute__((aligned(16))) float s_acc[kRows * kMqD];
+    __shared__ float s_m[kMqWaves][kRows];
+    __shared__ float s_l[kMqWaves][kRows];
 
     const int split = blockIdx.x;
     const int rb = (int)blockIdx.y / p.Hkv, h = (int)blockIdx.y - rb * p.Hkv;
@@ -100,10 +104,10 @@ __global__ __launch_bounds__(kMqThreads) void multi_attn_kernel(MqParams p) {
     const int32_t *cnt_bh = p.counts + bh * (int64_t)p.cap;
 
     // query rows of the block as B operands: lane (c, kq) holds pieces kq, kq + 4, kq + 8, kq + 12 of row c
-    uint4 qop[2][4];
+    uint4 qop[QT][4];
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-        const int R = rb * kMqRows + qt * 16 + c;
+    for (int qt = 0; qt < QT; ++qt) {
+        const int R = rb * kRows + qt * 16 + c;
         const bool valid = R < p.nq * p.G;
         const int j = valid ? R / p.G : 0;
         const int g = valid ? R - j * p.G : 0;
@@ -113,13 +117,16 @@ __global__ __launch_bounds__(kMqThreads) void multi_attn_kernel(MqParams p) {
             qop[qt][jj] = valid ? *reinterpret_cast<const uint4 *>(qp + 8 * (kq + 4 * jj)) : make_uint4(0, 0, 0, 0);
     }
 
-    float m_run[2] = {-INFINITY, -INFINITY};   // per query row (qt, c), identical on the four lane groups
-    float l_run[2] = {0.f, 0.f};               // this lane's share (its cache rows) of the row's sum
-    mq_float4 o[2][8];                         // o[qt][jn][i]: query row qt*16 + 4kq + i, column 8c + jn
+    float m_run[QT];   // per query row (qt, c), identical on the four lane groups
+    float l_run[QT];               // this lane's share (its cache rows) of the row's sum
+    mq_float4 o[QT][8];                         // o[qt][jn][i]: query row qt*16 + 4kq + i, column 8c + jn
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt)
+    for (int qt = 0; qt < QT; ++qt) {
+        m_run[qt] = -INFINITY;
+        l_run[qt] = 0.f;
 #pragma unroll
         for (int jn = 0; jn < 8; ++jn) o[qt][jn] = mq_float4{0.f, 0.f, 0.f, 0.f};
+    }
 
     // one step of loads: the keys of 32 cache rows in operand layout, their values 16 bytes per lane, sizes
     struct StepRegs {
@@ -149,11 +156,11 @@ __global__ __launch_bounds__(kMqThreads) void multi_attn_kernel(MqParams p) {
         const auto &vr = x.vr;
         const auto &cnt = x.cnt;
         // ---- logits: z[t][qt][i] for cache row base + 16t + 4kq + i and query row qt*16 + c
-        float z[2][2][4];
+        float z[2][QT][4];
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int qt = 0; qt < 2; ++qt) {
+            for (int qt = 0; qt < QT; ++qt) {
                 mq_float4 s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj) {
@@ -167,10 +174,10 @@ __global__ __launch_bounds__(kMqThreads) void multi_attn_kernel(MqParams p) {
                     z[t][qt][i] = (cnt[t][i] > 0) ? fmaf(s[i], p.scale_log2, __log2f((float)cnt[t][i])) : -INFINITY;
             }
         // ---- online softmax per query row
-        mq_short4 pa[2][2];
-        float alpha[2];
+        mq_short4 pa[2][QT];
+        float alpha[QT];
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
+        for (int qt = 0; qt < QT; ++qt) {
             float mx = -INFINITY;
 #pragma unroll
             for (int t = 0; t < 2; ++t)
@@ -192,9 +199,12 @@ __global__ __launch_bounds__(kMqThreads) void multi_attn_kernel(MqParams p) {
             l_run[qt] = fmaf(l_run[qt], alpha[qt], psum);
         }
         // ---- rescale the accumulators when a maximum moved (their rows are 4kq + i, the factors sit on lane row)
-        if (__ballot(alpha[0] != 1.0f || alpha[1] != 1.0f) != 0ull) {
+        bool moved = false;
 #pragma unroll
-            for (int qt = 0; qt < 2; ++qt)
+        for (int qt = 0; qt < QT; ++qt) moved = moved || (alpha[qt] != 1.0f);
+        if (__ballot(moved) != 0ull) {
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const float a = __shfl(alpha[qt], 4 * kq + i, kWave);
@@ -213,7 +223,7 @@ __global__ __launch_bounds__(kMqThreads) void multi_attn_kernel(MqParams p) {
                 const uint32_t hi = (jn & 1) ? pack_hi(d2, d3) : pack_lo(d2, d3);
                 const mq_short4 bb = mq_op(lo, hi);
 #pragma unroll
-                for (int qt = 0; qt < 2; ++qt)
+                for (int qt = 0; qt < QT; ++qt)
                     o[qt][jn] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa[t][qt], bb, o[qt][jn], 0, 0, 0);
             }
     };
@@ -236,14 +246,14 @@ __global__ __launch_bounds__(kMqThreads) void multi_attn_kernel(MqParams p) {
 
     // ---- fold the four wavefronts through LDS
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
+    for (int qt = 0; qt < QT; ++qt) {
         const float lw = mq_rows_sum(l_run[qt]);
         if (kq == 0) { s_m[wave][qt * 16 + c] = m_run[qt]; s_l[wave][qt * 16 + c] = lw; }
     }
     __syncthreads();
-    float f[2][4];      // this wavefront's factor for query rows qt*16 + 4kq + i
+    float f[QT][4];      // this wavefront's factor for query rows qt*16 + 4kq + i
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt)
+    for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int row = qt * 16 + 4 * kq + i;
@@ -256,7 +266,7 @@ __global__ __launch_bounds__(kMqThreads) void multi_attn_kernel(MqParams p) {
     for (int w = 0; w < kMqWaves; ++w) {
         if (wave == w) {
 #pragma unroll
-            for (int qt = 0; qt < 2; ++qt)
+            for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int row = qt * 16 + 4 * kq + i;
@@ -271,13 +281,13 @@ __global__ __launch_bounds__(kMqThreads) void multi_attn_kernel(MqParams p) {
         __syncthreads();
     }
     // ---- this split's partial
-    float *part = p.part + (((bh * p.row_blocks + rb) * (int64_t)p.max_splits + split) * kMqRows) * kMqPart;
-    for (int i = tid; i < kMqRows * kMqD / 4; i += kMqThreads) {
+    float *part = p.part + (((bh * p.row_blocks + rb) * (int64_t)p.max_splits + split) * kRows) * kMqPart;
+    for (int i = tid; i < kRows * kMqD / 4; i += kMqThreads) {
         const int row = i / (kMqD / 4), q4 = i % (kMqD / 4);
         *reinterpret_cast<float4 *>(part + (int64_t)row * kMqPart + 4 * q4) =
             *reinterpret_cast<const float4 *>(s_acc + row * kMqD + 4 * q4);
     }
-    if (tid < kMqRows) {
+    if (tid < kRows) {
         float mw = -INFINITY;
 #pragma unroll
         for (int w = 0; w < kMqWaves; ++w) mw = fmaxf(mw, s_m[w][tid]);
@@ -303,9 +313,9 @@ __global__ __launch_bounds__(kMqD) void multi_attn_combine_kernel(MqParams p) {
     const int64_t bh = (int64_t)b * p.Hkv + h;
     const int rows_total = min(max(p.comp_lens[bh], 0), p.cap);
     const int S = mq_splits_for(rows_total, p.max_splits, p.min_rows);
-    const int rb = R / kMqRows, row = R - rb * kMqRows;
-    const float *part = p.part + (((bh * p.row_blocks + rb) * (int64_t)p.max_splits) * kMqRows + row) * kMqPart;
-    const int64_t split_stride = (int64_t)kMqRows * kMqPart;
+    const int rb = R / p.block_rows, row = R - rb * p.block_rows;
+    const float *part = p.part + (((bh * p.row_blocks + rb) * (int64_t)p.max_splits) * p.block_rows + row) * kMqPart;
+    const int64_t split_stride = (int64_t)p.block_rows * kMqPart;
     if (col < kWave) {
         const float m = (col < S) ? part[col * split_stride + kMqD] : -INFINITY;
         const float l = (col < S) ? part[col * split_stride + kMqD + 1] : 0.f;
@@ -339,9 +349,10 @@ __global__ __launch_bounds__(kMqD) void multi_attn_combine_kernel(MqParams p) {
 }
 
 // ------------------------------------------------------------------------------------------------
-static void mq_shape(int B, int Hq, int Hkv, int nq, int cap, int &row_blocks, int &max_splits, int &min_rows) {
+static void mq_shape(int B, int Hq, int Hkv, int nq, int cap, int &row_blocks, int &max_splits, int &min_rows, int &block_rows) {
     const int G = Hq / Hkv;
-    row_blocks = (nq * G + kMqRows - 1) / kMqRows;
+    block_rows = (nq * G <= 16) ? 16 : kMqRows;
+    row_blocks = (nq * G + block_rows - 1) / block_rows;
     min_rows = 256;
     // enough workgroups to cover the 256 CUs about twice, never more splits than the capacity can feed
     const int want = (512 + B * Hkv * row_blocks - 1) / (B * Hkv * row_blocks);
@@ -353,10 +364,14 @@ static bool mq_fast(const MultiArgs &a) {
     return a.d == kMqD && a.q_dtype == DType::BF16 && a.kv_dtype == DType::BF16;
 }
 
+size_t multi_fast_workspace_bytes(int B, int Hq, int Hkv, int nq, int cap) {
+    int rb, ms, mr, br;
+    mq_shape(B, Hq, Hkv, nq, cap, rb, ms, mr, br);
+    return align_up((size_t)B * Hkv * rb * ms * br * kMqPart * 4, 256);
+}
+
 size_t multi_workspace_bytes(int B, int Hq, int Hkv, int nq, int cap, int d) {
-    int rb, ms, mr;
-    mq_shape(B, Hq, Hkv, nq, cap, rb, ms, mr);
-    const size_t fast = align_up((size_t)B * Hkv * rb * ms * kMqRows * kMqPart * 4, 256);
+    const size_t fast = multi_fast_workspace_bytes(B, Hq, Hkv, nq, cap);
     const size_t generic = decode_workspace_bytes(B, Hq, Hkv, cap, d);
     return fast > generic ? fast : generic;
 }
@@ -385,6 +400,10 @@ hipError_t launch_multi(const MultiArgs &a, hipStream_t stream) {
         }
         return hipSuccess;
     }
+    return launch_multi_fast(a, stream);
+}
+
+hipError_t launch_multi_fast(const MultiArgs &a, hipStream_t stream) {
     MqParams p;
     p.Q = reinterpret_cast<const bf16_t *>(a.Q);
     p.Kc = reinterpret_cast<const bf16_t *>(a.Kc);
@@ -393,9 +412,11 @@ hipError_t launch_multi(const MultiArgs &a, hipStream_t stream) {
     p.nq = a.nq; p.cap = a.cap; p.B = a.B; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
     p.scale_log2 = a.scale * kMqLog2e;
     p.part = reinterpret_cast<float *>(a.ws);
-    mq_shape(a.B, a.Hq, a.Hkv, a.nq, a.cap, p.row_blocks, p.max_splits, p.min_rows);
+    mq_shape(a.B, a.Hq, a.Hkv, a.nq, a.cap, p.row_blocks, p.max_splits, p.min_rows, p.block_rows);
     p.O = a.O; p.o_is_bf16 = a.o_dtype == DType::BF16; p.lse = a.lse;
-    hipLaunchKernelGGL(multi_attn_kernel, dim3(p.max_splits, p.row_blocks * a.Hkv, a.B), dim3(kMqThreads), 0, stream, p);
+    const dim3 grid(p.max_splits, p.row_blocks * a.Hkv, a.B);
+    if (p.block_rows == 16) hipLaunchKernelGGL(multi_attn_kernel<1>, grid, dim3(kMqThreads), 0, stream, p);
+    else hipLaunchKernelGGL(multi_attn_kernel<2>, grid, dim3(kMqThreads), 0, stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(multi_attn_combine_kernel, dim3(a.nq * p.G, a.Hkv, a.B), dim3(kMqD), 0, stream, p);

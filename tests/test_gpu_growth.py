@@ -61,10 +61,15 @@ def test_decode_tail_against_oracle(bf16, q_bf16, d, Hkv, G, B, cap, tcap):
         assert np.array_equal(np.isneginf(got_l), np.isneginf(want_L))
         assert np.abs(got_l[finite] - want_L[finite]).max() <= 1e-3, trial
         if trial == 1:
-            # an empty tail is the plain call
+            # an empty tail is the plain call: bit for bit where both run the same kernel (wide head
+            # groups take the matrix-core kernel for the plain call), within the tolerance otherwise
             O0, lse0 = sc.sc_decode_attn(dQ, dKc, dVc, dcounts, dlens, want_lse=True, workspace=ws)
             torch.cuda.synchronize()
-            assert torch.equal(O0, O) and torch.equal(lse0, lse)
+            if not (bf16 and q_bf16 and d == 128 and G >= sc.tune_get("decode_mfma_min_group")):
+                assert torch.equal(O0, O) and torch.equal(lse0, lse)
+            else:
+                got0 = O0.float().cpu().numpy().astype(np.float64)
+                assert (np.abs(got0 - want_O) / np.maximum(1.0, np.abs(want_O))).max() <= tol
     # nothing merged anywhere: attention over the new tokens alone
     dzero = torch.zeros_like(dlens)
     O, _ = sc.sc_decode_attn(dQ, dKc, dVc, dcounts, dzero, workspace=ws, Kt=dKt, Vt=dVt,

@@ -183,10 +183,12 @@ def test_repeatable_bit_for_bit():
     dict(gsc_chunks_per_task=1), dict(gsc_chunks_per_task=3, gsc_grid_x=16), dict(gsc_chunks_per_task=5),
     dict(gsc_chunks_per_task=32, gsc_grid_x=4), dict(gsc_grid_x=7), dict(gsc_fast_path=0),
     dict(gsc_fast_path=0, gsc_chunks_per_item=3, gsc_grid_x=5),
+    dict(decode_mfma_min_group=1), dict(decode_mfma_min_group=9), dict(decode_max_splits=3, decode_min_rows=64),
 ])
 def test_launch_shape_knobs_do_not_change_results(knobs):
-    # other task sizes, grids narrower than the task count (workgroups then walk several tasks) and the
-    # generic kernels on the fast path's inputs: same integers, merged rows within the same bounds
+    # other task sizes, grids narrower than the task count (workgroups then walk several tasks), the
+    # generic kernels on the fast path's inputs, and single-row decode on either attention kernel:
+    # same integers, merged rows and attention outputs within the same bounds
     w = wl.get_workload("long128k")
     case = build_case(w, 0.7, n_max=5000 + 11, heads=2)
     old = {k: sc.tune_get(k) for k in knobs}
