@@ -208,6 +208,41 @@ sc_status sc_gsc_merge_append(const void *K, const void *V, sc_dtype in_dtype,
                               void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * sc_gsc_merge_budget — sc_gsc_merge with the threshold chosen for a target cache size.  The paper
+ * reports at cache budgets (Sec. 3.1: 20 / 35 / 50 % of the entries kept) without giving the rule
+ * that turns a budget into the threshold of Alg. 1; this call takes the largest threshold a bisection
+ * finds whose merged caches hold at most budget_rows rows in total (summed over all sequences and KV
+ * heads of the call; a head whose rows exceed cap counts as over budget):
+ *     lo = tau_lo, hi = tau_hi;  `iterations` times:  mid = 0.5f * (lo + hi) in fp32;
+ *     rows(mid) <= budget_rows ? lo = mid : hi = mid;   result = lo.
+ * tau_lo is assumed to meet the budget (-1.01 merges every chunk into one row and always does if
+ * anything can); it is not probed unless iterations is 0.  Every probe is a complete sc_gsc_merge on
+ * the caller's stream, the bracket lives in device memory and is moved by a small kernel between the
+ * probes: iterations + 1 merges, no host synchronisation.  The last merge runs at the result, so on
+ * completion Kc, Vc, counts, comp_lens, cluster_id hold exactly what sc_gsc_merge(tau = result) gives.
+ *
+ *   budget_rows     target total of merged rows, e.g. round(0.35 * Hkv * sum of seq_lens)
+ *   iterations      0..32 bisection steps (12 narrow [-1, 1] to 5e-4)
+ *   tau_out         device f32 [1]: the threshold found
+ *   rows_out        device i64 [1] or NULL: total rows at that threshold (-1 if a head overflowed cap);
+ *                   larger than budget_rows if even tau_lo does not meet the budget
+ *   ws              sc_gsc_merge_budget_workspace_bytes(B, Hkv, N_max, d) bytes
+ * All other arguments and errors as for sc_gsc_merge; additionally iterations out of range,
+ * tau_lo > tau_hi, negative budget_rows, NULL or misaligned tau_out.
+ */
+size_t sc_gsc_merge_budget_workspace_bytes(int B, int Hkv, int N_max, int d);
+sc_status sc_gsc_merge_budget(const void *K, const void *V, sc_dtype in_dtype,
+                              int64_t stride_b, int64_t stride_h, int64_t stride_n,
+                              const int32_t *seq_lens, const int32_t *offsets, int64_t offsets_stride_b,
+                              const int32_t *num_chunks,
+                              int B, int Hkv, int N_max, int d,
+                              int64_t budget_rows, float tau_lo, float tau_hi, int iterations,
+                              void *Kc, void *Vc, sc_dtype out_dtype, int cap,
+                              int32_t *counts, int32_t *comp_lens, int32_t *cluster_id,
+                              float *tau_out, int64_t *rows_out,
+                              void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
  * sc_multi_attn — Eq. 4 for several query rows at once (Sec. 2.4 states it for Q in R^{n x d}): every
  * query row attends to the whole merged cache of its KV head, no mask between the rows (they are all
  * later than the cache):

@@ -221,3 +221,26 @@ def multi_attn(Q, Kc, Vc, counts, comp_lens, scale: Optional[float] = None):
     outs = [decode_attn(Q[j], Kc, Vc, counts, comp_lens, scale) for j in range(Q.shape[0])]
     return np.stack([o for o, _ in outs]), np.stack([l for _, l in outs])
 
+
+# ------------------------------------------------- threshold for a cache budget (Sec. 3.1 reports at budgets)
+def tau_for_budget(rows_at, budget_rows: int, tau_lo: float, tau_hi: float, iterations: int):
+    """Largest threshold a bisection finds whose total number of merged rows stays within budget_rows.
+
+    rows_at(tau) -> total rows of all (sequence, head) problems at that threshold, or None if some
+    head does not fit its capacity.  The paper gives no rule from budget to threshold; this one is
+    the plain bisection on fp32 midpoints: lo is assumed to fit, `iterations` midpoints are probed,
+    a midpoint that fits becomes lo, one that does not becomes hi; the answer is lo.
+    Returns (tau float32, list of probed thresholds).
+    """
+    lo, hi = np.float32(tau_lo), np.float32(tau_hi)
+    probed = []
+    for _ in range(iterations):
+        mid = np.float32(0.5) * (lo + hi)
+        probed.append(float(mid))
+        r = rows_at(float(mid))
+        if r is not None and r <= budget_rows:
+            lo = mid
+        else:
+            hi = mid
+    return lo, probed
+

@@ -71,6 +71,11 @@ def load_library() -> ctypes.CDLL:
     lib.sc_multi_attn.restype = i32
     lib.sc_multi_attn.argtypes = [vp, i32, i32, vp, vp, i32, i32, vp, vp, i32, i32, i32, i32, f32,
                                   vp, i32, vp, vp, sz, vp]
+    lib.sc_gsc_merge_budget_workspace_bytes.restype = sz
+    lib.sc_gsc_merge_budget_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    lib.sc_gsc_merge_budget.restype = i32
+    lib.sc_gsc_merge_budget.argtypes = [vp, vp, i32, i64, i64, i64, vp, vp, i64, vp, i32, i32, i32, i32,
+                                        i64, f32, f32, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -82,6 +87,7 @@ EXPORTED = [
     "sc_decode_attn_workspace_bytes", "sc_decode_attn_init_workspace", "sc_decode_attn",
     "sc_decode_attn_tail", "sc_gsc_merge_append",
     "sc_multi_attn_workspace_bytes", "sc_multi_attn",
+    "sc_gsc_merge_budget_workspace_bytes", "sc_gsc_merge_budget",
 ]
 
 
@@ -290,4 +296,38 @@ def sc_multi_attn(Q, Kc, Vc, counts, comp_lens, scale: float = 0.0, O=None, lse=
                            workspace.ptr, workspace.nbytes, _stream())
     _check(st, "sc_multi_attn")
     return O, lse
+
+
+def sc_gsc_merge_budget(K, V, offsets, num_chunks, budget_rows: int, tau_lo: float = -1.01, tau_hi: float = 1.0,
+                        iterations: int = 12, seq_lens=None, cap: Optional[int] = None, out_dtype=None,
+                        want_cluster_id: bool = False, workspace: Optional[Workspace] = None):
+    """sc_gsc_merge at the largest threshold a bisection finds that keeps the total rows within budget_rows.
+
+    Returns (Kc, Vc, counts, comp_lens, cluster_id, tau [1] f32, rows [1] i64), all on the device.
+    """
+    torch = _torch()
+    lib = load_library()
+    _require_cuda(K, V, offsets, num_chunks, seq_lens)
+    if K.dim() != 4 or K.shape != V.shape or K.stride() != V.stride() or K.stride(3) != 1 or K.dtype != V.dtype:
+        raise SemantiCacheError("K and V must be [B, Hkv, N_max, d] with identical strides and dtype")
+    B, H, N, d = K.shape
+    cap = N if cap is None else int(cap)
+    out_dtype = K.dtype if out_dtype is None else out_dtype
+    dev = K.device
+    Kc = torch.empty((B, H, cap, d), dtype=out_dtype, device=dev)
+    Vc = torch.empty((B, H, cap, d), dtype=out_dtype, device=dev)
+    counts = torch.empty((B, H, cap), dtype=torch.int32, device=dev)
+    comp_lens = torch.empty((B, H), dtype=torch.int32, device=dev)
+    cluster_id = torch.full((B, H, N), -9, dtype=torch.int32, device=dev) if want_cluster_id else None
+    tau = torch.empty((1,), dtype=torch.float32, device=dev)
+    rows = torch.empty((1,), dtype=torch.int64, device=dev)
+    if workspace is None:
+        workspace = Workspace(lib.sc_gsc_merge_budget_workspace_bytes(B, H, N, d), dev)
+    st = lib.sc_gsc_merge_budget(_ptr(K), _ptr(V), _dtype_code(K), K.stride(0), K.stride(1), K.stride(2),
+                                 _ptr(seq_lens), _ptr(offsets), offsets.stride(0), _ptr(num_chunks), B, H, N, d,
+                                 int(budget_rows), float(tau_lo), float(tau_hi), int(iterations),
+                                 _ptr(Kc), _ptr(Vc), _dtype_code(Kc), cap, _ptr(counts), _ptr(comp_lens),
+                                 _ptr(cluster_id), _ptr(tau), _ptr(rows), workspace.ptr, workspace.nbytes, _stream())
+    _check(st, "sc_gsc_merge_budget")
+    return Kc, Vc, counts, comp_lens, cluster_id, tau, rows
 

@@ -104,11 +104,12 @@ size_t sc_gsc_merge_workspace_bytes(int B, int Hkv, int N_max, int d) {
     return gsc_merge_workspace_bytes(B, Hkv, N_max, d);
 }
 
-static sc_status gsc_common(const void *K, const void *V, sc_dtype in_dtype, int64_t stride_b, int64_t stride_h,
-                            int64_t stride_n, const int32_t *seq_lens, const int32_t *offsets, int64_t offsets_stride_b,
-                            const int32_t *num_chunks, int B, int Hkv, int N_max, int d, float tau, void *Kc, void *Vc,
-                            sc_dtype out_dtype, int cap, int32_t *counts, const int32_t *base_lens, bool append,
-                            int32_t *comp_lens, int32_t *cluster_id, void *ws, size_t ws_bytes, void *stream) {
+static sc_status gsc_check_and_fill(const void *K, const void *V, sc_dtype in_dtype, int64_t stride_b, int64_t stride_h,
+                                    int64_t stride_n, const int32_t *seq_lens, const int32_t *offsets,
+                                    int64_t offsets_stride_b, const int32_t *num_chunks, int B, int Hkv, int N_max, int d,
+                                    float tau, void *Kc, void *Vc, sc_dtype out_dtype, int cap, int32_t *counts,
+                                    const int32_t *base_lens, bool append, int32_t *comp_lens, int32_t *cluster_id,
+                                    void *ws, size_t ws_bytes, GscMergeArgs &a) {
     if (!K || !V || !offsets || !num_chunks || !Kc || !Vc || !counts || !comp_lens) return SC_ERR_INVALID_ARG;
     // every workgroup reads the old length while one of them files the new one
     if (append && (!base_lens || base_lens == comp_lens || !aligned4(base_lens))) return SC_ERR_INVALID_ARG;
@@ -127,7 +128,6 @@ static sc_status gsc_common(const void *K, const void *V, sc_dtype in_dtype, int
     const size_t need = gsc_merge_workspace_bytes(B, Hkv, N_max, d);
     if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SC_ERR_WORKSPACE;
 
-    GscMergeArgs a;
     a.K = K; a.V = V; a.in_dtype = static_cast<DType>(in_dtype);
     a.stride_b = stride_b; a.stride_h = stride_h; a.stride_n = stride_n;
     a.seq_lens = seq_lens; a.offsets = offsets; a.offsets_stride_b = offsets_stride_b; a.num_chunks = num_chunks;
@@ -135,6 +135,19 @@ static sc_status gsc_common(const void *K, const void *V, sc_dtype in_dtype, int
     a.Kc = Kc; a.Vc = Vc; a.out_dtype = static_cast<DType>(out_dtype); a.cap = cap;
     a.counts = counts; a.comp_lens = comp_lens; a.cluster_id = cluster_id; a.ws = ws;
     a.base_lens = append ? base_lens : nullptr;
+    return SC_OK;
+}
+
+static sc_status gsc_common(const void *K, const void *V, sc_dtype in_dtype, int64_t stride_b, int64_t stride_h,
+                            int64_t stride_n, const int32_t *seq_lens, const int32_t *offsets, int64_t offsets_stride_b,
+                            const int32_t *num_chunks, int B, int Hkv, int N_max, int d, float tau, void *Kc, void *Vc,
+                            sc_dtype out_dtype, int cap, int32_t *counts, const int32_t *base_lens, bool append,
+                            int32_t *comp_lens, int32_t *cluster_id, void *ws, size_t ws_bytes, void *stream) {
+    GscMergeArgs a;
+    const sc_status st = gsc_check_and_fill(K, V, in_dtype, stride_b, stride_h, stride_n, seq_lens, offsets, offsets_stride_b,
+                                            num_chunks, B, Hkv, N_max, d, tau, Kc, Vc, out_dtype, cap, counts, base_lens,
+                                            append, comp_lens, cluster_id, ws, ws_bytes, a);
+    if (st != SC_OK) return st;
     return runtime_status(launch_gsc_merge(a, static_cast<hipStream_t>(stream)));
 }
 
@@ -157,6 +170,34 @@ sc_status sc_gsc_merge_append(const void *K, const void *V, sc_dtype in_dtype, i
     return gsc_common(K, V, in_dtype, stride_b, stride_h, stride_n, seq_lens, offsets, offsets_stride_b, num_chunks, B, Hkv,
                       N_max, d, tau, Kc, Vc, out_dtype, cap, counts, base_lens, true, comp_lens, cluster_id, ws, ws_bytes,
                       stream);
+}
+
+size_t sc_gsc_merge_budget_workspace_bytes(int B, int Hkv, int N_max, int d) {
+    if (B <= 0 || Hkv <= 0 || N_max <= 0) return 0;
+    return align_up(gsc_merge_workspace_bytes(B, Hkv, N_max, d), 256) + gsc_budget_state_bytes();
+}
+
+sc_status sc_gsc_merge_budget(const void *K, const void *V, sc_dtype in_dtype, int64_t stride_b, int64_t stride_h,
+                              int64_t stride_n, const int32_t *seq_lens, const int32_t *offsets,
+                              int64_t offsets_stride_b, const int32_t *num_chunks, int B, int Hkv, int N_max, int d,
+                              int64_t budget_rows, float tau_lo, float tau_hi, int iterations, void *Kc, void *Vc,
+                              sc_dtype out_dtype, int cap, int32_t *counts, int32_t *comp_lens, int32_t *cluster_id,
+                              float *tau_out, int64_t *rows_out, void *ws, size_t ws_bytes, void *stream) {
+    if (!tau_out || !aligned4(tau_out) || (rows_out && (reinterpret_cast<uintptr_t>(rows_out) & 7u))) return SC_ERR_INVALID_ARG;
+    if (iterations < 0 || iterations > 32 || budget_rows < 0) return SC_ERR_INVALID_ARG;
+    if (tau_lo != tau_lo || tau_hi != tau_hi || tau_lo > tau_hi) return SC_ERR_INVALID_ARG;
+    if (B <= 0 || Hkv <= 0 || N_max <= 0) return SC_ERR_INVALID_ARG;
+    // everything else is checked exactly as for sc_gsc_merge (no launch happens on a failed check)
+    GscMergeArgs a;
+    const sc_status st = gsc_check_and_fill(K, V, in_dtype, stride_b, stride_h, stride_n, seq_lens, offsets, offsets_stride_b,
+                                            num_chunks, B, Hkv, N_max, d, tau_lo, Kc, Vc, out_dtype, cap, counts, nullptr,
+                                            false, comp_lens, cluster_id, ws, ws_bytes, a);
+    if (st != SC_OK) return st;
+    const size_t gsc_bytes = align_up(gsc_merge_workspace_bytes(B, Hkv, N_max, d), 256);
+    if (ws_bytes < gsc_bytes + gsc_budget_state_bytes()) return SC_ERR_WORKSPACE;
+    return runtime_status(launch_gsc_budget(a, (long long)budget_rows, tau_lo, tau_hi, iterations, tau_out,
+                                            reinterpret_cast<long long *>(rows_out),
+                                            reinterpret_cast<char *>(ws) + gsc_bytes, static_cast<hipStream_t>(stream)));
 }
 
 // ------------------------------------------------------------------------------------------------

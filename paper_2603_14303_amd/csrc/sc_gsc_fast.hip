@@ -558,7 +558,7 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
     TO *ktmp_c = reinterpret_cast<TO *>(p.ktmp) + bh * (int64_t)p.N_max * kFastD;
     TO *vtmp_c = reinterpret_cast<TO *>(p.vtmp) + bh * (int64_t)p.N_max * kFastD;
     const int64_t tmp_rows = p.N_max;
-    const float tau = p.tau;
+    const float tau = p.tau_dev ? *p.tau_dev : p.tau;
 #ifdef SC_GSC_TIMING
     // development builds only: timestamps go to the upper half of the value staging area, which a bf16
     // output never touches (the area is sized for fp32 output)

@@ -162,6 +162,7 @@ __global__ __launch_bounds__(kGscThreads) void gsc_assign_kernel(GscParams p) {
     n = n < 0 ? 0 : (n > p.N_max ? p.N_max : n);
     const int C = p.chunks_per_item;
     const int items = (M + C - 1) / C;
+    const float tau = p.tau_dev ? *p.tau_dev : p.tau;
     const int64_t bh = (int64_t)b * p.Hkv + h;
     const T *Kbh = reinterpret_cast<const T *>(p.K) + b * p.stride_b + h * p.stride_h;
     const int32_t *off = p.offsets + (int64_t)b * p.offsets_stride_b;
@@ -179,7 +180,7 @@ __global__ __launch_bounds__(kGscThreads) void gsc_assign_kernel(GscParams p) {
             const int start = __builtin_amdgcn_readfirstlane(s_off[idx]);
             const int l = __builtin_amdgcn_readfirstlane(s_off[idx + 1]) - 1 - start;
             int pc = 0;
-            if (l > 0) pc = gsc_chunk<T, D>(Kbh, p.stride_n, start, l, p.tau, cid_bh, seed_bh, lane);
+            if (l > 0) pc = gsc_chunk<T, D>(Kbh, p.stride_n, start, l, tau, cid_bh, seed_bh, lane);
             if (lane == 0) {
                 pcount_bh[m0 + idx] = pc;
                 const int delim = start + l;
@@ -416,6 +417,7 @@ hipError_t launch_gsc_merge(const GscMergeArgs &a, hipStream_t stream) {
     p.num_chunks = a.num_chunks;
     p.B = a.B; p.Hkv = a.Hkv; p.N_max = a.N_max;
     p.tau = a.tau;
+    p.tau_dev = a.tau_dev;
     p.Kc = a.Kc; p.Vc = a.Vc;
     p.out_is_bf16 = (a.out_dtype == DType::BF16) ? 1 : 0;
     p.cap = a.cap;

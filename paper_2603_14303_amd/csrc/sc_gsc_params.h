@@ -18,6 +18,7 @@ struct GscParams {
     const int32_t *num_chunks;
     int B, Hkv, N_max;
     float tau;
+    const float *tau_dev;   // if not NULL the threshold is read from device memory instead (budget search)
     void *Kc, *Vc;
     int out_is_bf16;
     int cap;

@@ -30,10 +30,16 @@ struct GscMergeArgs {
     int cap;
     int32_t *counts, *comp_lens, *cluster_id;
     const int32_t *base_lens = nullptr;   // append mode: rows already in the outputs, [B, Hkv]
+    const float *tau_dev = nullptr;       // threshold in device memory (overrides tau)
     void *ws;
 };
 size_t gsc_merge_workspace_bytes(int B, int Hkv, int N_max, int d);
 hipError_t launch_gsc_merge(const GscMergeArgs &a, hipStream_t stream);
+
+// ---- sc_gsc_merge_budget: bisection on the threshold, all on the device
+size_t gsc_budget_state_bytes();
+hipError_t launch_gsc_budget(GscMergeArgs a, long long budget_rows, float tau_lo, float tau_hi, int iterations,
+                             float *tau_out, long long *rows_out, void *state, hipStream_t stream);
 
 // ---- sc_decode_attn
 struct DecodeArgs {

@@ -185,6 +185,28 @@ def test_multi_attn_rejects_bad_arguments(lib):
     assert call(ws=None) == 4 and call(wsb=need - 1) == 4
 
 
+def test_gsc_merge_budget_rejects_bad_arguments(lib):
+    f = lib.sc_gsc_merge_budget
+    need = lib.sc_gsc_merge_budget_workspace_bytes(1, 2, 1024, 64)
+    assert need > lib.sc_gsc_merge_workspace_bytes(1, 2, 1024, 64)
+    ok = dict(K=FAKE, V=FAKE, idt=0, sb=2 * 1024 * 64, sh=1024 * 64, sn=64, lens=None, off=FAKE, ostride=1026,
+              nch=FAKE, B=1, H=2, N=1024, d=64, budget=700, lo=-1.01, hi=1.0, it=12, Kc=FAKE, Vc=FAKE, odt=0, cap=1024,
+              counts=FAKE, clens=FAKE, cid=None, tau=FAKE, rows=FAKE + 8, ws=FAKE, wsb=need)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["K"], a["V"], a["idt"], a["sb"], a["sh"], a["sn"], a["lens"], a["off"], a["ostride"], a["nch"],
+                 a["B"], a["H"], a["N"], a["d"], a["budget"], a["lo"], a["hi"], a["it"], a["Kc"], a["Vc"], a["odt"],
+                 a["cap"], a["counts"], a["clens"], a["cid"], a["tau"], a["rows"], a["ws"], a["wsb"], None)
+    for k in ("K", "V", "off", "nch", "Kc", "Vc", "counts", "clens", "tau"):
+        assert call(**{k: None}) == 1, k
+    assert call(it=-1) == 1 and call(it=33) == 1 and call(budget=-1) == 1
+    assert call(lo=0.5, hi=0.25) == 1 and call(lo=float("nan")) == 1
+    assert call(rows=FAKE + 4) == 1 and call(tau=FAKE + 2) == 1
+    assert call(cap=0) == 3 and call(d=96) == 2
+    assert call(ws=None) == 4 and call(wsb=need - 1) == 4
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
     with pytest.raises(sc.SemantiCacheError):

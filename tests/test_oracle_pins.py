@@ -426,6 +426,45 @@ def test_multi_query_attention_is_the_matrix_form_of_eq4():
             assert np.allclose(L[:, b, hq], logsumexp(Z, axis=1), atol=1e-12)
 
 
+def test_budget_threshold_brackets_the_budget():
+    # on real compression counts: the threshold found fits the budget, and raising it by the final
+    # width of the bracket no longer does (when the bracket started valid); a brute-force scan of a
+    # fine grid agrees on which side of the result fits
+    w = wl.get_workload("tiny")
+    mask = wl.delimiter_mask(w, 0)
+    n = len(mask)
+    off = oracle.segment(mask)
+    KV = [wl.keys_values(w, 0, 0, h, mask, n) for h in range(2)]
+    cache = {}
+
+    def rows_at(tau):
+        if tau not in cache:
+            cache[tau] = sum(oracle.compress_head(K, V, off, tau)["n_rows"] for K, V in KV)
+        return cache[tau]
+
+    grid = np.linspace(-1.0, 1.0, 81)
+    counts = [rows_at(float(t)) for t in grid]
+    assert all(a <= b for a, b in zip(counts, counts[1:])), "rows must not shrink as the threshold rises (on this data)"
+    total = 2 * n
+    for frac in (0.2, 0.35, 0.5, 0.9):
+        budget = int(round(frac * total))
+        tau, probed = oracle.tau_for_budget(rows_at, budget, -1.01, 1.0, 14)
+        assert len(probed) == 14 and probed[0] == float(np.float32(0.5) * (np.float32(-1.01) + np.float32(1.0)))
+        if rows_at(-1.01) > budget:
+            assert tau == np.float32(-1.01)
+            continue
+        assert rows_at(float(tau)) <= budget
+        width = 2.01 / 2 ** 14
+        assert rows_at(min(1.0, float(tau) + 1.01 * width)) > budget or float(tau) + 1.01 * width >= 1.0
+        for t, c in zip(grid, counts):          # the grid agrees wherever it is clear of the bracket
+            if t <= float(tau):
+                assert c <= budget
+            elif t > float(tau) + 1.01 * width:
+                assert c > budget
+    # no iterations: lo comes back unprobed
+    assert oracle.tau_for_budget(rows_at, 5, 0.25, 0.75, 0)[0] == np.float32(0.25)
+
+
 # ------------------------------------------------------------------ end to end
 def test_pipeline_at_tau_one_is_full_cache_attention():
     w = wl.get_workload("tiny")
