@@ -244,3 +244,32 @@ def tau_for_budget(rows_at, budget_rows: int, tau_lo: float, tau_hi: float, iter
             hi = mid
     return lo, probed
 
+
+def multi_attn_tail(Q, Kc, Vc, counts, comp_lens, Kt, Vt, tail_lens, causal: bool, scale: Optional[float] = None):
+    """multi_attn over the merged cache followed by an uncompressed tail (rows of size 1).
+
+    Q [nq, B, Hq, d]; Kt, Vt [B, Hkv, tail_cap, d]; tail_lens [B].  With causal, the last nq tail rows
+    of a sequence are the query rows' own tokens: query j sees the merged rows and the tail rows
+    0 .. tail_lens[b] - nq + j (itself included, none if that is negative); without it every query
+    row sees the whole tail.
+    """
+    Q = np.asarray(Q)
+    nq, B, Hq, d = Q.shape
+    Hkv = Kc.shape[1]
+    G = Hq // Hkv
+    O = np.zeros((nq, B, Hq, d), dtype=np.float64)
+    L = np.zeros((nq, B, Hq), dtype=np.float64)
+    for b in range(B):
+        t = int(tail_lens[b])
+        for h in range(Hkv):
+            nc = int(comp_lens[b, h])
+            k_all = np.concatenate([_f64(Kc[b, h, :nc]), _f64(Kt[b, h, :t])], axis=0)
+            v_all = np.concatenate([_f64(Vc[b, h, :nc]), _f64(Vt[b, h, :t])], axis=0)
+            s_all = np.concatenate([np.asarray(counts[b, h, :nc], dtype=np.int32), np.ones((t,), dtype=np.int32)])
+            for j in range(nq):
+                seen = max(0, t - nq + 1 + j) if causal else t
+                for g in range(G):
+                    hq = h * G + g
+                    O[j, b, hq], L[j, b, hq] = decode_head(Q[j, b, hq], k_all, v_all, s_all, nc + seen, scale)
+    return O, L
+

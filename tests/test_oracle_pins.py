@@ -426,6 +426,39 @@ def test_multi_query_attention_is_the_matrix_form_of_eq4():
             assert np.allclose(L[:, b, hq], logsumexp(Z, axis=1), atol=1e-12)
 
 
+def test_multi_query_tail_with_causal_mask_is_masked_softmax():
+    # the matrix form with an explicit mask: -inf above the diagonal of the queries' own tokens
+    rng = np.random.default_rng(31)
+    nq, B, Hkv, G, d, cap, tcap = 4, 2, 2, 2, 8, 6, 7
+    Q = rng.standard_normal((nq, B, Hkv * G, d))
+    Kc, Vc = rng.standard_normal((B, Hkv, cap, d)), rng.standard_normal((B, Hkv, cap, d))
+    Kt, Vt = rng.standard_normal((B, Hkv, tcap, d)), rng.standard_normal((B, Hkv, tcap, d))
+    counts = rng.integers(1, 5, (B, Hkv, cap)).astype(np.int32)
+    lens = np.array([[6, 2], [0, 5]], dtype=np.int32)
+    tails = np.array([7, 2], dtype=np.int32)          # the second tail is shorter than the query block
+    for causal in (True, False):
+        O, L = oracle.multi_attn_tail(Q, Kc, Vc, counts, lens, Kt, Vt, tails, causal)
+        for b in range(B):
+            for hq in range(Hkv * G):
+                h, n, t = hq // G, lens[b, hq // G], tails[b]
+                Z = np.concatenate([Q[:, b, hq] @ Kc[b, h, :n].T / np.sqrt(d) + np.log(counts[b, h, :n])[None, :],
+                                    Q[:, b, hq] @ Kt[b, h, :t].T / np.sqrt(d)], axis=1)
+                if causal:
+                    for j in range(nq):
+                        Z[j, n + max(0, t - nq + 1 + j):] = -np.inf
+                VV = np.concatenate([Vc[b, h, :n], Vt[b, h, :t]])
+                for j in range(nq):
+                    if np.isneginf(Z[j]).all():
+                        assert (O[j, b, hq] == 0).all() and np.isneginf(L[j, b, hq])
+                    else:
+                        assert np.allclose(O[j, b, hq], softmax(Z[j]) @ VV, atol=1e-13)
+                        assert abs(L[j, b, hq] - logsumexp(Z[j])) < 1e-12
+    # without a mask and with an empty tail it is multi_attn
+    O0, L0 = oracle.multi_attn(Q, Kc, Vc, counts, lens)
+    O1, L1 = oracle.multi_attn_tail(Q, Kc, Vc, counts, lens, Kt, Vt, np.zeros(B, np.int32), False)
+    assert np.array_equal(O0, O1) and np.array_equal(L0, L1)
+
+
 def test_budget_threshold_brackets_the_budget():
     # on real compression counts: the threshold found fits the budget, and raising it by the final
     # width of the bracket no longer does (when the bracket started valid); a brute-force scan of a
