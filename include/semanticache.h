@@ -256,11 +256,26 @@ sc_status sc_gsc_merge_budget(const void *K, const void *V, sc_dtype in_dtype,
  *   O               device [nq, B, Hq, d] of o_dtype;  lse  device f32 [nq, B, Hq] or NULL
  *   ws              sc_multi_attn_workspace_bytes(B, Hq, Hkv, nq, cap, d) bytes; carries no state
  *
- * bf16 queries and cache with d = 128 run on the matrix cores (probabilities are rounded to bf16
- * before they multiply the values, fp32 accumulation); every other combination goes row by row through
+ * bf16 queries and cache with d = 128 run on the matrix cores (probabilities enter the second product
+ * as two bf16 parts, i.e. with 16 significant bits; fp32 accumulation); every other combination goes row by row through
  * the sc_decode_attn kernels.  Host errors as for sc_decode_attn, plus nq out of range.
+ *
+ * sc_multi_attn_tail — the same over the merged rows followed by the first tail_lens[b] rows of an
+ * uncompressed tail (size 1, as for sc_decode_attn_tail).  With causal != 0 the last nq tail rows of a
+ * sequence are the query rows' own tokens and query j sees the tail rows 0 .. tail_lens[b] - nq + j
+ * (itself included; none if that is negative): the step that verifies nq speculative tokens, or a
+ * chunk of prefill behind a compressed cache.  causal is supported on the matrix-core path only
+ * (bf16, d = 128; SC_ERR_UNSUPPORTED otherwise).  Workspace: sc_multi_attn_workspace_bytes with
+ * cap + tail_cap in place of cap.
  */
 size_t sc_multi_attn_workspace_bytes(int B, int Hq, int Hkv, int nq, int cap, int d);
+sc_status sc_multi_attn_tail(const void *Q, sc_dtype q_dtype, int nq,
+                             const void *Kc, const void *Vc, sc_dtype kv_dtype, int cap,
+                             const int32_t *counts, const int32_t *comp_lens,
+                             const void *Kt, const void *Vt, int tail_cap, const int32_t *tail_lens, int causal,
+                             int B, int Hq, int Hkv, int d, float scale,
+                             void *O, sc_dtype o_dtype, float *lse,
+                             void *ws, size_t ws_bytes, void *stream);
 sc_status sc_multi_attn(const void *Q, sc_dtype q_dtype, int nq,
                         const void *Kc, const void *Vc, sc_dtype kv_dtype, int cap,
                         const int32_t *counts, const int32_t *comp_lens,

@@ -71,6 +71,9 @@ def load_library() -> ctypes.CDLL:
     lib.sc_multi_attn.restype = i32
     lib.sc_multi_attn.argtypes = [vp, i32, i32, vp, vp, i32, i32, vp, vp, i32, i32, i32, i32, f32,
                                   vp, i32, vp, vp, sz, vp]
+    lib.sc_multi_attn_tail.restype = i32
+    lib.sc_multi_attn_tail.argtypes = [vp, i32, i32, vp, vp, i32, i32, vp, vp, vp, vp, i32, vp, i32, i32, i32, i32, i32,
+                                       f32, vp, i32, vp, vp, sz, vp]
     lib.sc_gsc_merge_budget_workspace_bytes.restype = sz
     lib.sc_gsc_merge_budget_workspace_bytes.argtypes = [i32, i32, i32, i32]
     lib.sc_gsc_merge_budget.restype = i32
@@ -86,7 +89,7 @@ EXPORTED = [
     "sc_gsc_merge_workspace_bytes", "sc_gsc_merge",
     "sc_decode_attn_workspace_bytes", "sc_decode_attn_init_workspace", "sc_decode_attn",
     "sc_decode_attn_tail", "sc_gsc_merge_append",
-    "sc_multi_attn_workspace_bytes", "sc_multi_attn",
+    "sc_multi_attn_workspace_bytes", "sc_multi_attn", "sc_multi_attn_tail",
     "sc_gsc_merge_budget_workspace_bytes", "sc_gsc_merge_budget",
 ]
 
@@ -275,8 +278,12 @@ def sc_decode_attn(Q, Kc, Vc, counts, comp_lens, scale: float = 0.0, O=None, lse
 
 
 def sc_multi_attn(Q, Kc, Vc, counts, comp_lens, scale: float = 0.0, O=None, lse=None, want_lse: bool = False,
-                  workspace: Optional[Workspace] = None):
-    """Q [nq, B, Hq, d] -> (O [nq, B, Hq, d], lse [nq, B, Hq]): every query row over the whole merged cache."""
+                  workspace: Optional[Workspace] = None, Kt=None, Vt=None, tail_lens=None, causal: bool = False):
+    """Q [nq, B, Hq, d] -> (O [nq, B, Hq, d], lse [nq, B, Hq]): every query row over the whole merged cache.
+
+    With Kt, Vt [B, Hkv, tail_cap, d] and tail_lens [B] (sc_multi_attn_tail) an uncompressed tail follows the
+    merged rows; with causal the last nq tail rows are the query rows' own tokens.
+    """
     torch = _torch()
     lib = load_library()
     _require_cuda(Q, Kc, Vc, counts, comp_lens, O, lse)
@@ -289,8 +296,22 @@ def sc_multi_attn(Q, Kc, Vc, counts, comp_lens, scale: float = 0.0, O=None, lse=
         O = torch.empty((nq, B, Hq, d), dtype=Q.dtype, device=Q.device)
     if lse is None and want_lse:
         lse = torch.empty((nq, B, Hq), dtype=torch.float32, device=Q.device)
+    tcap = int(Kt.shape[2]) if Kt is not None else 0
     if workspace is None:
-        workspace = Workspace(lib.sc_multi_attn_workspace_bytes(B, Hq, Hkv, nq, cap, d), Q.device)
+        workspace = Workspace(lib.sc_multi_attn_workspace_bytes(B, Hq, Hkv, nq, cap + tcap, d), Q.device)
+    if Kt is not None:
+        _require_cuda(Kt, Vt, tail_lens)
+        for t in (Kt, Vt, tail_lens):
+            if not t.is_contiguous():
+                raise SemantiCacheError("inputs must be contiguous")
+        if Kt.shape != Vt.shape or Kt.dtype != Kc.dtype or Kt.shape[:2] != Kc.shape[:2] or Kt.shape[3] != d:
+            raise SemantiCacheError("Kt, Vt must be [B, Hkv, tail_cap, d] of the cache's dtype")
+        st = lib.sc_multi_attn_tail(_ptr(Q), _dtype_code(Q), nq, _ptr(Kc), _ptr(Vc), _dtype_code(Kc), cap, _ptr(counts),
+                                    _ptr(comp_lens), _ptr(Kt), _ptr(Vt), tcap, _ptr(tail_lens), int(bool(causal)),
+                                    B, Hq, Hkv, d, float(scale), _ptr(O), _dtype_code(O), _ptr(lse),
+                                    workspace.ptr, workspace.nbytes, _stream())
+        _check(st, "sc_multi_attn_tail")
+        return O, lse
     st = lib.sc_multi_attn(_ptr(Q), _dtype_code(Q), nq, _ptr(Kc), _ptr(Vc), _dtype_code(Kc), cap, _ptr(counts),
                            _ptr(comp_lens), B, Hq, Hkv, d, float(scale), _ptr(O), _dtype_code(O), _ptr(lse),
                            workspace.ptr, workspace.nbytes, _stream())

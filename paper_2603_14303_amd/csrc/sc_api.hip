@@ -266,12 +266,18 @@ size_t sc_multi_attn_workspace_bytes(int B, int Hq, int Hkv, int nq, int cap, in
     return multi_workspace_bytes(B, Hq, Hkv, nq, cap, d);
 }
 
-sc_status sc_multi_attn(const void *Q, sc_dtype q_dtype, int nq, const void *Kc, const void *Vc, sc_dtype kv_dtype,
-                        int cap, const int32_t *counts, const int32_t *comp_lens, int B, int Hq, int Hkv, int d,
-                        float scale, void *O, sc_dtype o_dtype, float *lse, void *ws, size_t ws_bytes, void *stream) {
+static sc_status multi_common(const void *Q, sc_dtype q_dtype, int nq, const void *Kc, const void *Vc, sc_dtype kv_dtype,
+                              int cap, const int32_t *counts, const int32_t *comp_lens, const void *Kt, const void *Vt,
+                              int tail_cap, const int32_t *tail_lens, int causal, bool with_tail, int B, int Hq, int Hkv,
+                              int d, float scale, void *O, sc_dtype o_dtype, float *lse, void *ws, size_t ws_bytes,
+                              void *stream) {
     if (!Q || !Kc || !Vc || !counts || !comp_lens || !O) return SC_ERR_INVALID_ARG;
+    if (with_tail && (!Kt || !Vt || !tail_lens || !aligned16(Kt) || !aligned16(Vt) || !aligned4(tail_lens))) return SC_ERR_INVALID_ARG;
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || nq <= 0) return SC_ERR_INVALID_ARG;
-    if (cap <= 0) return SC_ERR_CAPACITY;
+    if (cap <= 0 || (with_tail && tail_cap <= 0)) return SC_ERR_CAPACITY;
+    if (with_tail && (int64_t)cap + tail_cap > (1 << 30)) return SC_ERR_CAPACITY;
+    // the mask between the query rows exists on the matrix-core path only
+    if (with_tail && causal && !(d == 128 && q_dtype == SC_BF16 && kv_dtype == SC_BF16)) return SC_ERR_UNSUPPORTED;
     if (!dtype_ok(q_dtype) || !dtype_ok(kv_dtype) || !dtype_ok(o_dtype)) return SC_ERR_UNSUPPORTED;
     if (d != 64 && d != 128) return SC_ERR_UNSUPPORTED;
     if (Hq % Hkv) return SC_ERR_UNSUPPORTED;
@@ -280,17 +286,33 @@ sc_status sc_multi_attn(const void *Q, sc_dtype q_dtype, int nq, const void *Kc,
     if (!aligned16(Q) || !aligned16(Kc) || !aligned16(Vc) || !aligned4(O)) return SC_ERR_INVALID_ARG;
     if (!aligned4(counts) || !aligned4(comp_lens) || (lse && !aligned4(lse))) return SC_ERR_INVALID_ARG;
     if (scale != scale) return SC_ERR_INVALID_ARG;
-    const size_t need = multi_workspace_bytes(B, Hq, Hkv, nq, cap, d);
+    const size_t need = multi_workspace_bytes(B, Hq, Hkv, nq, cap + (with_tail ? tail_cap : 0), d);
     if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SC_ERR_WORKSPACE;
 
     MultiArgs a;
     a.Q = Q; a.q_dtype = static_cast<DType>(q_dtype); a.nq = nq;
     a.Kc = Kc; a.Vc = Vc; a.kv_dtype = static_cast<DType>(kv_dtype); a.cap = cap;
     a.counts = counts; a.comp_lens = comp_lens;
+    if (with_tail) { a.Kt = Kt; a.Vt = Vt; a.tail_lens = tail_lens; a.tail_cap = tail_cap; a.causal = causal ? 1 : 0; }
     a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.d = d;
     a.scale = (scale == 0.f) ? 1.0f / sqrtf((float)d) : scale;
     a.O = O; a.o_dtype = static_cast<DType>(o_dtype); a.lse = lse; a.ws = ws;
     return runtime_status(launch_multi(a, static_cast<hipStream_t>(stream)));
+}
+
+sc_status sc_multi_attn(const void *Q, sc_dtype q_dtype, int nq, const void *Kc, const void *Vc, sc_dtype kv_dtype,
+                        int cap, const int32_t *counts, const int32_t *comp_lens, int B, int Hq, int Hkv, int d,
+                        float scale, void *O, sc_dtype o_dtype, float *lse, void *ws, size_t ws_bytes, void *stream) {
+    return multi_common(Q, q_dtype, nq, Kc, Vc, kv_dtype, cap, counts, comp_lens, nullptr, nullptr, 0, nullptr, 0, false, B,
+                        Hq, Hkv, d, scale, O, o_dtype, lse, ws, ws_bytes, stream);
+}
+
+sc_status sc_multi_attn_tail(const void *Q, sc_dtype q_dtype, int nq, const void *Kc, const void *Vc, sc_dtype kv_dtype,
+                             int cap, const int32_t *counts, const int32_t *comp_lens, const void *Kt, const void *Vt,
+                             int tail_cap, const int32_t *tail_lens, int causal, int B, int Hq, int Hkv, int d,
+                             float scale, void *O, sc_dtype o_dtype, float *lse, void *ws, size_t ws_bytes, void *stream) {
+    return multi_common(Q, q_dtype, nq, Kc, Vc, kv_dtype, cap, counts, comp_lens, Kt, Vt, tail_cap, tail_lens, causal, true,
+                        B, Hq, Hkv, d, scale, O, o_dtype, lse, ws, ws_bytes, stream);
 }
 
 }  // extern "C"

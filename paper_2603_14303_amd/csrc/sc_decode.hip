@@ -666,7 +666,8 @@ size_t decode_workspace_bytes(int B, int Hq, int Hkv, int cap, int d) {
     const int G = Hq / Hkv;
     // sized for the largest split count the tuning knob may take, so the knob never invalidates a workspace
     const size_t split_k = align_up((size_t)B * Hkv * kDecMaxSplits * G * (d + kPartPad) * 4, 256);
-    const size_t mfma = (d == 128) ? multi_fast_workspace_bytes(B, Hq, Hkv, 1, cap) : 0;   // see launch_decode
+    // (see launch_decode; sized for any number of rows, the tail's capacity is not known here)
+    const size_t mfma = (d == 128) ? multi_fast_workspace_bytes(B, Hq, Hkv, 1, 1 << 30) : 0;
     return decode_workspace_state_bytes(B, Hkv) + (split_k > mfma ? split_k : mfma);
 }
 
@@ -711,12 +712,13 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream) {
     // issue-bound (0.36-0.46 of peak bandwidth at G = 7); the matrix-core kernel for blocks of query
     // rows treats the G heads as one 16-row tile and streams faster there.  Its partials go behind the
     // flags, which it neither needs nor touches.
-    if (a.kv_dtype == DType::BF16 && a.q_dtype == DType::BF16 && a.d == 128 && !a.Kt &&
+    if (a.kv_dtype == DType::BF16 && a.q_dtype == DType::BF16 && a.d == 128 &&
         a.Hq / a.Hkv >= tuning().decode_mfma_min_group) {
         MultiArgs m;
         m.Q = a.Q; m.q_dtype = a.q_dtype; m.nq = 1;
         m.Kc = a.Kc; m.Vc = a.Vc; m.kv_dtype = a.kv_dtype; m.cap = a.cap;
         m.counts = a.counts; m.comp_lens = a.comp_lens;
+        m.Kt = a.Kt; m.Vt = a.Vt; m.tail_lens = a.tail_lens; m.tail_cap = a.tail_cap;
         m.B = a.B; m.Hq = a.Hq; m.Hkv = a.Hkv; m.d = a.d;
         m.scale = a.scale;
         m.O = a.O; m.o_dtype = a.o_dtype; m.lse = a.lse;

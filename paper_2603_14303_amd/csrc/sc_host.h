@@ -73,6 +73,10 @@ struct MultiArgs {
     DType kv_dtype;
     int cap;
     const int32_t *counts, *comp_lens;
+    const void *Kt = nullptr, *Vt = nullptr;   // uncompressed tail [B, Hkv, tail_cap, d], or none
+    const int32_t *tail_lens = nullptr;
+    int tail_cap = 0;
+    int causal = 0;           // the last nq tail rows are the query rows' own tokens
     int B, Hq, Hkv, d;
     float scale;
     void *O;                  // [nq, B, Hq, d]

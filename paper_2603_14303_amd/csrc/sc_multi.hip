@@ -12,7 +12,7 @@
 //     layout of the second product, so the probabilities never move between lanes.
 //   * scale, + log2(size) bias, online softmax per query row (exp2 domain): in-lane over the lane's
 //     cache rows, then over the four lane groups with two row swaps.
-//   * O += P V with the same MFMA, P rounded to bf16 (the running sum adds the rounded values), V rows
+//   * O += P V with the same MFMA; P enters as two bf16 parts (leading part + remainder, two products), V rows
 //     loaded 16 bytes per lane and regrouped with v_perm into the B operand (column 8c + j on lane c).
 // The four wavefronts fold through LDS, the workgroup writes one partial (acc[128], m, l) per query
 // row, and a second small kernel folds the splits.  Two launches instead of a hand-over inside the
@@ -43,6 +43,9 @@ struct MqParams {
     const bf16_t *Q;          // [nq, B, Hq, 128]
     const bf16_t *Kc, *Vc;    // [B, Hkv, cap, 128]
     const int32_t *counts, *comp_lens;
+    const bf16_t *Kt, *Vt;    // uncompressed tail [B, Hkv, tail_cap, 128], or NULL
+    const int32_t *tail_lens; // [B]
+    int tail_cap, causal;     // causal: the last nq tail rows are the query rows' own tokens
     int nq, cap, B, Hq, Hkv, G;
     float scale_log2;
     float *part;              // [B*Hkv*row_blocks][max_splits][32][kMqPart]
@@ -76,8 +79,10 @@ __device__ __forceinline__ float mq_rows_sum(float x) {
 }
 __device__ __forceinline__ float mq_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// QT: MFMA tiles of query rows per workgroup (1 or 2)
-template <int QT>
+// QT: MFMA tiles of query rows per workgroup (1 or 2).  TAIL: the rows of a (sequence, KV head) are its
+// merged rows followed by the first tail_lens[b] rows of the tail (size 1); with `causal` query j sees the
+// tail rows up to its own token, tail_lens[b] - nq + j.
+template <int QT, bool TAIL>
 __global__ __launch_bounds__(kMqThreads, QT == 1 ? 2 : 1) void multi_attn_kernel(MqParams p) {
     constexpr int kRows = 16 * QT;
     __shared__ __attribute__((aligned(16))) float s_acc[kRows * kMqD];
@@ -92,7 +97,9 @@ __global__ __launch_bounds__(kMqThreads, QT == 1 ? 2 : 1) void multi_attn_kernel
     const int c = lane & 15, kq = lane >> 4;
     const int64_t bh = (int64_t)b * p.Hkv + h;
     // (made scalar explicitly: the row loop below holds wave-wide operations and must not diverge)
-    const int rows_total = __builtin_amdgcn_readfirstlane(min(max(p.comp_lens[bh], 0), p.cap));
+    const int rows_c = __builtin_amdgcn_readfirstlane(min(max(p.comp_lens[bh], 0), p.cap));
+    const int rows_t = TAIL ? __builtin_amdgcn_readfirstlane(min(max(p.tail_lens[b], 0), p.tail_cap)) : 0;
+    const int rows_total = rows_c + rows_t;
     const int S = mq_splits_for(rows_total, p.max_splits, p.min_rows);
     if (split >= S) return;
     int per = (rows_total + S - 1) / S;
@@ -102,9 +109,12 @@ __global__ __launch_bounds__(kMqThreads, QT == 1 ? 2 : 1) void multi_attn_kernel
     const bf16_t *Kbh = p.Kc + bh * (int64_t)p.cap * kMqD;
     const bf16_t *Vbh = p.Vc + bh * (int64_t)p.cap * kMqD;
     const int32_t *cnt_bh = p.counts + bh * (int64_t)p.cap;
+    const bf16_t *Ktbh = TAIL ? p.Kt + bh * (int64_t)p.tail_cap * kMqD : nullptr;
+    const bf16_t *Vtbh = TAIL ? p.Vt + bh * (int64_t)p.tail_cap * kMqD : nullptr;
 
     // query rows of the block as B operands: lane (c, kq) holds pieces kq, kq + 4, kq + 8, kq + 12 of row c
     uint4 qop[QT][4];
+    int limit[QT];                             // rows [0, limit) are visible to query row (qt, c)
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
         const int R = rb * kRows + qt * 16 + c;
@@ -115,6 +125,7 @@ __global__ __launch_bounds__(kMqThreads, QT == 1 ? 2 : 1) void multi_attn_kernel
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj)
             qop[qt][jj] = valid ? *reinterpret_cast<const uint4 *>(qp + 8 * (kq + 4 * jj)) : make_uint4(0, 0, 0, 0);
+        limit[qt] = rows_c + ((TAIL && p.causal) ? max(0, rows_t - p.nq + 1 + j) : rows_t);
     }
 
     float m_run[QT];   // per query row (qt, c), identical on the four lane groups
@@ -140,18 +151,27 @@ __global__ __launch_bounds__(kMqThreads, QT == 1 ? 2 : 1) void multi_attn_kernel
             const int krow = row0 + c;
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj)
-                x.kop[t][jj] = (krow < r1) ? *reinterpret_cast<const uint4 *>(Kbh + (int64_t)krow * kMqD + 8 * (kq + 4 * jj))
-                                           : make_uint4(0, 0, 0, 0);
+                x.kop[t][jj] = (krow >= r1) ? make_uint4(0, 0, 0, 0)
+                               : (TAIL && krow >= rows_c)
+                                     ? *reinterpret_cast<const uint4 *>(Ktbh + (int64_t)(krow - rows_c) * kMqD + 8 * (kq + 4 * jj))
+                                     : *reinterpret_cast<const uint4 *>(Kbh + (int64_t)krow * kMqD + 8 * (kq + 4 * jj));
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int vrow = row0 + 4 * kq + i;
-                x.vr[t][i] = (vrow < r1) ? *reinterpret_cast<const uint4 *>(Vbh + (int64_t)vrow * kMqD + 8 * c)
-                                         : make_uint4(0, 0, 0, 0);
-                x.cnt[t][i] = (vrow < r1) ? cnt_bh[vrow] : 0;
+                if (vrow >= r1) {
+                    x.vr[t][i] = make_uint4(0, 0, 0, 0);
+                    x.cnt[t][i] = 0;
+                } else if (TAIL && vrow >= rows_c) {
+                    x.vr[t][i] = *reinterpret_cast<const uint4 *>(Vtbh + (int64_t)(vrow - rows_c) * kMqD + 8 * c);
+                    x.cnt[t][i] = 1;
+                } else {
+                    x.vr[t][i] = *reinterpret_cast<const uint4 *>(Vbh + (int64_t)vrow * kMqD + 8 * c);
+                    x.cnt[t][i] = cnt_bh[vrow];
+                }
             }
         }
     };
-    auto compute_step = [&](const StepRegs &x) {
+    auto compute_step = [&](const StepRegs &x, int base) {
         const auto &kop = x.kop;
         const auto &vr = x.vr;
         const auto &cnt = x.cnt;
@@ -171,10 +191,11 @@ __global__ __launch_bounds__(kMqThreads, QT == 1 ? 2 : 1) void multi_attn_kernel
                 }
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    z[t][qt][i] = (cnt[t][i] > 0) ? fmaf(s[i], p.scale_log2, __log2f((float)cnt[t][i])) : -INFINITY;
+                    z[t][qt][i] = (cnt[t][i] > 0 && (!TAIL || base + 16 * t + 4 * kq + i < limit[qt]))
+                                      ? fmaf(s[i], p.scale_log2, __log2f((float)cnt[t][i])) : -INFINITY;
             }
         // ---- online softmax per query row
-        mq_short4 pa[2][QT];
+        mq_short4 pa[2][QT], pb[2][QT];   // probabilities as bf16 pairs: leading part and remainder
         float alpha[QT];
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
@@ -191,10 +212,15 @@ __global__ __launch_bounds__(kMqThreads, QT == 1 ? 2 : 1) void multi_attn_kernel
             float psum = 0.f;
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
-                const uint32_t p01 = pack_bf16x2(mq_exp2(z[t][qt][0] - m_safe), mq_exp2(z[t][qt][1] - m_safe));
-                const uint32_t p23 = pack_bf16x2(mq_exp2(z[t][qt][2] - m_safe), mq_exp2(z[t][qt][3] - m_safe));
-                psum += (bf16_lo(p01) + bf16_hi(p01)) + (bf16_lo(p23) + bf16_hi(p23));
+                // p = hi + lo with both parts bf16: two products instead of one keep 16 bits of every weight
+                const float e0 = mq_exp2(z[t][qt][0] - m_safe), e1 = mq_exp2(z[t][qt][1] - m_safe);
+                const float e2 = mq_exp2(z[t][qt][2] - m_safe), e3 = mq_exp2(z[t][qt][3] - m_safe);
+                const uint32_t p01 = pack_bf16x2(e0, e1), p23 = pack_bf16x2(e2, e3);
+                const uint32_t r01 = pack_bf16x2(e0 - bf16_lo(p01), e1 - bf16_hi(p01));
+                const uint32_t r23 = pack_bf16x2(e2 - bf16_lo(p23), e3 - bf16_hi(p23));
+                psum += (e0 + e1) + (e2 + e3);
                 pa[t][qt] = mq_op(p01, p23);
+                pb[t][qt] = mq_op(r01, r23);
             }
             l_run[qt] = fmaf(l_run[qt], alpha[qt], psum);
         }
@@ -224,7 +250,10 @@ __global__ __launch_bounds__(kMqThreads, QT == 1 ? 2 : 1) void multi_attn_kernel
                 const mq_short4 bb = mq_op(lo, hi);
 #pragma unroll
                 for (int qt = 0; qt < QT; ++qt)
+                {
                     o[qt][jn] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa[t][qt], bb, o[qt][jn], 0, 0, 0);
+                    o[qt][jn] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pb[t][qt], bb, o[qt][jn], 0, 0, 0);
+                }
             }
     };
     // two register sets: the loads of the next step fly while this one is computed
@@ -235,11 +264,11 @@ __global__ __launch_bounds__(kMqThreads, QT == 1 ? 2 : 1) void multi_attn_kernel
         while (base < r1) {
             const int next = base + kMqBlockStep;
             if (next < r1) load_step(next, xb);
-            compute_step(xa);
+            compute_step(xa, base);
             if (next >= r1) break;
             const int next2 = next + kMqBlockStep;
             if (next2 < r1) load_step(next2, xa);
-            compute_step(xb);
+            compute_step(xb, next);
             base = next2;
         }
     }
@@ -311,7 +340,7 @@ __global__ __launch_bounds__(kMqD) void multi_attn_combine_kernel(MqParams p) {
     const int h = blockIdx.y, b = blockIdx.z;
     const int col = threadIdx.x;
     const int64_t bh = (int64_t)b * p.Hkv + h;
-    const int rows_total = min(max(p.comp_lens[bh], 0), p.cap);
+    const int rows_total = min(max(p.comp_lens[bh], 0), p.cap) + (p.Kt ? min(max(p.tail_lens[b], 0), p.tail_cap) : 0);
     const int S = mq_splits_for(rows_total, p.max_splits, p.min_rows);
     const int rb = R / p.block_rows, row = R - rb * p.block_rows;
     const float *part = p.part + (((bh * p.row_blocks + rb) * (int64_t)p.max_splits) * p.block_rows + row) * kMqPart;
@@ -349,7 +378,7 @@ __global__ __launch_bounds__(kMqD) void multi_attn_combine_kernel(MqParams p) {
 }
 
 // ------------------------------------------------------------------------------------------------
-static void mq_shape(int B, int Hq, int Hkv, int nq, int cap, int &row_blocks, int &max_splits, int &min_rows, int &block_rows) {
+static void mq_shape(int B, int Hq, int Hkv, int nq, int cap /* merged + tail rows */, int &row_blocks, int &max_splits, int &min_rows, int &block_rows) {
     const int G = Hq / Hkv;
     block_rows = (nq * G <= 16) ? 16 : kMqRows;
     row_blocks = (nq * G + block_rows - 1) / block_rows;
@@ -372,7 +401,7 @@ size_t multi_fast_workspace_bytes(int B, int Hq, int Hkv, int nq, int cap) {
 
 size_t multi_workspace_bytes(int B, int Hq, int Hkv, int nq, int cap, int d) {
     const size_t fast = multi_fast_workspace_bytes(B, Hq, Hkv, nq, cap);
-    const size_t generic = decode_workspace_bytes(B, Hq, Hkv, cap, d);
+    const size_t generic = decode_workspace_bytes(B, Hq, Hkv, cap, d);   // (covers any cap)
     return fast > generic ? fast : generic;
 }
 
@@ -389,6 +418,7 @@ hipError_t launch_multi(const MultiArgs &a, hipStream_t stream) {
             d.q_dtype = a.q_dtype;
             d.Kc = a.Kc; d.Vc = a.Vc; d.kv_dtype = a.kv_dtype; d.cap = a.cap;
             d.counts = a.counts; d.comp_lens = a.comp_lens;
+            d.Kt = a.Kt; d.Vt = a.Vt; d.tail_lens = a.tail_lens; d.tail_cap = a.tail_cap;   // (no mask: checked by the caller)
             d.B = a.B; d.Hq = a.Hq; d.Hkv = a.Hkv; d.d = a.d;
             d.scale = a.scale;
             d.O = reinterpret_cast<char *>(a.O) + j * per * o_es;
@@ -409,14 +439,22 @@ hipError_t launch_multi_fast(const MultiArgs &a, hipStream_t stream) {
     p.Kc = reinterpret_cast<const bf16_t *>(a.Kc);
     p.Vc = reinterpret_cast<const bf16_t *>(a.Vc);
     p.counts = a.counts; p.comp_lens = a.comp_lens;
+    p.Kt = reinterpret_cast<const bf16_t *>(a.Kt);
+    p.Vt = reinterpret_cast<const bf16_t *>(a.Vt);
+    p.tail_lens = a.tail_lens; p.tail_cap = a.Kt ? a.tail_cap : 0; p.causal = a.causal;
     p.nq = a.nq; p.cap = a.cap; p.B = a.B; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
     p.scale_log2 = a.scale * kMqLog2e;
     p.part = reinterpret_cast<float *>(a.ws);
-    mq_shape(a.B, a.Hq, a.Hkv, a.nq, a.cap, p.row_blocks, p.max_splits, p.min_rows, p.block_rows);
+    mq_shape(a.B, a.Hq, a.Hkv, a.nq, a.cap + p.tail_cap, p.row_blocks, p.max_splits, p.min_rows, p.block_rows);
     p.O = a.O; p.o_is_bf16 = a.o_dtype == DType::BF16; p.lse = a.lse;
     const dim3 grid(p.max_splits, p.row_blocks * a.Hkv, a.B);
-    if (p.block_rows == 16) hipLaunchKernelGGL(multi_attn_kernel<1>, grid, dim3(kMqThreads), 0, stream, p);
-    else hipLaunchKernelGGL(multi_attn_kernel<2>, grid, dim3(kMqThreads), 0, stream, p);
+    if (p.Kt) {
+        if (p.block_rows == 16) hipLaunchKernelGGL((multi_attn_kernel<1, true>), grid, dim3(kMqThreads), 0, stream, p);
+        else hipLaunchKernelGGL((multi_attn_kernel<2, true>), grid, dim3(kMqThreads), 0, stream, p);
+    } else {
+        if (p.block_rows == 16) hipLaunchKernelGGL((multi_attn_kernel<1, false>), grid, dim3(kMqThreads), 0, stream, p);
+        else hipLaunchKernelGGL((multi_attn_kernel<2, false>), grid, dim3(kMqThreads), 0, stream, p);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(multi_attn_combine_kernel, dim3(a.nq * p.G, a.Hkv, a.B), dim3(kMqD), 0, stream, p);

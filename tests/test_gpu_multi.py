@@ -79,3 +79,59 @@ def test_multi_attn_on_a_compressed_layer():
     assert err <= 4e-3 * max(1.0, np.abs(want_O).max()), err
     assert np.abs(lse.cpu().numpy() - want_L).max() <= 1e-3
     print("multi_attn on compressed layer: err %.2e" % err)
+
+
+@pytest.mark.parametrize("Hkv,G,B,cap,tcap,nq,causal", [
+    (8, 4, 1, 6000, 300, 16, True),      # two row blocks, tail spread over the last splits
+    (4, 7, 3, 1500, 64, 5, True),        # ragged row blocks, per-sequence tails, one shorter than the query block
+    (2, 2, 2, 300, 40, 3, False),        # no mask
+    (2, 8, 1, 40, 100, 9, True),         # tail longer than the merged cache
+])
+def test_multi_attn_tail_against_oracle(Hkv, G, B, cap, tcap, nq, causal):
+    rng = np.random.default_rng(900 + cap + nq)
+    Hq, d = Hkv * G, 128
+    Q = _round_like(rng.standard_normal((nq, B, Hq, d)), True)
+    Kc, Vc = _round_like(rng.standard_normal((B, Hkv, cap, d)), True), _round_like(rng.standard_normal((B, Hkv, cap, d)), True)
+    Kt, Vt = _round_like(rng.standard_normal((B, Hkv, tcap, d)), True), _round_like(rng.standard_normal((B, Hkv, tcap, d)), True)
+    counts = rng.integers(1, 40, (B, Hkv, cap)).astype(np.int32)
+    lens = rng.integers(cap // 2, cap + 1, (B, Hkv)).astype(np.int32)
+    lens[-1, -1] = 0
+    tails = rng.integers(nq, tcap + 1, (B,)).astype(np.int32)
+    if B > 1:
+        tails[1] = max(1, nq - 2)                                   # fewer tail rows than query rows
+    dQ, dKc, dVc = g.to_device(Q, True), g.to_device(Kc, True), g.to_device(Vc, True)
+    dKt, dVt = g.to_device(Kt, True), g.to_device(Vt, True)
+    dcounts, dlens = torch.from_numpy(counts).to(g.DEV), torch.from_numpy(lens).to(g.DEV)
+    dtails = torch.from_numpy(tails).to(g.DEV)
+    O, lse = sc.sc_multi_attn(dQ, dKc, dVc, dcounts, dlens, want_lse=True, Kt=dKt, Vt=dVt, tail_lens=dtails, causal=causal)
+    torch.cuda.synchronize()
+    want_O, want_L = oracle.multi_attn_tail(Q, Kc, Vc, counts, lens, Kt, Vt, tails, causal)
+    got = O.float().cpu().numpy().astype(np.float64)
+    err = np.abs(got - want_O) / np.maximum(1.0, np.abs(want_O))
+    assert err.max() <= 4e-3, (err.max(), np.unravel_index(err.argmax(), err.shape))
+    got_l = lse.cpu().numpy().astype(np.float64)
+    finite = np.isfinite(want_L)
+    assert np.array_equal(np.isneginf(got_l), np.isneginf(want_L))
+    assert np.abs(got_l[finite] - want_L[finite]).max() <= 1e-3
+    # one query row, no mask: what sc_decode_attn with the same tail gives (either kernel, same tolerance)
+    O1, _ = sc.sc_multi_attn(dQ[:1].contiguous(), dKc, dVc, dcounts, dlens, Kt=dKt, Vt=dVt, tail_lens=dtails)
+    Od, _ = sc.sc_decode_attn(dQ[0].contiguous(), dKc, dVc, dcounts, dlens, Kt=dKt, Vt=dVt, tail_lens=dtails)
+    torch.cuda.synchronize()
+    assert (O1[0].float() - Od.float()).abs().max().item() <= 8e-3 * max(1.0, float(np.abs(want_O).max()))
+
+
+def test_multi_attn_tail_mask_needs_the_matrix_core_path():
+    B, Hkv, G, cap, tcap, nq, d = 1, 2, 1, 64, 16, 2, 64
+    z = lambda *s: torch.zeros(s, dtype=torch.float32, device=g.DEV)
+    with pytest.raises(sc.SemantiCacheError, match="UNSUPPORTED"):
+        sc.sc_multi_attn(z(nq, B, Hkv * G, d), z(B, Hkv, cap, d), z(B, Hkv, cap, d),
+                         torch.ones((B, Hkv, cap), dtype=torch.int32, device=g.DEV),
+                         torch.full((B, Hkv), cap, dtype=torch.int32, device=g.DEV), Kt=z(B, Hkv, tcap, d),
+                         Vt=z(B, Hkv, tcap, d), tail_lens=torch.full((B,), tcap, dtype=torch.int32, device=g.DEV), causal=True)
+    # without the mask the same shapes go row by row through the decode kernels
+    O, _ = sc.sc_multi_attn(z(nq, B, Hkv * G, d), z(B, Hkv, cap, d), z(B, Hkv, cap, d) + 2.0,
+                            torch.ones((B, Hkv, cap), dtype=torch.int32, device=g.DEV),
+                            torch.full((B, Hkv), cap, dtype=torch.int32, device=g.DEV), Kt=z(B, Hkv, tcap, d),
+                            Vt=z(B, Hkv, tcap, d) + 2.0, tail_lens=torch.full((B,), tcap, dtype=torch.int32, device=g.DEV))
+    torch.cuda.synchronize()
+    assert torch.allclose(O, torch.full_like(O, 2.0), atol=1e-5)
