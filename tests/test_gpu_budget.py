@@ -77,3 +77,36 @@ def test_budget_search_matches_oracle(name, n, heads, fracs, iters):
     out = sc.sc_gsc_merge_budget(K, V, off, nch, total, -1.01, 1.0, iters, seq_lens=sl, cap=small_cap)
     torch.cuda.synchronize()
     assert (out[3] >= 0).all() and (out[3] <= small_cap).all()
+
+
+def test_budget_search_replays_from_a_graph():
+    # the whole search is a fixed sequence of launches: capture it once, replay it with other work and
+    # synchronisations in between, and get the eager result every time
+    w = wl.get_workload("layer32k")
+    case = build_case(w, 0.7, n_max=2048 + 5, heads=2, exclude_near=False)
+    K, V = g.to_device(case["K"], True), g.to_device(case["V"], True)
+    off, nch, sl = g.run_segment(case["mask"], case["seq_lens"])
+    budget = int(0.3 * 2 * int(case["seq_lens"][0]))
+    eager = sc.sc_gsc_merge_budget(K, V, off, nch, budget, -1.01, 1.0, 9, seq_lens=sl)
+    torch.cuda.synchronize()
+    ws = sc.Workspace(sc.load_library().sc_gsc_merge_budget_workspace_bytes(1, 2, K.shape[2], 128), g.DEV)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        warm = sc.sc_gsc_merge_budget(K, V, off, nch, budget, -1.01, 1.0, 9, seq_lens=sl, workspace=ws)
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            out = sc.sc_gsc_merge_budget(K, V, off, nch, budget, -1.01, 1.0, 9, seq_lens=sl, workspace=ws)
+    torch.cuda.synchronize()
+    for replay in range(3):
+        out[5].zero_(); out[3].zero_(); out[0].zero_()
+        scratch = torch.randn(1 << 20, device=g.DEV).sum()          # unrelated eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert out[5].item() == eager[5].item() and out[6].item() == eager[6].item(), replay
+        assert torch.equal(out[3], eager[3])
+        for h in range(2):
+            r = int(eager[3][0, h])
+            assert torch.equal(out[0][0, h, :r], eager[0][0, h, :r]) and torch.equal(out[2][0, h, :r], eager[2][0, h, :r])
+        del scratch
