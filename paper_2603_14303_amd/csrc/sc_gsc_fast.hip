@@ -208,10 +208,11 @@ __device__ __forceinline__ void store_tile(const floatx4_t (&D)[8], const floatx
     for (int i = 0; i < 4; ++i) {
         const int o = 16 * ot + 4 * g + i;
         if (o < n_out && dst_row0 + o < row_limit) {
-            const float inv = __builtin_amdgcn_rcpf(Dn[i]);   // exact for powers of two, 1 ulp otherwise
+            // 1/size: exact for powers of two, 1 ulp otherwise; a row of size 1 is multiplied by exactly 1
+            const float inv = (Dn[i] > 1.5f) ? __builtin_amdgcn_rcpf(Dn[i]) : 1.0f;
             float v[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = (Dn[i] > 1.5f) ? D[j][i] * inv : D[j][i];
+            for (int j = 0; j < 8; ++j) v[j] = D[j][i] * inv;
             store8(dst_c + (dst_row0 + o) * kFastD, v);
         }
     }
@@ -396,8 +397,12 @@ __device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, int 
         }
     }
     wave_lds_fence();
-    // sim(m, n) > t  <=>  dot * rinv_m > t * norm_n : one multiplication per pair
-    float tn[4], hn[4], ln[4], bn[4];
+    // sim(m, n) > t  <=>  dot * rinv_m > t * norm_n.  Per pair one fused multiply-add gives
+    //     dd = (tau + band) * norm_n - dot * rinv_m :   dd < 0  the pair is above the band (a sure yes),
+    //     0 <= dd <= 2 * band * norm_n  inside the band (unsure),  beyond that a sure no;
+    // its sign bit is shifted into a nibble (v_alignbit), and an unsigned minimum over the bit patterns
+    // keeps the smallest non-negative dd the lane has seen (negative values compare as huge).
+    float hn[4], wn[4];
     floatx4_t rm[4];
     bool bad = false;
 #pragma unroll
@@ -405,22 +410,15 @@ __device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, int 
         const float rn = s_rinv[16 * I + c];
         const float norm = __builtin_amdgcn_rcpf(rn);
         bad = bad || (16 * I + c < R && !(rn == rn));
-        tn[I] = tau * norm;
         hn[I] = (tau + kFastBand) * norm;
-        ln[I] = (tau - kFastBand) * norm;
-        bn[I] = (kFastBand * 1.0001f) * norm;
+        wn[I] = (2.0f * kFastBand) * norm;
         rm[I] = *reinterpret_cast<const floatx4_t *>(s_rinv + 16 * I + 4 * g);
     }
-    // per column tile J: bits m (0..63) as two dwords; closest approach to tau relative to the column norm
+    // per column tile J: bits m (0..63) as two dwords (row 16*I + 4g + i at bit 16*(I&1) + 4g + i of word I>>1)
     uint32_t y[4][2];
-    float dmin[4];
+    uint32_t dmin[4];
 #pragma unroll
-    for (int J = 0; J < 4; ++J) { y[J][0] = y[J][1] = 0u; dmin[J] = 3.0e38f; }
-    uint32_t bitc[2][4];   // this lane's bit for row 16*(I&1) + 4g + i of a 32-row half
-#pragma unroll
-    for (int hlf = 0; hlf < 2; ++hlf)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) bitc[hlf][i] = 1u << (16 * hlf + 4 * g + i);
+    for (int J = 0; J < 4; ++J) { y[J][0] = y[J][1] = 0u; dmin[J] = 0x7F800000u; }
     {
         constexpr int base[4] = {0, 4, 7, 9};
 #pragma unroll
@@ -429,12 +427,14 @@ __device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, int 
             for (int J = I; J < 4; ++J) {
                 if (J < nt) {
                     const int k = base[I] + (J - I);
+                    uint32_t nib = 0u;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float t = acc[k][i] * rm[I][i];
-                        y[J][I >> 1] |= (t > hn[J]) ? bitc[I & 1][i] : 0u;
-                        dmin[J] = fminf(dmin[J], fabsf(t - tn[J]));
+                    for (int i = 3; i >= 0; --i) {
+                        const uint32_t dd = __float_as_uint(fmaf(-acc[k][i], rm[I][i], hn[J]));
+                        nib = __builtin_amdgcn_alignbit(nib, dd, 31);     // (nib << 1) | sign bit
+                        dmin[J] = min(dmin[J], dd);
                     }
+                    y[J][I >> 1] |= nib << (16 * (I & 1) + 4 * g);
                 }
             }
     }
@@ -452,7 +452,7 @@ __device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, int 
     // anything close to tau, or an unusable norm, anywhere in the window?  (rare)
     bool close = bad;
 #pragma unroll
-    for (int J = 0; J < 4; ++J) close = close || (J < nt && !(dmin[J] > bn[J]));
+    for (int J = 0; J < 4; ++J) close = close || (J < nt && dmin[J] <= __float_as_uint(wn[J]));
     if (ballot64(close) != 0ull) {
         // the same products and bounds as above, so that "yes", "no" and "unsure" partition the pairs
         constexpr int base[4] = {0, 4, 7, 9};
@@ -465,9 +465,10 @@ __device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, int 
                     const int k = base[I] + (J - I);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const float t = acc[k][i] * rm[I][i];
-                        const bool uu = !(t > hn[J]) && !(t < ln[J]);
-                        if (I < 2) u0 |= uu ? bitc[I & 1][i] : 0u; else u1 |= uu ? bitc[I & 1][i] : 0u;
+                        const float dd = fmaf(-acc[k][i], rm[I][i], hn[J]);
+                        const bool uu = !(dd < 0.f) && !(dd > wn[J]);     // also true for a value that is not a number
+                        const uint32_t bit = 1u << (16 * (I & 1) + 4 * g + i);
+                        if (I < 2) u0 |= uu ? bit : 0u; else u1 |= uu ? bit : 0u;
                     }
                 }
             }
@@ -602,6 +603,8 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                 const int nchw = idx_hi - idx;
                 RowRegs xk, xv;
                 load_rows(xk, row_source(Kbh, p.stride_n, w0, R, g, c));
+                // the values are not needed before the merge: requested now, they arrive under the Gram step
+                load_rows(xv, row_source(Vbh, p.stride_n, w0, R, g, c));
                 // chunk range [lo, hi) of every row; a delimiter is a one-row range of its own
                 int lo = lane, hi = lane + 1;
                 bool in_chunk = false;
@@ -617,8 +620,6 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
 #else
                 gram_bitmatrix(s_lds, xk, R, tau, lane, yes_row, unsure_row);
 #endif
-                // the values are not needed before the keys are merged: their loads fly meanwhile
-                load_rows(xv, row_source(Vbh, p.stride_n, w0, R, g, c));
                 // Alg. 1 on the bit matrix, one seed per chunk and round: the first unassigned row of a
                 // chunk is its next seed and absorbs the unassigned rows of the chunk whose bit is set
                 const uint64_t my_range = bits_range(lo, hi);
