@@ -1,0 +1,100 @@
+"""Randomised structures on the GPU: many small sequences with unusual chunk layouts (runs of delimiters,
+no delimiter, chunks far longer than a window, chunks of one token), key mixtures with up to a dozen
+centres, exact duplicates, zero rows, and thresholds inside the similarity bands.  Integers must match
+the oracle bit for bit, merged rows within the usual bound.  Seeds are fixed."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2603_14303_amd import binding as sc
+from paper_2603_14303_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import gpu_common as g
+
+
+def _random_mask(rng, n):
+    kind = rng.integers(0, 6)
+    m = np.zeros(n, np.uint8)
+    if kind == 0:                                   # geometric gaps, short
+        p = np.cumsum(rng.geometric(1.0 / rng.integers(2, 30), size=n)) - 1
+        m[p[p < n]] = 1
+    elif kind == 1:                                 # a few very long chunks
+        p = np.cumsum(rng.integers(60, 400, size=n // 60 + 1)) - 1
+        m[p[p < n]] = 1
+    elif kind == 2:                                 # runs of delimiters and single-token chunks
+        m[rng.random(n) < 0.5] = 1
+    elif kind == 3:                                 # no delimiter at all
+        pass
+    elif kind == 4:                                 # chunk lengths around the window size
+        p = np.cumsum(rng.integers(28, 70, size=n // 28 + 1)) - 1
+        m[p[p < n]] = 1
+    else:                                           # leading and trailing delimiters, mixed gaps
+        p = np.cumsum(rng.choice([1, 2, 17, 33, 64, 65, 129], size=n)) - 1
+        m[p[p < n]] = 1
+        m[0] = 1
+        m[n - 1] = 1
+    return m
+
+
+def _random_keys(rng, mask, n, d, bf16):
+    cid = np.concatenate([[0], np.cumsum(mask[:n - 1])]).astype(np.int64)
+    n_chunks = int(cid.max()) + 1
+    max_c = int(rng.integers(1, 13))
+    centres = rng.standard_normal((n_chunks, max_c, d)).astype(np.float32)
+    n_c = rng.integers(1, max_c + 1, size=n_chunks)
+    pick = np.floor(rng.random(n) * n_c[cid]).astype(np.int64)
+    noise = np.float32(rng.choice([0.0, 0.05, 0.15, 0.4]))
+    K = centres[cid, pick] + noise * rng.standard_normal((n, d)).astype(np.float32)
+    V = rng.standard_normal((n, d)).astype(np.float32)
+    K[rng.random(n) < 0.01] = 0.0                                   # zero-norm keys
+    dup = np.nonzero(rng.random(n) < 0.05)[0]
+    dup = dup[dup > 0]
+    K[dup] = K[dup - 1]                                             # exact duplicates of the previous token
+    K *= rng.choice([1.0, 0.01, 30.0], size=(n, 1)).astype(np.float32)   # cosine does not care about scale
+    if bf16:
+        K, V = wl.round_to_bf16(K), wl.round_to_bf16(V)
+    return K, V
+
+
+@pytest.mark.parametrize("bf16,d,seed", [(True, 128, s) for s in range(12)] + [(False, 64, s) for s in range(100, 106)])
+def test_random_structures(bf16, d, seed):
+    rng = np.random.default_rng(seed)
+    B, H = 3, 2
+    N = int(rng.integers(200, 1500))
+    lens = rng.integers(1, N + 1, size=B).astype(np.int32)
+    lens[0] = N
+    mask = np.zeros((B, N), np.uint8)
+    K = np.zeros((B, H, N, d), np.float32)
+    V = np.zeros_like(K)
+    for b in range(B):
+        n = int(lens[b])
+        mask[b, :n] = _random_mask(rng, n)
+        for h in range(H):
+            K[b, h, :n], V[b, h, :n] = _random_keys(rng, mask[b], n, d, bf16)
+    tau = float(rng.choice([0.3, 0.7, 0.9, 0.97, 0.985, 0.995, 0.9999, -0.5]))
+    dK, dV = g.to_device(K, bf16), g.to_device(V, bf16)
+    off, nch, sl = g.check_segment(mask, lens)
+    Kc, Vc, counts, clens, cid = sc.sc_gsc_merge(dK, dV, off, nch, tau, seq_lens=sl, out_dtype=torch.float32,
+                                                 want_cluster_id=True)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for b in range(B):
+        n = int(lens[b])
+        o = oracle.segment(mask[b], n)
+        for h in range(H):
+            r = oracle.compress_head(K[b, h, :n], V[b, h, :n], o, tau)
+            if r["chunk_margin"].min() <= 1e-9:
+                continue                                             # a coin toss in fp64 itself: not a parity case
+            rows = r["n_rows"]
+            assert int(clens[b, h]) == rows, (seed, b, h, int(clens[b, h]), rows)
+            assert np.array_equal(cid[b, h, :n].cpu().numpy(), r["cid"]), (seed, b, h)
+            assert np.array_equal(counts[b, h, :rows].cpu().numpy(), r["counts"][:rows]), (seed, b, h)
+            ek = g.rowwise_err(Kc[b, h, :rows].cpu().numpy(), r["Kc"][:rows])
+            ev = g.rowwise_err(Vc[b, h, :rows].cpu().numpy(), r["Vc"][:rows])
+            worst = max(worst, ek, ev)
+            assert ek <= 1e-3 and ev <= 1e-3, (seed, b, h, ek, ev)
+    print("seed", seed, "N", N, "lens", lens.tolist(), "tau", tau, "rows", clens.cpu().numpy().tolist(), "err %.1e" % worst)
