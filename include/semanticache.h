@@ -53,6 +53,15 @@ const char *sc_last_runtime_error(void);
 const char *sc_version(void);
 
 /* ------------------------------------------------------------------------------------------------
+ * sc_check_lengths — the one call that waits.  Overflow that only the device can see (more chunks than
+ * offsets_cap, more merged rows than cap) is reported in band: the affected entry of num_chunks /
+ * comp_lens is -1 and nothing is written out of bounds.  This helper copies `count` such entries to
+ * the host on `stream`, waits for the stream, and returns SC_ERR_CAPACITY if any is negative
+ * (*first_bad, if given, receives its index, else -1), SC_OK otherwise.  Not for the hot path.
+ */
+sc_status sc_check_lengths(const int32_t *lengths, int count, int *first_bad, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
  * sc_segment — semantic chunking (Sec. 2.2, Eq. 1).
  *
  * A sequence of n tokens with delimiters at positions p_1 < ... < p_{M-1} becomes the alternating

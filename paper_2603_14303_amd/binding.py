@@ -44,6 +44,8 @@ def load_library() -> ctypes.CDLL:
     lib.sc_tune_set.argtypes = [c.c_char_p, i32]
     lib.sc_tune_get.restype = i32
     lib.sc_tune_get.argtypes = [c.c_char_p]
+    lib.sc_check_lengths.restype = i32
+    lib.sc_check_lengths.argtypes = [vp, i32, c.POINTER(c.c_int), vp]
     lib.sc_segment_workspace_bytes.restype = sz
     lib.sc_segment_workspace_bytes.argtypes = [i32, i32]
     lib.sc_segment.restype = i32
@@ -85,7 +87,7 @@ def load_library() -> ctypes.CDLL:
 
 EXPORTED = [
     "sc_status_string", "sc_last_runtime_error", "sc_version", "sc_tune_set", "sc_tune_get",
-    "sc_segment_workspace_bytes", "sc_segment",
+    "sc_check_lengths", "sc_segment_workspace_bytes", "sc_segment",
     "sc_gsc_merge_workspace_bytes", "sc_gsc_merge",
     "sc_decode_attn_workspace_bytes", "sc_decode_attn_init_workspace", "sc_decode_attn",
     "sc_decode_attn_tail", "sc_gsc_merge_append",
@@ -351,4 +353,18 @@ def sc_gsc_merge_budget(K, V, offsets, num_chunks, budget_rows: int, tau_lo: flo
                                  _ptr(cluster_id), _ptr(tau), _ptr(rows), workspace.ptr, workspace.nbytes, _stream())
     _check(st, "sc_gsc_merge_budget")
     return Kc, Vc, counts, comp_lens, cluster_id, tau, rows
+
+
+def check_lengths(lengths) -> int:
+    """Waits for the current stream; -1 if no entry of the device tensor is negative, else the flat index of
+    the first overflowed entry (num_chunks / comp_lens use -1 for "did not fit")."""
+    lib = load_library()
+    _require_cuda(lengths)
+    if not lengths.is_contiguous():
+        raise SemantiCacheError("lengths must be contiguous")
+    bad = ctypes.c_int(-1)
+    st = lib.sc_check_lengths(_ptr(lengths), int(lengths.numel()), ctypes.byref(bad), _stream())
+    if st not in (0, 3):
+        _check(st, "sc_check_lengths")
+    return int(bad.value)
 

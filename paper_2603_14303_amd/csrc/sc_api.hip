@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include "sc_host.h"
+#include <vector>
 
 namespace sc {
 
@@ -76,6 +77,23 @@ int sc_tune_get(const char *key) {
     if (!strcmp(key, "gsc_chunks_per_task")) return t.gsc_chunks_per_task;
     if (!strcmp(key, "gsc_stages")) return t.gsc_stages;
     return -1;
+}
+
+// ------------------------------------------------------------------------------------------------
+sc_status sc_check_lengths(const int32_t *lengths, int count, int *first_bad, void *stream) {
+    if (!lengths || count <= 0 || !aligned4(lengths)) return SC_ERR_INVALID_ARG;
+    if (first_bad) *first_bad = -1;
+    std::vector<int32_t> host((size_t)count);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = hipMemcpyAsync(host.data(), lengths, (size_t)count * sizeof(int32_t), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return runtime_status(e);
+    for (int i = 0; i < count; ++i)
+        if (host[i] < 0) {
+            if (first_bad) *first_bad = i;
+            return SC_ERR_CAPACITY;
+        }
+    return SC_OK;
 }
 
 // ------------------------------------------------------------------------------------------------

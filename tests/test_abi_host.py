@@ -207,6 +207,14 @@ def test_gsc_merge_budget_rejects_bad_arguments(lib):
     assert call(ws=None) == 4 and call(wsb=need - 1) == 4
 
 
+def test_check_lengths_rejects_bad_arguments(lib):
+    import ctypes
+    bad = ctypes.c_int(7)
+    assert lib.sc_check_lengths(None, 4, ctypes.byref(bad), None) == 1
+    assert lib.sc_check_lengths(FAKE, 0, ctypes.byref(bad), None) == 1
+    assert lib.sc_check_lengths(FAKE + 2, 4, None, None) == 1
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
     with pytest.raises(sc.SemantiCacheError):

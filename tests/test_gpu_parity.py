@@ -106,6 +106,7 @@ def test_capacity_overflow_and_empty_sequences():
     cap = int(rows.min()) - 3
     small = g.run_compress(case, torch.float32, cap=cap)
     assert small["comp_lens"].tolist() == [[-1, -1]]
+    assert sc.check_lengths(small["comp_lens"]) == 0 and sc.check_lengths(full["comp_lens"]) == -1
     assert torch.equal(small["Kc"][:, :, :cap], full["Kc"][:, :, :cap])
     assert torch.equal(small["counts"][:, :, :cap], full["counts"][:, :, :cap])
     # a sequence of length 0 gives an empty merged cache, and decode over it returns zeros
