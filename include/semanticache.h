@@ -150,19 +150,27 @@ sc_status sc_gsc_merge(const void *K, const void *V, sc_dtype in_dtype,
  *   Kc, Vc, counts  device, layout as written by sc_gsc_merge ([B, Hkv, cap, d] of kv_dtype, [B, Hkv, cap])
  *   comp_lens       device i32 [B, Hkv]; entries <= 0 give O = 0 and lse = -inf for that head group
  *   scale           logit scale; 0 selects 1/sqrt(d)
- *   O               device [B, Hq, d] of o_dtype, contiguous
+ *   O               device [B, Hq, d] of o_dtype, contiguous, 16-byte aligned
  *   lse             device f32 [B, Hq] or NULL; natural-log-sum-exp of the biased logits
  *
- *   ws              workspace of sc_decode_attn_workspace_bytes; unlike the other workspaces it carries
- *                   state: it starts with one "partial published" flag per (sequence, KV head, split),
- *                   which must be ZERO when a call starts.  Zero them once with
- *                   sc_decode_attn_init_workspace (or a memset of the whole workspace) after
- *                   allocating; every call leaves them zero again, so the workspace can be reused
- *                   by stream-ordered calls without further care.  Two calls that overlap in time
- *                   need two workspaces.  The workgroup that folds the splits of a (sequence, head)
- *                   waits for those flags for a bounded time; should the wait ever run out (it
- *                   cannot while workgroups start in grid order), that head group's O and lse are
- *                   filled with NaN rather than with a wrong result.
+ *   ws              workspace of sc_decode_attn_workspace_bytes.  Unlike the other workspaces it carries
+ *                   state and must be initialised ONCE with sc_decode_attn_init_workspace (for the same
+ *                   B and Hkv) after allocating; after that it can be reused by stream-ordered calls of
+ *                   that shape without further care.  Two calls that overlap in time need two workspaces.
+ *                   State: the rows of a (sequence, KV head) are cut into splits, one workgroup each,
+ *                   and the workgroup of the last split folds the partial results of the others.  Per
+ *                   (sequence, KV head) the workspace keeps an epoch counter and one flag per split;
+ *                   a split publishes its partial by storing the current epoch + 1 in its flag, the
+ *                   folding workgroup accepts only flags with that value and then raises the epoch, so
+ *                   nothing has to be cleared between calls and a flag left over from an earlier call
+ *                   can never be taken for a current one.
+ *                   The folding workgroup waits for the flags for a bounded time.  Should the wait ever
+ *                   run out (it cannot while workgroups start in grid order), the call fails visibly
+ *                   and for good: that head group's O and lse are filled with NaN, the workspace's
+ *                   status word is set, and every later call on the workspace also returns NaN for
+ *                   that head group until the workspace is initialised again.  The status word is the
+ *                   int32 at the start of the workspace (0, or -1 after a failure); it can be tested
+ *                   with sc_check_lengths((const int32_t *)ws, 1, NULL, stream).
  *
  * Host errors: NULL required pointer, sizes <= 0, Hq not a multiple of Hkv or Hq/Hkv > 8,
  * d not in {64,128}, bad dtype, workspace too small.
@@ -297,6 +305,10 @@ sc_status sc_multi_attn(const void *Q, sc_dtype q_dtype, int nq,
  * beyond floating-point summation order).  Keys:
  *   "decode_max_splits"    split-K workgroups per (sequence, KV head); <= 0 = chosen from B*Hkv
  *   "decode_min_rows"      rows of the merged cache a split should at least get
+ *   "decode_local_handover" 0: split partials always travel through memory, also where all splits of a
+ *                          head share one XCC and could use its L2 (the default, 1)
+ *   "decode_poll_budget"   polls of the folding workgroup before it gives up (default 2^20); negative:
+ *                          give up at once — a host-driven way to exercise the failure path in tests
  *   "decode_mfma_min_group" sc_decode_attn (bf16, d = 128, no tail): query heads per KV head from which the
  *                          matrix-core kernel of sc_multi_attn is used for the single row; 9 = never
  *   "gsc_fast_path"        0 forces the generic kernels even for bf16 / d = 128

@@ -56,6 +56,8 @@ int sc_tune_set(const char *key, int value) {
     if (!strcmp(key, "decode_max_splits")) t.decode_max_splits = value;
     else if (!strcmp(key, "decode_min_rows")) t.decode_min_rows = value;
     else if (!strcmp(key, "decode_mfma_min_group")) t.decode_mfma_min_group = value;
+    else if (!strcmp(key, "decode_local_handover")) t.decode_local_handover = value;
+    else if (!strcmp(key, "decode_poll_budget")) t.decode_poll_budget = value;
     else if (!strcmp(key, "gsc_chunks_per_item")) t.gsc_chunks_per_item = value;
     else if (!strcmp(key, "gsc_grid_x")) t.gsc_grid_x = value;
     else if (!strcmp(key, "gsc_fast_path")) t.gsc_fast_path = value;
@@ -71,6 +73,8 @@ int sc_tune_get(const char *key) {
     if (!strcmp(key, "decode_max_splits")) return t.decode_max_splits;
     if (!strcmp(key, "decode_min_rows")) return t.decode_min_rows;
     if (!strcmp(key, "decode_mfma_min_group")) return t.decode_mfma_min_group;
+    if (!strcmp(key, "decode_local_handover")) return t.decode_local_handover;
+    if (!strcmp(key, "decode_poll_budget")) return t.decode_poll_budget;
     if (!strcmp(key, "gsc_chunks_per_item")) return t.gsc_chunks_per_item;
     if (!strcmp(key, "gsc_grid_x")) return t.gsc_grid_x;
     if (!strcmp(key, "gsc_fast_path")) return t.gsc_fast_path;
@@ -235,7 +239,7 @@ static sc_status decode_common(const void *Q, sc_dtype q_dtype, const void *Kc, 
                                const int32_t *counts, const int32_t *comp_lens, const void *Kt, const void *Vt,
                                int tail_cap, const int32_t *tail_lens, bool with_tail, int B, int Hq, int Hkv, int d,
                                float scale, void *O, sc_dtype o_dtype, float *lse, void *ws, size_t ws_bytes,
-                               void *stream) {
+                               void *stream, size_t state_bytes = 0) {
     if (!Q || !Kc || !Vc || !counts || !comp_lens || !O) return SC_ERR_INVALID_ARG;
     if (with_tail && (!Kt || !Vt || !tail_lens)) return SC_ERR_INVALID_ARG;
     if (B <= 0 || Hq <= 0 || Hkv <= 0) return SC_ERR_INVALID_ARG;
@@ -246,14 +250,16 @@ static sc_status decode_common(const void *Q, sc_dtype q_dtype, const void *Kc, 
     if (Hq % Hkv) return SC_ERR_UNSUPPORTED;
     if (Hq / Hkv > 8) return SC_ERR_UNSUPPORTED;
     if (Hkv > 65535 || B > 65535) return SC_ERR_UNSUPPORTED;
-    if (!aligned16(Q) || !aligned16(Kc) || !aligned16(Vc) || !aligned4(O)) return SC_ERR_INVALID_ARG;
+    if (!aligned16(Q) || !aligned16(Kc) || !aligned16(Vc) || !aligned16(O)) return SC_ERR_INVALID_ARG;
     if (with_tail && (!aligned16(Kt) || !aligned16(Vt) || !aligned4(tail_lens))) return SC_ERR_INVALID_ARG;
     if (!aligned4(counts) || !aligned4(comp_lens) || (lse && !aligned4(lse))) return SC_ERR_INVALID_ARG;
     if (scale != scale) return SC_ERR_INVALID_ARG;
-    const size_t need = decode_workspace_bytes(B, Hq, Hkv, cap, d);
+    size_t need = decode_workspace_bytes(B, Hq, Hkv, cap, d);
+    if (state_bytes) need = need - decode_workspace_state_bytes(B, Hkv) + state_bytes;
     if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SC_ERR_WORKSPACE;
 
     DecodeArgs a;
+    a.state_bytes = state_bytes;
     a.Q = Q; a.q_dtype = static_cast<DType>(q_dtype);
     a.Kc = Kc; a.Vc = Vc; a.kv_dtype = static_cast<DType>(kv_dtype); a.cap = cap;
     a.counts = counts; a.comp_lens = comp_lens;

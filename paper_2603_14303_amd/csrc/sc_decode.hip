@@ -14,22 +14,15 @@
 // transposed DPP reduction that leaves ONE (row, head) score per lane, the online-softmax update done
 // once per score by its owner lane (exp2 domain, log2(size) bias), and a ds_swizzle broadcast of the 16
 // probabilities back to the lanes that hold the value pieces.  Partials (running max, sum, fp32
-// accumulator) are folded across lane groups and wavefronts and written to the workspace with
-// device-coherent stores; every split but the last then raises its flag, the workgroup of the last
-// split waits for the flags (bounded), folds the S partials into O and leaves the flags at zero, so
-// a workspace that was zeroed once stays ready for the next call.
+// accumulator) are folded across lane groups and wavefronts and written to the workspace; every split
+// but the last then publishes a flag, the workgroup of the last split waits for the flags (bounded)
+// and folds the S partials into O.  The hand-over is described above publish_or_collect below.
 //
 // Generic kernel (d = 64, fp32 caches or queries): same split-K scheme, plain DPP all-reduce.
 #include "sc_device.h"
 #include "sc_host.h"
 
 namespace sc {
-
-#ifdef SC_DEC_TIMING
-#define SC_STAMP(k) do { if (threadIdx.x == 0) p.dbg[((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 + (k)] = wall_clock64(); } while (0)
-#else
-#define SC_STAMP(k) do {} while (0)
-#endif
 
 constexpr int kDecThreads = 256;
 constexpr int kDecWaves = kDecThreads / kWave;
@@ -60,12 +53,12 @@ struct DecParams {
     void *O;
     int o_is_bf16;
     float *lse;
-    int32_t *flags;       // [B*Hkv][kDecMaxSplits] "partial published" flags, zero between calls
-    float *part;          // [B*Hkv][max_splits][G][D + 2]
+    int32_t *status;      // workspace status word: 0, or -1 once a hand-over has failed
+    struct HeadSync *sync;   // [B*Hkv] epoch and per-split flags of the hand-over
+    float *part;          // [B*Hkv][max_splits][G][D + 4]
     int max_splits, min_rows;
-#ifdef SC_DEC_TIMING
-    unsigned long long *dbg;   // [blocks][16] timestamps (development builds only)
-#endif
+    int local;            // all splits of a head share one XCC (see publish_or_collect)
+    int poll_budget;      // polls of the folding workgroup before it gives up
 };
 
 __device__ __forceinline__ int splits_for(int rows, int max_splits, int min_rows) {
@@ -103,61 +96,90 @@ template <int N, int I = 0> struct BcastAll {
 
 
 // ------------------------------------------------------------------------------------------------
-// Fold the S split partials of one (sequence, KV head) into O; run by the workgroup that arrived last.
-// Every global load is issued before its first use: (1) all (m, l) pairs, (2) per pass up to
-// HB*KMAX independent 16-byte loads per thread, so the fold costs a few memory round trips in total.
-// ------------------------------------------------------------------------------------------------
-// Hand-over of split partials between workgroups that may sit on different XCDs (each XCD has its own
-// L2).  Partials are written with device-coherent (write-through) stores, so publishing them needs
-// no L2 write-back: a workgroup waits for its own stores and then raises its flag with one more such
-// store.  The workgroup of the LAST split (S - 1) folds the partials: it polls the flags of the others
-// (one flag per lane, so a poll is one load), invalidates its caches and reads.  It is the last of its
-// (sequence, head) in dispatch order, so everything it waits for has been dispatched before it; the
-// wait is bounded all the same, and a wait that runs out files NaN instead of a result.
-// Flags instead of an arrival counter because device-wide atomics on one address are carried out one
-// after the other at about 100 ns each on this multi-die chip: 32 splits arriving together kept the
-// last one waiting for microseconds.
-__device__ __forceinline__ void coherent_store(float *p, float v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// Hand-over of the split partials to the workgroup that folds them.
+//
+// Grid: one-dimensional, workgroup id = split * (B * Hkv) + (sequence, head).  The workgroup of the
+// LAST split of a (sequence, head) folds; it has the highest id of its head, so everything it waits for
+// was dispatched before it.  The wait is bounded all the same.
+//
+// Per (sequence, head) the workspace holds an epoch word and one 64-bit flag per split.  A split
+// publishes by storing (epoch + 1) together with the number of the XCC (chiplet) it ran on; the folder
+// accepts a flag only if it carries that value, and raises the epoch when it is done.  Flags therefore
+// never need clearing and a flag left behind by an earlier call can never be taken for a current one.
+//
+// Every wavefront waits for its own partial stores to be acknowledged before the workgroup's barrier,
+// and only then is the flag stored: the flag can never overtake a partial.
+//
+// Two ways of moving the partials:
+//   local   (B * Hkv a multiple of 8)  the hardware hands workgroup ids to the 8 XCCs round robin, so
+//           all splits of a head sit on ONE XCC and share its L2: plain stores, acknowledged by that L2,
+//           and device-scope loads by the folder (they skip the reader's vector cache and are served by
+//           the L2 that holds the lines).  The folder checks the XCC numbers in the flags against its
+//           own; if they ever differed the partials might be invisible to it, and the call fails (below)
+//           instead of folding them.
+//   remote  (any other shape)  the splits of a head are spread over the XCCs, whose L2s are not coherent
+//           with each other inside a kernel: partials are written through to memory (device-scope
+//           stores) and read back with device-scope loads.
+//
+// Failure (the wait ran out, or XCC numbers differ in local mode): the head group's outputs are filled
+// with NaN, the workspace's status word is set to -1 and the head's epoch is poisoned, so that every
+// later call on this workspace also reports NaN for it until the workspace is initialised again.  A
+// workgroup that publishes after the folder gave up can thus never feed a later call.
+struct HeadSync {
+    unsigned long long epoch;
+    unsigned long long flag[kDecMaxSplits];
+};
+constexpr unsigned long long kEpochPoison = ~0ull;
+constexpr size_t kDecStatusBytes = 256;   // the workspace starts with the status word (int32: 0, or -1 after a failure)
+
+__device__ __forceinline__ int xcc_number() {
+    // XCC_ID hardware register, bits [3:0]: the chiplet this wavefront runs on
+    return __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 0xF;
 }
-constexpr int kFlagPollBudget = 1 << 20;   // polls of about 0.3 us each before giving up
+__device__ __forceinline__ void store_partial(float *p, float v, bool local) {
+    if (local) *p = v;
+    else __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Returns 0 in the workgroups that are done after publishing, 1 in the folding workgroup once every
-// other split of the (sequence, head) is published, -1 there if the wait ran out.
-__device__ __forceinline__ int publish_or_collect(int32_t *flags_bh, int S, int split, int tid, int *s_flag) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // own partial stores have completed
+// other split of the (sequence, head) is published, -1 there if the hand-over failed.
+__device__ __forceinline__ int publish_or_collect(HeadSync *hs, unsigned long long epoch, int S, int split, int tid,
+                                                  bool local, int poll_budget, int *s_flag) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's partial stores are acknowledged
     __syncthreads();
+    const int xcc = xcc_number();
+    const unsigned long long want = epoch + 1ull;
     if (split != S - 1) {
-        if (tid == 0) __hip_atomic_store(flags_bh + split, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0)
+            __hip_atomic_store(&hs->flag[split], (want << 8) | (unsigned long long)(xcc + 1), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
         return 0;
     }
     if (tid < kWave) {
-        int budget = kFlagPollBudget;
-        bool all = false;
-        while (!all && budget > 0) {
-            const int f0 = (tid < S - 1) ? __hip_atomic_load(flags_bh + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1;
-            const int f1 = (tid + kWave < S - 1) ? __hip_atomic_load(flags_bh + tid + kWave, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1;
-            all = __ballot(f0 != 0 && f1 != 0) == ~0ull;
+        int budget = poll_budget;
+        bool all = S <= 1;   // a single split has nothing to wait for
+        unsigned long long f0 = (unsigned long long)(xcc + 1), f1 = f0;
+        while (!all && poll_budget >= 0) {   // a negative budget gives up without looking (host-driven test of the failure path)
+            f0 = (tid < S - 1) ? __hip_atomic_load(&hs->flag[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : (want << 8);
+            f1 = (tid + kWave < S - 1) ? __hip_atomic_load(&hs->flag[tid + kWave], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : (want << 8);
+            all = __ballot((f0 >> 8) == want && (f1 >> 8) == want) == ~0ull;
             budget = __builtin_amdgcn_readfirstlane(budget) - 1;
-            if (!all) __builtin_amdgcn_s_sleep(2);
+            if (all || budget < 0) break;
+            __builtin_amdgcn_s_sleep(2);
         }
-        // flags back to zero for the next call
-        if (tid < S - 1) __hip_atomic_store(flags_bh + tid, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (tid + kWave < S - 1) __hip_atomic_store(flags_bh + tid + kWave, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (tid == 0) *s_flag = all ? 1 : -1;
-        // Drop stale cached lines of the partial buffer.  One wavefront does it for the workgroup: the
-        // caches concerned (the CU's vector cache, the XCD's L2) are shared by all of its wavefronts, the
-        // barrier below orders their loads behind it, and every further wavefront issuing the same
-        // invalidation costs a third of a microsecond in a queue per XCD (12 wavefronts x 4 folding
-        // workgroups per XCD used to add 20 us to a call with 32 (sequence, head) pairs).
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        // in local mode every published flag must name the folder's own XCC
+        const bool same0 = (tid >= S - 1) || (int)(f0 & 0xFF) == xcc + 1;
+        const bool same1 = (tid + kWave >= S - 1) || (int)(f1 & 0xFF) == xcc + 1;
+        const bool same = __ballot(same0 && same1) == ~0ull;
+        if (tid == 0) *s_flag = (all && (same || !local)) ? 1 : -1;
     }
     __syncthreads();
     return *s_flag;
 }
 
-// a wait that ran out: the outputs of the (sequence, head) say so
+// a failed hand-over: the outputs of the (sequence, head) say so, and so does the workspace from now on
 template <int G, int D>
-__device__ __forceinline__ void file_failure(const DecParams &p, int b, int h, int tid, int nthreads) {
+__device__ __forceinline__ void file_failure(const DecParams &p, HeadSync *hs, int b, int h, int tid, int nthreads) {
     const float bad = __builtin_nanf("");
     for (int i = tid; i < G * D; i += nthreads) {
         const int64_t ooff = ((int64_t)b * p.Hq + (int64_t)h * G + i / D) * D + i % D;
@@ -165,107 +187,96 @@ __device__ __forceinline__ void file_failure(const DecParams &p, int b, int h, i
         else reinterpret_cast<float *>(p.O)[ooff] = bad;
         if (i % D == 0 && p.lse) p.lse[(int64_t)b * p.Hq + (int64_t)h * G + i / D] = bad;
     }
+    if (tid == 0) {
+        __hip_atomic_store(p.status, -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&hs->epoch, kEpochPoison, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 }
 
 constexpr int kPartPad = 4;   // floats after the D accumulators of a partial: m, l, 2 unused (keeps 16-byte rows)
 
+typedef unsigned int u32x4_dec_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_dec_t __attribute__((ext_vector_type(2)));
+constexpr int kAuxDeviceScope = 16;   // buffer-load cache policy: sc1 = device scope (skips the vector cache)
+
+// ------------------------------------------------------------------------------------------------
+// Fold the S split partials of one (sequence, KV head) into O; run by the workgroup of the last split.
+// A thread owns one 16-byte piece of one head's output and every NS-th split.  All its loads of a pass
+// (the (m, l) pairs and up to KMAX partial pieces) are requested before the first is used, so the fold
+// costs one trip to the partials, two barriers and one store.  s_m / s_l: S * G floats each; s_red:
+// NTHREADS * 4 floats.
 template <int D, int G, int NTHREADS>
-__device__ __forceinline__ void combine_splits(const DecParams &p, const float *part_bh, int S, int b, int h,
-                                               int tid, int lane, int wave, float *s_w, float *s_l2, float *s_ml,
-                                               float *s_red) {
+__device__ __forceinline__ void combine_splits(const DecParams &p, const float *part_bh, int S, int b, int h, int tid,
+                                               float *s_m, float *s_l, float *s_red) {
     constexpr int kStride = D + kPartPad;
-    constexpr int HB = G < 4 ? G : 4;           // heads per pass
     constexpr int QPR = D / 4;                  // 16-byte pieces per partial row
-    constexpr int NTC = NTHREADS < 512 ? NTHREADS : 512;   // threads that load partial rows
-    constexpr int RS = NTC / QPR;               // partial rows in flight per load wave
-    constexpr int KMAX = 64 / RS;               // loads per thread, head and block of 64 splits
-    constexpr int NWAVES = NTHREADS / kWave;
-    const int q4 = tid % QPR, rs = tid / QPR;
-    const bool loader = tid < NTC;
-    // first block of partial rows: issued together with the (m, l) loads, one memory round trip
-    float4 x[HB][KMAX];
-    auto load_rows = [&](int h0, int sb) {
+    constexpr int COMBOS = G * QPR;             // (head, piece) pairs
+    constexpr int NS = NTHREADS / COMBOS;       // split groups
+    constexpr int KMAX = 6;                     // pieces in flight per thread and pass
+    static_assert(NS >= 1, "one thread per (head, piece) at least");
+    const int sg = tid / COMBOS, rem = tid - sg * COMBOS;
+    const int g = rem / QPR, q4 = rem - g * QPR;
+    const bool worker = sg < NS;
+    // the partials of this head behind a buffer descriptor: splits beyond S read as zeros
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(part_bh), (short)0,
+                                                                        S * G * kStride * 4, 0x00020000);
+    const int my_off = (g * kStride + 4 * q4) * 4;
+    float4 x[KMAX];
+    auto load_pass = [&](int s0) {
 #pragma unroll
-        for (int hh = 0; hh < HB; ++hh)
-#pragma unroll
-            for (int k = 0; k < KMAX; ++k) {
-                const int s = sb + rs + RS * k;
-                if (loader && s < S && h0 + hh < G) {
-                    const f32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(
-                        part_bh + ((int64_t)s * G + h0 + hh) * kStride + 4 * q4));
-                    x[hh][k] = make_float4(t.x, t.y, t.z, t.w);
-                } else {
-                    x[hh][k] = make_float4(0.f, 0.f, 0.f, 0.f);
-                }
-            }
+        for (int k = 0; k < KMAX; ++k) {
+            const int s = s0 + sg + NS * k;
+            // an index beyond the descriptor's range comes back as zeros
+            const u32x4_dec_t t = __builtin_amdgcn_raw_buffer_load_b128(rs, worker ? my_off + s * (G * kStride * 4) : 0x7FFFFFF0, 0,
+                                                                         kAuxDeviceScope);
+            x[k] = make_float4(__uint_as_float(t.x), __uint_as_float(t.y), __uint_as_float(t.z), __uint_as_float(t.w));
+        }
     };
-    load_rows(0, 0);
+    load_pass(0);
     for (int i = tid; i < S * G; i += NTHREADS) {
-        const float *src = part_bh + (int64_t)i * kStride + D;
-        s_w[i] = __builtin_nontemporal_load(src);
-        s_l2[i] = __builtin_nontemporal_load(src + 1);
+        const u32x2_dec_t ml = __builtin_amdgcn_raw_buffer_load_b64(rs, (i * kStride + D) * 4, 0, kAuxDeviceScope);
+        s_m[i] = __uint_as_float(ml.x);
+        s_l[i] = __uint_as_float(ml.y);
     }
     __syncthreads();
-    SC_STAMP(7);
-    for (int hh = wave; hh < G; hh += NWAVES) {
-        float mx = -INFINITY;
-        for (int s = lane; s < S; s += kWave) mx = fmaxf(mx, s_w[s * G + hh]);
+    float mx = -INFINITY;
+    if (worker)
+        for (int s = 0; s < S; ++s) mx = fmaxf(mx, s_m[s * G + g]);
+    const float m_safe = (mx == -INFINITY) ? 0.f : mx;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s0 = 0; s0 < S; s0 += NS * KMAX) {
+        if (s0 != 0) load_pass(s0);
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
-        const float m_safe = (mx == -INFINITY) ? 0.f : mx;
-        float lt = 0.f;
-        for (int s = lane; s < S; s += kWave) {
-            const float wgt = fast_exp2(s_w[s * G + hh] - m_safe);
-            s_w[s * G + hh] = wgt;
-            lt = fmaf(s_l2[s * G + hh], wgt, lt);
+        for (int k = 0; k < KMAX; ++k) {
+            const int s = s0 + sg + NS * k;
+            const float wgt = (worker && s < S) ? fast_exp2(s_m[s * G + g] - m_safe) : 0.f;
+            acc.x = fmaf(x[k].x, wgt, acc.x);
+            acc.y = fmaf(x[k].y, wgt, acc.y);
+            acc.z = fmaf(x[k].z, wgt, acc.z);
+            acc.w = fmaf(x[k].w, wgt, acc.w);
         }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) lt += __shfl_xor(lt, off, kWave);
-        if (lane == 0) { s_ml[2 * hh] = mx; s_ml[2 * hh + 1] = lt; }
     }
+    if (worker) *reinterpret_cast<float4 *>(s_red + (sg * COMBOS + rem) * 4) = acc;
     __syncthreads();
-    SC_STAMP(8);
-    for (int h0 = 0; h0 < G; h0 += HB) {
-        float4 acc[HB];
+    if (tid < COMBOS) {
+        float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-        for (int hh = 0; hh < HB; ++hh) acc[hh] = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int sb = 0; sb < S; sb += 64) {
-            if (h0 != 0 || sb != 0) load_rows(h0, sb);
-#pragma unroll
-            for (int hh = 0; hh < HB; ++hh)
-#pragma unroll
-                for (int k = 0; k < KMAX; ++k) {
-                    const int s = sb + rs + RS * k;
-                    const float wgt = (s < S && h0 + hh < G) ? s_w[s * G + h0 + hh] : 0.f;
-                    acc[hh].x = fmaf(x[hh][k].x, wgt, acc[hh].x);
-                    acc[hh].y = fmaf(x[hh][k].y, wgt, acc[hh].y);
-                    acc[hh].z = fmaf(x[hh][k].z, wgt, acc[hh].z);
-                    acc[hh].w = fmaf(x[hh][k].w, wgt, acc[hh].w);
-                }
+        for (int r = 0; r < NS; ++r) {
+            const float4 t = *reinterpret_cast<const float4 *>(s_red + (r * COMBOS + rem) * 4);
+            a.x += t.x; a.y += t.y; a.z += t.z; a.w += t.w;
         }
-        if (loader) {
-#pragma unroll
-            for (int hh = 0; hh < HB; ++hh)
-                *reinterpret_cast<float4 *>(s_red + ((rs * HB + hh) * D + 4 * q4)) = acc[hh];
+        float l = 0.f;
+        for (int s = 0; s < S; ++s) l = fmaf(s_l[s * G + g], fast_exp2(s_m[s * G + g] - m_safe), l);
+        const float inv = (l > 0.f) ? 1.0f / l : 0.f;
+        const float o0 = a.x * inv, o1 = a.y * inv, o2 = a.z * inv, o3 = a.w * inv;
+        const int64_t ooff = ((int64_t)b * p.Hq + (int64_t)h * G + g) * D + 4 * q4;
+        if (p.o_is_bf16) {
+            *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(p.O) + ooff) = make_uint2(pack_bf16x2(o0, o1), pack_bf16x2(o2, o3));
+        } else {
+            *reinterpret_cast<float4 *>(reinterpret_cast<float *>(p.O) + ooff) = make_float4(o0, o1, o2, o3);
         }
-        __syncthreads();
-        SC_STAMP(9);
-        for (int i = tid; i < HB * D; i += NTHREADS) {
-            const int hh = i / D, e = i % D;
-            if (h0 + hh < G) {
-                float a = 0.f;
-#pragma unroll
-                for (int r = 0; r < RS; ++r) a += s_red[(r * HB + hh) * D + e];
-                const float mx = s_ml[2 * (h0 + hh)], l = s_ml[2 * (h0 + hh) + 1];
-                const float out = (l > 0.f) ? a / l : 0.f;
-                const int64_t ooff = ((int64_t)b * p.Hq + (int64_t)h * G + h0 + hh) * D + e;
-                if (p.o_is_bf16) reinterpret_cast<uint16_t *>(p.O)[ooff] = (uint16_t)f32_to_bf16(out);
-                else reinterpret_cast<float *>(p.O)[ooff] = out;
-                if (e == 0 && p.lse)
-                    p.lse[(int64_t)b * p.Hq + (int64_t)h * G + h0 + hh] = (l > 0.f) ? (mx + __log2f(l)) * kLn2 : -INFINITY;
-            }
-        }
-        __syncthreads();
+        if (q4 == 0 && p.lse)
+            p.lse[(int64_t)b * p.Hq + (int64_t)h * G + g] = (l > 0.f) ? (mx + __log2f(l)) * kLn2 : -INFINITY;
     }
 }
 
@@ -292,28 +303,36 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
     constexpr int kRowsPerWaveStep = RPW * U;
     constexpr int kRowsPerBlockStep = kRowsPerWaveStep * WAVES;
     constexpr int kStride = D + kPartPad;   // floats per (split, head) partial: acc[D], m, l, pad
-    constexpr int HB = G < 4 ? G : 4;
-    constexpr int kBufFloats = (WAVES * G * D) > (16 * HB * D) ? (WAVES * G * D) : (16 * HB * D);
+    constexpr int kBufFloats = (WAVES * G * D) > (THREADS * 4) ? (WAVES * G * D) : (THREADS * 4);
 
-    // s_buf: per-wave accumulators [WAVES][G][D] first, partial-row sums of the final fold later
+    // s_buf: per-wave accumulators [WAVES][G][D] first, the split-group sums of the final fold later
     __shared__ __attribute__((aligned(16))) float s_buf[kBufFloats];
     __shared__ float s_m[WAVES][G];
     __shared__ float s_l[WAVES][G];
     __shared__ float s_w[kDecMaxSplits * G];
     __shared__ float s_l2[kDecMaxSplits * G];
-    __shared__ float s_ml[2 * G];
     __shared__ int s_last;
 
-    SC_STAMP(0);
-    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    // workgroup id = split * (B * Hkv) + (sequence, head): see publish_or_collect
+    const int n_bh = p.B * p.Hkv;
+    const int split = (int)blockIdx.x / n_bh;
+    const int bh_i = (int)blockIdx.x - split * n_bh;
+    const int b = bh_i / p.Hkv, h = bh_i - b * p.Hkv;
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // scalar: keeps the row loop wave-uniform
     const int g = lane / LPR, c = lane % LPR;
-    const int64_t bh = (int64_t)b * p.Hkv + h;
+    const int64_t bh = bh_i;
+    HeadSync *hs = p.sync + bh;
+    const unsigned long long epoch = __hip_atomic_load(&hs->epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const int rows_c = min(max(p.comp_lens[bh], 0), p.cap);
     const int rows_total = rows_c + (TAIL ? min(max(p.tail_lens[b], 0), p.tail_cap) : 0);
     const int S = splits_for(rows_total, p.max_splits, p.min_rows);
     if (split >= S) return;
+    if (epoch == kEpochPoison) {   // an earlier call on this workspace failed: fail again, visibly
+        if (split == S - 1) file_failure<G, D>(p, hs, b, h, tid, THREADS);
+        return;
+    }
+    const bool local = p.local != 0;
     // contiguous row range of this split, a multiple of the block step except for the last one
     int per = (rows_total + S - 1) / S;
     per = (per + kRowsPerBlockStep - 1) / kRowsPerBlockStep * kRowsPerBlockStep;
@@ -346,7 +365,6 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
             }
         }
     };
-    SC_STAMP(1);
     int base = r0 + wave * kRowsPerWaveStep;
     issue(base);
 
@@ -423,8 +441,6 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
         base += kRowsPerBlockStep;
         if (base < r1) issue(base);
     }
-
-    SC_STAMP(2);
     // ---- fold the RPW lane groups of the wave (each saw different rows), then park in LDS
     {
         const float mw = rows_allreduce_max(m_run);
@@ -445,9 +461,7 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
         if (g == 0 && c < G) { s_m[wave][c] = mw; s_l[wave][c] = lw; }
     }
     __syncthreads();
-
-    SC_STAMP(3);
-    // ---- fold the waves, write this split's partial (device-coherent stores)
+    // ---- fold the waves, write this split's partial
     float *part_bh = p.part + bh * (int64_t)p.max_splits * G * kStride;
     for (int i = tid; i < G * D; i += THREADS) {
         const int hh = i / D, e = i % D;
@@ -463,21 +477,18 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
             l = fmaf(s_l[w][hh], f, l);
         }
         float *dst = part_bh + ((int64_t)split * G + hh) * kStride;
-        coherent_store(dst + e, a);
-        if (e == 0) { coherent_store(dst + D, mw); coherent_store(dst + D + 1, l); }
+        store_partial(dst + e, a, local);
+        if (e == 0) { store_partial(dst + D, mw, local); store_partial(dst + D + 1, l, local); }
     }
-
-    SC_STAMP(4);
     // ---- the workgroup of the last split folds all splits
-    const int got = publish_or_collect(p.flags + bh * kDecMaxSplits, S, split, tid, &s_last);
-    SC_STAMP(5);
+    const int got = publish_or_collect(hs, epoch, S, split, tid, local, p.poll_budget, &s_last);
     if (got == 0) return;
     if (got < 0) {
-        file_failure<G, D>(p, b, h, tid, THREADS);
+        file_failure<G, D>(p, hs, b, h, tid, THREADS);
         return;
     }
-    combine_splits<D, G, THREADS>(p, part_bh, S, b, h, tid, lane, wave, s_w, s_l2, s_ml, s_buf);
-    SC_STAMP(6);
+    combine_splits<D, G, THREADS>(p, part_bh, S, b, h, tid, s_w, s_l2, s_buf);
+    if (tid == 0) __hip_atomic_store(&hs->epoch, epoch + 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -496,20 +507,30 @@ __global__ __launch_bounds__(kDecThreads) void decode_generic_kernel(DecParams p
     __shared__ float s_l[kDecWaves][G];
     __shared__ float s_w[kDecMaxSplits * G];
     __shared__ float s_l2[kDecMaxSplits * G];
-    __shared__ float s_ml[2 * G];
-    __shared__ __attribute__((aligned(16))) float s_red[(kDecThreads / (D / 4)) * (G < 4 ? G : 4) * D];
+    __shared__ __attribute__((aligned(16))) float s_red[kDecThreads * 4];
     __shared__ int s_last;
 
-    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    // workgroup id = split * (B * Hkv) + (sequence, head): see publish_or_collect
+    const int n_bh = p.B * p.Hkv;
+    const int split = (int)blockIdx.x / n_bh;
+    const int bh_i = (int)blockIdx.x - split * n_bh;
+    const int b = bh_i / p.Hkv, h = bh_i - b * p.Hkv;
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // scalar: keeps the row loop wave-uniform
     const int g = lane / LPR, c = lane % LPR;
-    const int64_t bh = (int64_t)b * p.Hkv + h;
+    const int64_t bh = bh_i;
+    HeadSync *hs = p.sync + bh;
+    const unsigned long long epoch = __hip_atomic_load(&hs->epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const int rows_c = min(max(p.comp_lens[bh], 0), p.cap);
     // merged rows, then the uncompressed tail (if the call has one): a tail row is a cluster of one
     const int rows_total = rows_c + (p.Kt ? min(max(p.tail_lens[b], 0), p.tail_cap) : 0);
     const int S = splits_for(rows_total, p.max_splits, p.min_rows);
     if (split >= S) return;
+    if (epoch == kEpochPoison) {   // an earlier call on this workspace failed: fail again, visibly
+        if (split == S - 1) file_failure<G, D>(p, hs, b, h, tid, kDecThreads);
+        return;
+    }
+    const bool local = p.local != 0;
     // contiguous row range of this split, a multiple of the block step except for the last one
     int per = (rows_total + S - 1) / S;
     per = (per + kRowsPerBlockStep - 1) / kRowsPerBlockStep * kRowsPerBlockStep;
@@ -639,18 +660,19 @@ __global__ __launch_bounds__(kDecThreads) void decode_generic_kernel(DecParams p
             l = fmaf(s_l[w][hh], f, l);
         }
         float *dst = part_bh + ((int64_t)split * G + hh) * kStride;
-        coherent_store(dst + e, a);
-        if (e == 0) { coherent_store(dst + D, mw); coherent_store(dst + D + 1, l); }
+        store_partial(dst + e, a, local);
+        if (e == 0) { store_partial(dst + D, mw, local); store_partial(dst + D + 1, l, local); }
     }
 
     // ---- the workgroup of the last split folds all splits
-    const int got = publish_or_collect(p.flags + bh * kDecMaxSplits, S, split, tid, &s_last);
+    const int got = publish_or_collect(hs, epoch, S, split, tid, local, p.poll_budget, &s_last);
     if (got == 0) return;
     if (got < 0) {
-        file_failure<G, D>(p, b, h, tid, kDecThreads);
+        file_failure<G, D>(p, hs, b, h, tid, kDecThreads);
         return;
     }
-    combine_splits<D, G, kDecThreads>(p, part_bh, S, b, h, tid, lane, wave, s_w, s_l2, s_ml, s_red);
+    combine_splits<D, G, kDecThreads>(p, part_bh, S, b, h, tid, s_w, s_l2, s_red);
+    if (tid == 0) __hip_atomic_store(&hs->epoch, epoch + 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __global__ void zero_words_kernel(int32_t *p, size_t n) {
@@ -658,7 +680,7 @@ __global__ void zero_words_kernel(int32_t *p, size_t n) {
     if (i < n) p[i] = 0;
 }
 
-size_t decode_workspace_state_bytes(int B, int Hkv) { return align_up((size_t)B * Hkv * kDecMaxSplits * 4, 256); }
+size_t decode_workspace_state_bytes(int B, int Hkv) { return kDecStatusBytes + align_up((size_t)B * Hkv * sizeof(HeadSync), 256); }
 
 static int clamp_splits() { return max(1, min(kDecMaxSplits, tuning().decode_max_splits)); }   // knob <= 0: automatic
 
@@ -680,7 +702,7 @@ hipError_t launch_decode_init_workspace(void *ws, size_t state_bytes, hipStream_
 
 template <typename T, int D, int G>
 static hipError_t launch_g(const DecParams &p, hipStream_t stream) {
-    const dim3 grid(p.max_splits, p.Hkv, p.B);
+    const dim3 grid((unsigned)p.max_splits * (unsigned)(p.Hkv * p.B));
     if constexpr (D == 128 && sizeof(T) == 2) {
         if (p.q_is_bf16) {
             if (p.Kt) hipLaunchKernelGGL((decode_bf16_kernel<D, G, true>), grid, dim3(FastShape<G>::THREADS), 0, stream, p);
@@ -722,7 +744,7 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream) {
         m.B = a.B; m.Hq = a.Hq; m.Hkv = a.Hkv; m.d = a.d;
         m.scale = a.scale;
         m.O = a.O; m.o_dtype = a.o_dtype; m.lse = a.lse;
-        m.ws = reinterpret_cast<char *>(a.ws) + decode_workspace_state_bytes(a.B, a.Hkv);
+        m.ws = reinterpret_cast<char *>(a.ws) + (a.state_bytes ? a.state_bytes : decode_workspace_state_bytes(a.B, a.Hkv));
         return launch_multi_fast(m, stream);
     }
     DecParams p;
@@ -734,12 +756,14 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream) {
     p.scale_log2 = a.scale * kLog2e;
     p.O = a.O; p.o_is_bf16 = a.o_dtype == DType::BF16;
     p.lse = a.lse;
-    p.flags = reinterpret_cast<int32_t *>(a.ws);
-    p.part = reinterpret_cast<float *>(reinterpret_cast<char *>(a.ws) + decode_workspace_state_bytes(a.B, a.Hkv));
-#ifdef SC_DEC_TIMING
-    p.dbg = reinterpret_cast<unsigned long long *>(a.lse);   // development builds borrow the lse pointer
-    p.lse = nullptr;
-#endif
+    p.status = reinterpret_cast<int32_t *>(a.ws);
+    p.sync = reinterpret_cast<HeadSync *>(reinterpret_cast<char *>(a.ws) + kDecStatusBytes);
+    p.part = reinterpret_cast<float *>(reinterpret_cast<char *>(a.ws) +
+                                       (a.state_bytes ? a.state_bytes : decode_workspace_state_bytes(a.B, a.Hkv)));
+    // the hardware hands consecutive workgroup ids to the 8 XCCs in turn: with B * Hkv a multiple of 8 the id
+    // (split * B * Hkv + head) keeps every head on one XCC
+    p.local = ((a.B * a.Hkv) % 8 == 0 && tuning().decode_local_handover) ? 1 : 0;
+    p.poll_budget = tuning().decode_poll_budget;
     p.min_rows = max(1, tuning().decode_min_rows);
     // Splits per (sequence, KV head): enough workgroups to cover the 256 CUs about once; more splits
     // only add partials to fold and tickets to take (both are serial tails of the kernel).

@@ -58,6 +58,7 @@ struct DecodeArgs {
     DType o_dtype;
     float *lse;
     void *ws;
+    size_t state_bytes = 0;   // size of the state region at the start of ws; 0 = decode_workspace_state_bytes(B, Hkv)
 };
 size_t decode_workspace_bytes(int B, int Hq, int Hkv, int cap, int d);
 size_t decode_workspace_state_bytes(int B, int Hkv);
@@ -94,6 +95,8 @@ hipError_t launch_multi_fast(const MultiArgs &a, hipStream_t stream);
 struct Tuning {
     int decode_max_splits = 0;      // split-K workgroups per (sequence, KV head); <= 0 picks it from B*Hkv
     int decode_min_rows = 192;      // rows of the merged cache a split should at least get
+    int decode_local_handover = 1;  // 0: split partials always go through memory, also when a head's splits share an XCC
+    int decode_poll_budget = 1 << 20;   // polls (about 0.3 us each) of the folding workgroup before it gives up; negative: give up at once (host-driven test of the failure path)
     int decode_mfma_min_group = 5;  // query heads per KV head from which single-row decode runs on the matrix-core kernel (9 = never)
     int gsc_chunks_per_item = 16;   // chunks handled by one workgroup work item
     int gsc_grid_x = 0;             // workgroups per (sequence, KV head); <= 0 picks it from B*Hkv
