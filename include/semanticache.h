@@ -185,6 +185,28 @@ sc_status sc_decode_attn(const void *Q, sc_dtype q_dtype,
                          void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * sc_decode_attn_static — sc_decode_attn for callers that cannot allocate device memory (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc) and therefore cannot hand
+ * in a workspace: same arguments without ws / ws_bytes, same kernels, same results bit for bit.  The
+ * scratch is an array inside the library's code object (16 MiB for partial results plus 1 MiB of
+ * hand-over state), one copy per GPU, held until the process ends; the call allocates and frees
+ * nothing and needs no initialisation call (the array starts zeroed, which is the initialised state).
+ *
+ *   Limits: sc_decode_attn_workspace_bytes(B, Hq, Hkv, cap, d) must not exceed 16 MiB (16 777 216 B),
+ *   e.g. B * Hkv <= 56 at Hq / Hkv = 4, d = 128, and B * Hkv must not exceed 1024; larger shapes are
+ *   refused with SC_ERR_WORKSPACE and nothing is launched.  All other host errors as for sc_decode_attn.
+ *   All calls on one GPU share that GPU's array, whatever their shapes: calls that overlap in time on
+ *   one GPU race; order them on one stream or with events.  The first call on a device looks up the
+ *   array's address (no allocation; do it once outside graph capture).  A failed hand-over (see
+ *   sc_decode_attn) shows as NaN outputs, here too for every later call of that head group.
+ */
+sc_status sc_decode_attn_static(const void *Q, sc_dtype q_dtype,
+                                const void *Kc, const void *Vc, sc_dtype kv_dtype, int cap,
+                                const int32_t *counts, const int32_t *comp_lens,
+                                int B, int Hq, int Hkv, int d, float scale,
+                                void *O, sc_dtype o_dtype, float *lse, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
  * Decode-time growth.  The paper compresses the prefill cache once and leaves open what happens to the
  * tokens that arrive afterwards (Sec. 2.1 treats the cache as given).  These two calls follow from
  * its definitions without adding any: a token that has not been merged is a cluster of one, exactly

@@ -62,6 +62,9 @@ def load_library() -> ctypes.CDLL:
     lib.sc_decode_attn.restype = i32
     lib.sc_decode_attn.argtypes = [vp, i32, vp, vp, i32, i32, vp, vp, i32, i32, i32, i32, f32,
                                    vp, i32, vp, vp, sz, vp]
+    lib.sc_decode_attn_static.restype = i32
+    lib.sc_decode_attn_static.argtypes = [vp, i32, vp, vp, i32, i32, vp, vp, i32, i32, i32, i32, f32,
+                                          vp, i32, vp, vp]
     lib.sc_decode_attn_tail.restype = i32
     lib.sc_decode_attn_tail.argtypes = [vp, i32, vp, vp, i32, i32, vp, vp, vp, vp, i32, vp, i32, i32, i32, i32, f32,
                                         vp, i32, vp, vp, sz, vp]
@@ -90,7 +93,7 @@ EXPORTED = [
     "sc_check_lengths", "sc_segment_workspace_bytes", "sc_segment",
     "sc_gsc_merge_workspace_bytes", "sc_gsc_merge",
     "sc_decode_attn_workspace_bytes", "sc_decode_attn_init_workspace", "sc_decode_attn",
-    "sc_decode_attn_tail", "sc_gsc_merge_append",
+    "sc_decode_attn_static", "sc_decode_attn_tail", "sc_gsc_merge_append",
     "sc_multi_attn_workspace_bytes", "sc_multi_attn", "sc_multi_attn_tail",
     "sc_gsc_merge_budget_workspace_bytes", "sc_gsc_merge_budget",
 ]
@@ -276,6 +279,23 @@ def sc_decode_attn(Q, Kc, Vc, counts, comp_lens, scale: float = 0.0, O=None, lse
                             _ptr(comp_lens), B, Hq, Hkv, d, float(scale), _ptr(O), _dtype_code(O), _ptr(lse),
                             workspace.ptr, workspace.nbytes, _stream())
     _check(st, "sc_decode_attn")
+    return O, lse
+
+
+def sc_decode_attn_static(Q, Kc, Vc, counts, comp_lens, O, lse=None, scale: float = 0.0):
+    """sc_decode_attn on the library's own per-GPU scratch: the caller passes inputs and outputs only, and
+    neither this wrapper nor the library allocates anything."""
+    lib = load_library()
+    _require_cuda(Q, Kc, Vc, counts, comp_lens, O, lse)
+    B, Hq, d = Q.shape
+    _, Hkv, cap, _ = Kc.shape
+    for t in (Q, Kc, Vc, counts, comp_lens, O):
+        if not t.is_contiguous():
+            raise SemantiCacheError("inputs and outputs must be contiguous")
+    st = lib.sc_decode_attn_static(_ptr(Q), _dtype_code(Q), _ptr(Kc), _ptr(Vc), _dtype_code(Kc), cap, _ptr(counts),
+                                   _ptr(comp_lens), B, Hq, Hkv, d, float(scale), _ptr(O), _dtype_code(O), _ptr(lse),
+                                   _stream())
+    _check(st, "sc_decode_attn_static")
     return O, lse
 
 

@@ -277,6 +277,26 @@ sc_status sc_decode_attn(const void *Q, sc_dtype q_dtype, const void *Kc, const 
                          Hkv, d, scale, O, o_dtype, lse, ws, ws_bytes, stream);
 }
 
+sc_status sc_decode_attn_static(const void *Q, sc_dtype q_dtype, const void *Kc, const void *Vc, sc_dtype kv_dtype,
+                                int cap, const int32_t *counts, const int32_t *comp_lens, int B, int Hq, int Hkv, int d,
+                                float scale, void *O, sc_dtype o_dtype, float *lse, void *stream) {
+    // the size check comes first: nothing below may depend on a scratch that is too small
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv) return SC_ERR_INVALID_ARG;
+    if (cap <= 0) return SC_ERR_CAPACITY;
+    if (d != 64 && d != 128) return SC_ERR_UNSUPPORTED;
+    if (decode_workspace_bytes(B, Hq, Hkv, cap, d) > kDecodeStaticScratchBytes) return SC_ERR_WORKSPACE;
+    if ((long long)B * Hkv > kDecodeStaticMaxHeads) return SC_ERR_WORKSPACE;
+    if (!Q || !Kc || !Vc || !counts || !comp_lens || !O) return SC_ERR_INVALID_ARG;
+    void *ws = nullptr;
+    const hipError_t e = decode_static_scratch(&ws);
+    if (e != hipSuccess) return runtime_status(e);
+    // The array is shared by calls of every shape, so its state region (epochs and flags of the split
+    // hand-over) has ONE layout, for kDecodeStaticMaxHeads heads: a call of one shape never writes partials
+    // over the state a call of another shape relies on.  The partials follow behind it.
+    return decode_common(Q, q_dtype, Kc, Vc, kv_dtype, cap, counts, comp_lens, nullptr, nullptr, 0, nullptr, false, B, Hq,
+                         Hkv, d, scale, O, o_dtype, lse, ws, kDecodeStaticArrayBytes, stream, kDecodeStaticStateBytes);
+}
+
 sc_status sc_decode_attn_tail(const void *Q, sc_dtype q_dtype, const void *Kc, const void *Vc, sc_dtype kv_dtype, int cap,
                               const int32_t *counts, const int32_t *comp_lens, const void *Kt, const void *Vt,
                               int tail_cap, const int32_t *tail_lens, int B, int Hq, int Hkv, int d, float scale,

@@ -22,6 +22,8 @@
 #include "sc_device.h"
 #include "sc_host.h"
 
+#include <mutex>
+
 namespace sc {
 
 constexpr int kDecThreads = 256;
@@ -691,6 +693,37 @@ size_t decode_workspace_bytes(int B, int Hq, int Hkv, int cap, int d) {
     // (see launch_decode; sized for any number of rows, the tail's capacity is not known here)
     const size_t mfma = (d == 128) ? multi_fast_workspace_bytes(B, Hq, Hkv, 1, 1 << 30) : 0;
     return decode_workspace_state_bytes(B, Hkv) + (split_k > mfma ? split_k : mfma);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Scratch of sc_decode_attn_static: one file-scope array per GPU, for callers that cannot hand in a
+// workspace because they cannot allocate one.  Its name is only a host-side stand-in; the device
+// address is looked up once per device and only that pointer is ever given to a kernel.  The array is
+// zero when the code object is loaded, which is the state the flags at its start must have, and
+// every call leaves them zero again.
+static __device__ __align__(256) unsigned char scratch[kDecodeStaticArrayBytes];
+static_assert(kDecodeStaticStateBytes == kDecStatusBytes + kDecodeStaticMaxHeads * sizeof(HeadSync) && kDecodeStaticStateBytes % 256 == 0,
+              "state region of the static scratch");
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices] = {};
+
+hipError_t decode_static_scratch(void **ptr) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return hipSuccess;
 }
 
 hipError_t launch_decode_init_workspace(void *ws, size_t state_bytes, hipStream_t stream) {
