@@ -30,7 +30,7 @@ constexpr int kDecThreads = 256;
 constexpr int kDecWaves = kDecThreads / kWave;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr int kDecMaxSplits = 128;
+constexpr int kDecMaxSplits = 64;
 constexpr int kDecUnroll = 4;   // loads per step of the generic kernel
 
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
@@ -203,55 +203,80 @@ constexpr int kAuxDeviceScope = 16;   // buffer-load cache policy: sc1 = device 
 
 // ------------------------------------------------------------------------------------------------
 // Fold the S split partials of one (sequence, KV head) into O; run by the workgroup of the last split.
-// A thread owns one 16-byte piece of one head's output and every NS-th split.  All its loads of a pass
-// (the (m, l) pairs and up to KMAX partial pieces) are requested before the first is used, so the fold
-// costs one trip to the partials, two barriers and one store.  s_m / s_l: S * G floats each; s_red:
-// NTHREADS * 4 floats.
+// A thread owns one 16-byte piece of one head's output and every NS-th split.  Every wavefront finds the
+// heads' maxima and denominators by itself, from the (m, l) pairs of all splits held two to eight per
+// lane and reduced with lane exchanges, so nothing has to go through LDS before the weights are known.
+// All loads of a pass (the pairs, up to KMAX partial pieces and their m) are requested before the first
+// is used: the fold costs one trip to the partials, one barrier and one store.  s_red: NTHREADS * 4 floats.
 template <int D, int G, int NTHREADS>
 __device__ __forceinline__ void combine_splits(const DecParams &p, const float *part_bh, int S, int b, int h, int tid,
-                                               float *s_m, float *s_l, float *s_red) {
+                                               float *s_red) {
     constexpr int kStride = D + kPartPad;
     constexpr int QPR = D / 4;                  // 16-byte pieces per partial row
     constexpr int COMBOS = G * QPR;             // (head, piece) pairs
     constexpr int NS = NTHREADS / COMBOS;       // split groups
     constexpr int KMAX = 6;                     // pieces in flight per thread and pass
-    static_assert(NS >= 1, "one thread per (head, piece) at least");
+    constexpr int GPW = G <= 1 ? 1 : (G <= 2 ? 2 : (G <= 4 ? 4 : 8));   // heads padded to a power of two
+    constexpr int EPL = kDecMaxSplits * GPW / kWave;                    // (split, head) pairs per lane
+    static_assert(NS >= 1 && EPL >= 1, "one thread per (head, piece) at least");
+    const int lane = tid & (kWave - 1);
     const int sg = tid / COMBOS, rem = tid - sg * COMBOS;
     const int g = rem / QPR, q4 = rem - g * QPR;
     const bool worker = sg < NS;
     // the partials of this head behind a buffer descriptor: splits beyond S read as zeros
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(part_bh), (short)0,
                                                                         S * G * kStride * 4, 0x00020000);
+    constexpr int kNowhere = 0x7FFFFFF0;        // an offset beyond any descriptor: the load returns zeros
     const int my_off = (g * kStride + 4 * q4) * 4;
     float4 x[KMAX];
+    float xm[KMAX];
     auto load_pass = [&](int s0) {
 #pragma unroll
         for (int k = 0; k < KMAX; ++k) {
             const int s = s0 + sg + NS * k;
-            // an index beyond the descriptor's range comes back as zeros
-            const u32x4_dec_t t = __builtin_amdgcn_raw_buffer_load_b128(rs, worker ? my_off + s * (G * kStride * 4) : 0x7FFFFFF0, 0,
+            const bool ok = worker && s < S;
+            const u32x4_dec_t t = __builtin_amdgcn_raw_buffer_load_b128(rs, ok ? my_off + s * (G * kStride * 4) : kNowhere, 0,
                                                                          kAuxDeviceScope);
             x[k] = make_float4(__uint_as_float(t.x), __uint_as_float(t.y), __uint_as_float(t.z), __uint_as_float(t.w));
+            xm[k] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, ok ? ((s * G + g) * kStride + D) * 4 : kNowhere, 0,
+                                                                          kAuxDeviceScope));
         }
     };
     load_pass(0);
-    for (int i = tid; i < S * G; i += NTHREADS) {
-        const u32x2_dec_t ml = __builtin_amdgcn_raw_buffer_load_b64(rs, (i * kStride + D) * 4, 0, kAuxDeviceScope);
-        s_m[i] = __uint_as_float(ml.x);
-        s_l[i] = __uint_as_float(ml.y);
+    // (m, l) of pair e = lane + 64 j: split e / GPW, head e % GPW = lane % GPW
+    const int gl = lane % GPW;
+    float em[EPL], el[EPL];
+#pragma unroll
+    for (int j = 0; j < EPL; ++j) {
+        const int s = (lane + kWave * j) / GPW;
+        const bool ok = s < S && gl < G;
+        const u32x2_dec_t ml = __builtin_amdgcn_raw_buffer_load_b64(rs, ok ? ((s * G + gl) * kStride + D) * 4 : kNowhere, 0,
+                                                                     kAuxDeviceScope);
+        em[j] = ok ? __uint_as_float(ml.x) : -INFINITY;
+        el[j] = ok ? __uint_as_float(ml.y) : 0.f;
     }
-    __syncthreads();
-    float mx = -INFINITY;
-    if (worker)
-        for (int s = 0; s < S; ++s) mx = fmaxf(mx, s_m[s * G + g]);
-    const float m_safe = (mx == -INFINITY) ? 0.f : mx;
+    float mx = em[0];
+#pragma unroll
+    for (int j = 1; j < EPL; ++j) mx = fmaxf(mx, em[j]);
+#pragma unroll
+    for (int off = GPW; off < kWave; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+    const float mx_safe = (mx == -INFINITY) ? 0.f : mx;
+    float lt = 0.f;
+#pragma unroll
+    for (int j = 0; j < EPL; ++j) lt = fmaf(el[j], fast_exp2(em[j] - mx_safe), lt);
+#pragma unroll
+    for (int off = GPW; off < kWave; off <<= 1) lt += __shfl_xor(lt, off, kWave);
+    // lane g of the wavefront holds head g's maximum and denominator
+    const float my_mx = __shfl(mx, g, kWave), my_l = __shfl(lt, g, kWave);
+    const float m_safe = (my_mx == -INFINITY) ? 0.f : my_mx;
+
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int s0 = 0; s0 < S; s0 += NS * KMAX) {
         if (s0 != 0) load_pass(s0);
 #pragma unroll
         for (int k = 0; k < KMAX; ++k) {
             const int s = s0 + sg + NS * k;
-            const float wgt = (worker && s < S) ? fast_exp2(s_m[s * G + g] - m_safe) : 0.f;
+            const float wgt = (worker && s < S) ? fast_exp2(xm[k] - m_safe) : 0.f;
             acc.x = fmaf(x[k].x, wgt, acc.x);
             acc.y = fmaf(x[k].y, wgt, acc.y);
             acc.z = fmaf(x[k].z, wgt, acc.z);
@@ -267,8 +292,7 @@ __device__ __forceinline__ void combine_splits(const DecParams &p, const float *
             const float4 t = *reinterpret_cast<const float4 *>(s_red + (r * COMBOS + rem) * 4);
             a.x += t.x; a.y += t.y; a.z += t.z; a.w += t.w;
         }
-        float l = 0.f;
-        for (int s = 0; s < S; ++s) l = fmaf(s_l[s * G + g], fast_exp2(s_m[s * G + g] - m_safe), l);
+        const float l = my_l;
         const float inv = (l > 0.f) ? 1.0f / l : 0.f;
         const float o0 = a.x * inv, o1 = a.y * inv, o2 = a.z * inv, o3 = a.w * inv;
         const int64_t ooff = ((int64_t)b * p.Hq + (int64_t)h * G + g) * D + 4 * q4;
@@ -278,7 +302,7 @@ __device__ __forceinline__ void combine_splits(const DecParams &p, const float *
             *reinterpret_cast<float4 *>(reinterpret_cast<float *>(p.O) + ooff) = make_float4(o0, o1, o2, o3);
         }
         if (q4 == 0 && p.lse)
-            p.lse[(int64_t)b * p.Hq + (int64_t)h * G + g] = (l > 0.f) ? (mx + __log2f(l)) * kLn2 : -INFINITY;
+            p.lse[(int64_t)b * p.Hq + (int64_t)h * G + g] = (l > 0.f) ? (my_mx + __log2f(l)) * kLn2 : -INFINITY;
     }
 }
 
@@ -311,8 +335,6 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
     __shared__ __attribute__((aligned(16))) float s_buf[kBufFloats];
     __shared__ float s_m[WAVES][G];
     __shared__ float s_l[WAVES][G];
-    __shared__ float s_w[kDecMaxSplits * G];
-    __shared__ float s_l2[kDecMaxSplits * G];
     __shared__ int s_last;
 
     // workgroup id = split * (B * Hkv) + (sequence, head): see publish_or_collect
@@ -489,7 +511,7 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
         file_failure<G, D>(p, hs, b, h, tid, THREADS);
         return;
     }
-    combine_splits<D, G, THREADS>(p, part_bh, S, b, h, tid, s_w, s_l2, s_buf);
+    combine_splits<D, G, THREADS>(p, part_bh, S, b, h, tid, s_buf);
     if (tid == 0) __hip_atomic_store(&hs->epoch, epoch + 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
@@ -507,8 +529,6 @@ __global__ __launch_bounds__(kDecThreads) void decode_generic_kernel(DecParams p
     __shared__ float s_acc[kDecWaves][G][D];
     __shared__ float s_m[kDecWaves][G];
     __shared__ float s_l[kDecWaves][G];
-    __shared__ float s_w[kDecMaxSplits * G];
-    __shared__ float s_l2[kDecMaxSplits * G];
     __shared__ __attribute__((aligned(16))) float s_red[kDecThreads * 4];
     __shared__ int s_last;
 
@@ -673,7 +693,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_generic_kernel(DecParams p
         file_failure<G, D>(p, hs, b, h, tid, kDecThreads);
         return;
     }
-    combine_splits<D, G, kDecThreads>(p, part_bh, S, b, h, tid, s_w, s_l2, s_red);
+    combine_splits<D, G, kDecThreads>(p, part_bh, S, b, h, tid, s_red);
     if (tid == 0) __hip_atomic_store(&hs->epoch, epoch + 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 

@@ -67,7 +67,7 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream);
 // sc_decode_attn_static: device address of the current GPU's file-scope scratch array (looked up once per device)
 constexpr size_t kDecodeStaticScratchBytes = (size_t)16 << 20;
 constexpr int kDecodeStaticMaxHeads = 1024;   // (sequence, KV head) pairs its state region is laid out for, whatever the call's shape
-constexpr size_t kDecodeStaticStateBytes = 256 + (size_t)kDecodeStaticMaxHeads * 1032;   // = decode_workspace_state_bytes(1, 1024)
+constexpr size_t kDecodeStaticStateBytes = 256 + (size_t)kDecodeStaticMaxHeads * 520;   // = decode_workspace_state_bytes(1, 1024)
 constexpr size_t kDecodeStaticArrayBytes = kDecodeStaticScratchBytes + kDecodeStaticStateBytes;
 hipError_t decode_static_scratch(void **ptr);
 
