@@ -237,19 +237,7 @@ def main():
             seg_only()
 
     gsc_ms = timed([capture(gsc_round)], 10, N_KV_COPIES)
-    # the kernels of the call one by one (the workspace still holds what the complete calls above left)
     stage_us = {}
-    if sc.tune_get("gsc_fast_path") and w.dtype == "bf16" and d == 128:
-        stages = [("gsc_compress_kernel", 1), ("gsc_relocate_kernel", 4)]
-        if N > 32768:
-            stages.insert(1, ("gsc_scan_kernel", 2))   # shorter sequences fold the scan into the relocation
-        for name, bit in stages:
-            sc.tune_set("gsc_stages", bit)
-            try:
-                g1 = capture(gsc_round)
-            finally:
-                sc.tune_set("gsc_stages", 7)
-            stage_us[name] = timed([g1], 10, N_KV_COPIES) * 1e3
     seg_ms = timed([capture(seg_round)], 10, 8)
     dec_call_ms = timed([capture(lambda i=i: dec_only(i)) for i in range(4)], 16, w.decode_steps)
     # plain device-to-device copy of one K copy (read 67 MB + write 67 MB) as an attainable-bandwidth reference

@@ -337,8 +337,6 @@ sc_status sc_multi_attn(const void *Q, sc_dtype q_dtype, int nq,
  *   "gsc_chunks_per_task"  fast path: chunks handled by one single-wave workgroup task (1..32)
  *   "gsc_chunks_per_item"  generic path: chunks per work item
  *   "gsc_grid_x"           workgroups per (sequence, KV head); <= 0 = chosen from B*Hkv
- *   "gsc_stages"           fast path, for per-kernel timing only: bit 0 cluster+merge, bit 1 scan,
- *                          bit 2 relocation; anything but 7 leaves the outputs of the call incomplete
  * Return 0 / the value, or -1 for an unknown key.
  */
 int sc_tune_set(const char *key, int value);

@@ -28,16 +28,6 @@ typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2f_t;
 typedef short short4_t __attribute__((ext_vector_type(4)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
-#ifdef SC_GSC_TIMING
-// development builds: per-wave timestamps into the unused upper half of the key staging area
-// (every lane stores the same word: a lane-dependent branch here changes the control flow under study)
-#define SC_GSTAMP(k) do { dbg[(((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 1 + wave) * 16 + (k)] = wall_clock64(); } while (0)
-#define SC_GVAL(k, v) do { dbg[(((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 1 + wave) * 16 + (k)] = (unsigned long long)(v); } while (0)
-#else
-#define SC_GSTAMP(k) do {} while (0)
-#define SC_GVAL(k, v) do {} while (0)
-#endif
-
 
 constexpr int kFastD = 128;
 constexpr int kWin = 64;                 // rows of a window
@@ -330,12 +320,6 @@ __device__ __forceinline__ uint32_t or_rows(uint32_t x) {   // OR over the four 
     return r[0] | r[1];
 }
 
-#ifdef SC_GSC_TIMING
-#define SC_ISTAMP(k) do { if (stamps) stamps[k] = wall_clock64(); } while (0)
-#else
-#define SC_ISTAMP(k) do {} while (0)
-#endif
-
 // Gram tiles (I, J), I <= J < NT, of the rows parked in LDS; tile k = index in the 4 x 4 upper triangle
 template <int NT>
 __device__ __forceinline__ void gram_tiles(const char *lds, int g, int c, floatx4_t (&acc)[10]) {
@@ -363,9 +347,7 @@ __device__ __forceinline__ void gram_tiles(const char *lds, int g, int c, floatx
 // norm is unusable.  The common case (no pair of the window anywhere near tau) never builds the
 // unsure words: every lane tracks the smallest distance to tau it has seen instead.
 __device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, int R, float tau, int lane,
-                                               uint64_t &yes_row, uint64_t &unsure_row, unsigned long long *stamps = nullptr) {
-    (void)stamps;
-    SC_ISTAMP(10);
+                                               uint64_t &yes_row, uint64_t &unsure_row) {
     const int g = lane >> 4, c = lane & 15;
     float *s_rinv = reinterpret_cast<float *>(lds + kLdsRinvOff);
     uint32_t *s_bits = reinterpret_cast<uint32_t *>(lds + kLdsBitsOff);
@@ -374,7 +356,6 @@ __device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, int 
         *reinterpret_cast<uint4 *>(lds + (4 * t + g) * kLdsRowBytes + 16 * c) = x.r[t];
     *reinterpret_cast<uint4 *>(s_bits + 4 * lane) = make_uint4(0u, 0u, 0u, 0u);
     wave_lds_fence();
-    SC_ISTAMP(11);
 
     const int nt = (R + 15) >> 4;   // 16-row tiles in use
     floatx4_t acc[10];
@@ -384,7 +365,6 @@ __device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, int 
     else if (nt == 3) gram_tiles<3>(lds, g, c, acc);
     else if (nt == 2) gram_tiles<2>(lds, g, c, acc);
     else gram_tiles<1>(lds, g, c, acc);
-    SC_ISTAMP(12);
     // squared norms are the diagonal of the Gram matrix: tile (I, I), row 4g+i == column c
     {
         const int kd[4] = {0, 4, 7, 9};
@@ -438,7 +418,6 @@ __device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, int 
                 }
             }
     }
-    SC_ISTAMP(13);
     // complete the words over the four lane groups; lane r = 16J + c keeps the words of its own row
     uint32_t yl = 0u, yh = 0u;
 #pragma unroll
@@ -534,8 +513,6 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
     const int wg_x = rem_id / n_bh_grid, bh_id = rem_id - wg_x * n_bh_grid;
     const int b = bh_id / p.Hkv, h = bh_id - b * p.Hkv;
     const int lane_id = threadIdx.x;
-    const int wave = 0;
-    (void)wave;
     const int C = p.chunks_per_item;
     // The offsets of the workgroup's first task are requested together with the chunk count instead of
     // after it (which offsets are meaningful is decided once the count is known; the index is clamped to
@@ -560,13 +537,6 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
     TO *vtmp_c = reinterpret_cast<TO *>(p.vtmp) + bh * (int64_t)p.N_max * kFastD;
     const int64_t tmp_rows = p.N_max;
     const float tau = p.tau_dev ? *p.tau_dev : p.tau;
-#ifdef SC_GSC_TIMING
-    // development builds only: timestamps go to the upper half of the value staging area, which a bf16
-    // output never touches (the area is sized for fp32 output)
-    unsigned long long *dbg = reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(p.vtmp) + (size_t)p.B * p.Hkv * p.N_max * kFastD * 2);
-    int first_window = 1;
-#endif
-    SC_GSTAMP(0);
 
     for (int task = wg_x; task < tasks; task += p.grid_x) {
         TaskOffsets to;
@@ -576,7 +546,6 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
         const int nch = min(C, M - m0);
         if (task == wg_x) to.v = (lane_id <= nch) ? first_v : 0;
         else to.v = (lane_id <= nch) ? off[m0 + lane_id] : 0;
-        SC_GSTAMP(1);
         {
             const int task_rows = to.at(nch) - to.at(0) - ((m0 + nch == M) ? 1 : 0);
             if ((task_rows > kWin) != (pass == 0)) continue;
@@ -614,12 +583,7 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                     if (lane >= cs && lane < ce) { lo = cs; hi = ce; in_chunk = true; }
                 }
                 uint64_t yes_row, unsure_row;
-#ifdef SC_GSC_TIMING
-                gram_bitmatrix(s_lds, xk, R, tau, lane, yes_row, unsure_row, first_window ? dbg + ((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 : nullptr);
-                if (first_window) { SC_GSTAMP(2); }
-#else
                 gram_bitmatrix(s_lds, xk, R, tau, lane, yes_row, unsure_row);
-#endif
                 // Alg. 1 on the bit matrix, one seed per chunk and round: the first unassigned row of a
                 // chunk is its next seed and absorbs the unassigned rows of the chunk whose bit is set
                 const uint64_t my_range = bits_range(lo, hi);
@@ -669,9 +633,6 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                 // seeds in row order are the output rows of the window
                 const int nseed = __popcll(seedmask);
                 const int my_o = (lane < R) ? __popcll(seedmask & bits_range(0, my_seed)) : -1;
-#ifdef SC_GSC_TIMING
-                if (first_window) { SC_GSTAMP(3); SC_GVAL(8, nseed); SC_GVAL(9, R); }
-#endif
                 if (cid_bh && lane < R)
                     cid_bh[w0 + lane] = in_chunk ? __popcll(seedmask & bits_range(lo, my_seed)) : -1;
                 {
@@ -692,9 +653,6 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                     store_tile<TO>(DV, Dn, ot, nseed, vtmp_c, (int64_t)w0, tmp_rows, lane);
                     store_sizes(Dn, ot, nseed, stmp_bh, (int64_t)w0, tmp_rows, lane);
                 }
-#ifdef SC_GSC_TIMING
-                if (first_window) { SC_GSTAMP(6); first_window = 0; }
-#endif
                 idx = idx_hi;
             } else {
                 // ---------------- one chunk longer than a window: one sweep over blocks of 64 rows.
@@ -909,7 +867,6 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                 idx += 1;
             }
         }
-        SC_GSTAMP(5);
     }
 }
 
@@ -1049,24 +1006,18 @@ hipError_t launch_gsc_fast(const GscParams &p, hipStream_t stream) {
     pc.grid_x = gx;
     const dim3 grid2((unsigned)(2 * gx * p.Hkv * p.B));   // two passes over the tasks: long ones first
     const dim3 grid1((unsigned)(gx * p.Hkv * p.B));
-    // gsc_stages exists so that a benchmark can time each kernel of the call by itself on a workspace
-    // that a complete call has filled before; anything but 7 leaves the outputs incomplete
-    const int stages = tuning().gsc_stages;
-    hipError_t e = hipSuccess;
-    if (stages & 1) {
-        if (p.out_is_bf16) hipLaunchKernelGGL((gsc_compress_kernel<bf16_t>), grid2, dim3(kFastTaskThreads), 0, stream, pc);
-        else hipLaunchKernelGGL((gsc_compress_kernel<float>), grid2, dim3(kFastTaskThreads), 0, stream, pc);
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
+    if (p.out_is_bf16) hipLaunchKernelGGL((gsc_compress_kernel<bf16_t>), grid2, dim3(kFastTaskThreads), 0, stream, pc);
+    else hipLaunchKernelGGL((gsc_compress_kernel<float>), grid2, dim3(kFastTaskThreads), 0, stream, pc);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
     // up to 32k tokens the relocation adds up the cluster counts before its task itself; longer sequences
     // (more chunks to add up per workgroup) get the scan kernel
     const bool inline_prefix = p.N_max <= 32768;
-    if ((stages & 2) && !inline_prefix) {
+    if (!inline_prefix) {
         e = launch_gsc_scan(p, stream);
         if (e != hipSuccess) return e;
     }
-    if (stages & 4) {
+    {
         if (inline_prefix) {
             if (p.base_lens) {
                 if (p.out_is_bf16) hipLaunchKernelGGL((gsc_relocate_kernel<bf16_t, true, true>), grid1, dim3(kFastTaskThreads), 0, stream, pc);

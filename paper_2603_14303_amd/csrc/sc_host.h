@@ -108,7 +108,6 @@ struct Tuning {
     int gsc_grid_x = 0;             // workgroups per (sequence, KV head); <= 0 picks it from B*Hkv
     int gsc_chunks_per_task = 2;    // fast path: chunks handled by one single-wave workgroup
     int gsc_fast_path = 1;          // 0 forces the generic kernels even for bf16 / d = 128
-    int gsc_stages = 7;             // fast path, for timing: bit 0 compress, bit 1 scan, bit 2 relocate
 };
 Tuning &tuning();
 
