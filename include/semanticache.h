@@ -323,6 +323,18 @@ sc_status sc_multi_attn(const void *Q, sc_dtype q_dtype, int nq,
                         void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * sc_stream_read_probe — a measuring aid for benchmarks, not a step of the method: reads the first
+ * `bytes` bytes (rounded down to a multiple of 16) of a device buffer once, 16 bytes per lane, fully
+ * coalesced, eight loads in flight per lane, i.e. with the access pattern of the kernels above and
+ * nothing else to do.  Timing it on a buffer much larger than the caches gives the HBM read bandwidth
+ * a kernel can attain on the device, to put beside the nominal peak the rooflines are quoted against.
+ *   src             device buffer, 16-byte aligned
+ *   sink            device scratch of at least 4 KiB that the kernel writes to (contents meaningless)
+ * Host errors: NULL pointers, bytes < 16, misaligned pointers.
+ */
+sc_status sc_stream_read_probe(const void *src, size_t bytes, void *sink, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
  * Launch-shape knobs for experiments (process-wide, not thread-safe; results never depend on them
  * beyond floating-point summation order).  Keys:
  *   "decode_max_splits"    split-K workgroups per (sequence, KV head); <= 0 = chosen from B*Hkv

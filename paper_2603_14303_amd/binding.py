@@ -46,6 +46,8 @@ def load_library() -> ctypes.CDLL:
     lib.sc_tune_get.argtypes = [c.c_char_p]
     lib.sc_check_lengths.restype = i32
     lib.sc_check_lengths.argtypes = [vp, i32, c.POINTER(c.c_int), vp]
+    lib.sc_stream_read_probe.restype = i32
+    lib.sc_stream_read_probe.argtypes = [vp, sz, vp, vp]
     lib.sc_segment_workspace_bytes.restype = sz
     lib.sc_segment_workspace_bytes.argtypes = [i32, i32]
     lib.sc_segment.restype = i32
@@ -90,7 +92,7 @@ def load_library() -> ctypes.CDLL:
 
 EXPORTED = [
     "sc_status_string", "sc_last_runtime_error", "sc_version", "sc_tune_set", "sc_tune_get",
-    "sc_check_lengths", "sc_segment_workspace_bytes", "sc_segment",
+    "sc_check_lengths", "sc_stream_read_probe", "sc_segment_workspace_bytes", "sc_segment",
     "sc_gsc_merge_workspace_bytes", "sc_gsc_merge",
     "sc_decode_attn_workspace_bytes", "sc_decode_attn_init_workspace", "sc_decode_attn",
     "sc_decode_attn_static", "sc_decode_attn_tail", "sc_gsc_merge_append",
@@ -373,6 +375,13 @@ def sc_gsc_merge_budget(K, V, offsets, num_chunks, budget_rows: int, tau_lo: flo
                                  _ptr(cluster_id), _ptr(tau), _ptr(rows), workspace.ptr, workspace.nbytes, _stream())
     _check(st, "sc_gsc_merge_budget")
     return Kc, Vc, counts, comp_lens, cluster_id, tau, rows
+
+
+def stream_read_probe(buf, sink) -> None:
+    """Reads the device tensor `buf` once (measuring aid: time it to get the attainable HBM read bandwidth)."""
+    _require_cuda(buf, sink)
+    st = load_library().sc_stream_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream())
+    _check(st, "sc_stream_read_probe")
 
 
 def check_lengths(lengths) -> int:

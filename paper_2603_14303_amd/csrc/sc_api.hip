@@ -99,6 +99,12 @@ sc_status sc_check_lengths(const int32_t *lengths, int count, int *first_bad, vo
 }
 
 // ------------------------------------------------------------------------------------------------
+sc_status sc_stream_read_probe(const void *src, size_t bytes, void *sink, void *stream) {
+    if (!src || !sink || bytes < 16 || !aligned16(src) || !aligned4(sink)) return SC_ERR_INVALID_ARG;
+    return runtime_status(launch_stream_read_probe(src, bytes, sink, static_cast<hipStream_t>(stream)));
+}
+
+// ------------------------------------------------------------------------------------------------
 size_t sc_segment_workspace_bytes(int B, int N_max) {
     (void)B; (void)N_max;
     return 0;

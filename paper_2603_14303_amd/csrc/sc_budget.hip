@@ -3,7 +3,7 @@
 // The paper reports its results at cache budgets (Sec. 3.1: 20 / 35 / 50 % of the entries kept) but does
 // not say how a budget becomes the threshold tau of Alg. 1.  The number of rows N'(tau) grows with tau
 // (a higher bar merges less), so the largest tau that still meets the budget is found by bisection.
-// Every probe is a complete sc_gsc_merge; the threshold lives in device memory, a one-thread kernel
+// Every probe is the clustering half of sc_gsc_merge (counts only); the threshold lives in device memory, a one-thread kernel
 // between two probes reads the merged lengths of the last one and moves the bracket, so the whole
 // search is a fixed sequence of launches on the caller's stream with no host synchronisation.  The
 // last launch runs at the threshold found and leaves its merged cache in the outputs.
@@ -75,6 +75,9 @@ hipError_t launch_gsc_budget(GscMergeArgs a, long long budget_rows, float tau_lo
     }
     a.tau_dev = &st->tau;
     for (int it = 0; it <= iterations; ++it) {     // `iterations` probes, then the launch at the result
+        // a probe only needs the row counts: clustering without reading the values, without the merge and
+        // without writing rows (where the fast path runs; elsewhere a probe is a full merge)
+        a.count_only = it < iterations;
         e = launch_gsc_merge(a, stream);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(budget_update_kernel, dim3(1), dim3(256), 0, stream, st, a.comp_lens, a.B * a.Hkv, budget_rows,

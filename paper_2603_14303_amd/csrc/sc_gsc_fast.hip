@@ -121,6 +121,11 @@ __device__ __forceinline__ bool cosine_exceeds_f64_fast(const bf16_t *seed_row, 
     return dot / (sqrt(ss) * sqrt(cc)) > (double)tau;   // NaN compares false
 }
 
+// the same for two rows of the window / block parked in LDS by gram_bitmatrix (the parked bf16 values are
+// the inputs themselves, so the result is the same; the rows come back in a tenth of the time of a
+// trip to memory, which matters when tau lies inside the band of the similarities and many pairs are redone)
+__device__ __forceinline__ bool cosine_exceeds_f64_lds(const char *lds, int row_a, int row_b, float tau, int lane);
+
 __device__ __forceinline__ float safe_rinv(float nsq) {
     // a norm that is zero, denormal, huge or not a number makes every cosine with that row "unsure"
     return (nsq > 1e-30f && nsq < 1e30f) ? __frsqrt_rn(nsq) : __builtin_nanf("");
@@ -467,6 +472,21 @@ __device__ __forceinline__ void gram_bitmatrix(char *lds, const RowRegs &x, int 
     wave_lds_fence();   // the LDS area is reused by the next window
 }
 
+__device__ __forceinline__ bool cosine_exceeds_f64_lds(const char *lds, int row_a, int row_b, float tau, int lane) {
+    double dot = 0.0, ss = 0.0, cc = 0.0;
+#pragma unroll
+    for (int k = 0; k < kFastD / kWave; ++k) {
+        const int e = (lane & (kWave - 1)) + k * kWave;
+        const double a = load1_f64(reinterpret_cast<const bf16_t *>(lds + row_a * kLdsRowBytes) + e);
+        const double b = load1_f64(reinterpret_cast<const bf16_t *>(lds + row_b * kLdsRowBytes) + e);
+        dot += a * b; ss += a * a; cc += b * b;
+    }
+    dot = wave_allreduce_sum(dot);
+    ss = wave_allreduce_sum(ss);
+    cc = wave_allreduce_sum(cc);
+    return dot / (sqrt(ss) * sqrt(cc)) > (double)tau;   // NaN compares false
+}
+
 // ------------------------------------------------------------------------------------------------
 // Work decomposition shared by both passes: a task is `chunks_per_item` (<= 32) consecutive chunks of
 // one (sequence, head), handled by one single-wavefront workgroup, so a finished task frees its
@@ -537,6 +557,7 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
     TO *vtmp_c = reinterpret_cast<TO *>(p.vtmp) + bh * (int64_t)p.N_max * kFastD;
     const int64_t tmp_rows = p.N_max;
     const float tau = p.tau_dev ? *p.tau_dev : p.tau;
+    const bool count_only = p.count_only != 0;
 
     for (int task = wg_x; task < tasks; task += p.grid_x) {
         TaskOffsets to;
@@ -573,7 +594,8 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                 RowRegs xk, xv;
                 load_rows(xk, row_source(Kbh, p.stride_n, w0, R, g, c));
                 // the values are not needed before the merge: requested now, they arrive under the Gram step
-                load_rows(xv, row_source(Vbh, p.stride_n, w0, R, g, c));
+                // (a counting call reads none: the descriptor is empty and the loads come back as zeros)
+                load_rows(xv, row_source(Vbh, p.stride_n, w0, count_only ? 0 : R, g, c));
                 // chunk range [lo, hi) of every row; a delimiter is a one-row range of its own
                 int lo = lane, hi = lane + 1;
                 bool in_chunk = false;
@@ -620,8 +642,7 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                         const int j = __builtin_amdgcn_readfirstlane(first_bit(recheck));
                         recheck &= recheck - 1ull;
                         const int sj = __builtin_amdgcn_readlane(s, j);
-                        const bool res = cosine_exceeds_f64_fast(Kbh + (int64_t)(w0 + sj) * p.stride_n,
-                                                                 Kbh + (int64_t)(w0 + j) * p.stride_n, tau, lane);
+                        const bool res = cosine_exceeds_f64_lds(s_lds, sj, j, tau, lane);
                         if (lane == j) yes = res;
                     }
                     const uint64_t seeds_now = ballot64(is_seed);
@@ -644,7 +665,7 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                 uint32_t ob[4];
                 orow_to_operand_bytes_lds(s_lds + kLdsIdxOff, my_o, lane, ob);
                 const int q_hi = (R + 15) >> 4;
-                for (int ot = 0; ot * 16 < nseed; ++ot) {
+                for (int ot = 0; ot * 16 < nseed && !count_only; ++ot) {
                     floatx4_t DK[8], DV[8], Dn = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int j = 0; j < 8; ++j) DK[j] = DV[j] = Dn;
@@ -687,7 +708,7 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                         gram_bitmatrix(s_lds, x, R, tau, lane, yes_row, unsure_row);
                     }
                     RowRegs xv;
-                    load_rows(xv, row_source(Vbh, p.stride_n, start + rb, R, g, c));
+                    load_rows(xv, row_source(Vbh, p.stride_n, start + rb, count_only ? 0 : R, g, c));
                     uint64_t todo = bits_range(0, R);
                     int my_o = -1;
                     const int seeds_before = nseeds;
@@ -795,8 +816,7 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                         while (recheck != 0ull) {
                             const int j = __builtin_amdgcn_readfirstlane(first_bit(recheck));
                             recheck &= recheck - 1ull;
-                            const bool res = cosine_exceeds_f64_fast(block0 + (int64_t)i * p.stride_n,
-                                                                     block0 + (int64_t)j * p.stride_n, tau, lane);
+                            const bool res = cosine_exceeds_f64_lds(s_lds, i, j, tau, lane);
                             if (lane == j) yes = res;
                         }
                         const uint64_t got = ballot64(yes);
@@ -817,11 +837,15 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                     // sums of the first sixteen clusters
                     uint32_t ob[4];
                     orow_to_operand_bytes_lds(s_lds + kLdsIdxOff, (lane < R) ? my_o : -1, lane, ob);
-                    membership_mfma_kv(s_lds, xv, ob, c, nt, lane, DK, DV, Dn);
+                    if (!count_only) membership_mfma_kv(s_lds, xv, ob, c, nt, lane, DK, DV, Dn);
                     wave_lds_fence();   // the next block overwrites the parked keys and the seed tables are read above
                 }
                 if (closed && lane == 0 && cid_bh) cid_bh[start + l] = -1;
                 if (lane == 0) pcount_bh[m0 + idx] = nseeds;
+                if (count_only) {
+                    idx += 1;
+                    continue;
+                }
                 {
                     const int n0 = min(nseeds, 16);
                     store_tile<TO>(DK, Dn, 0, n0, ktmp_c, (int64_t)start, tmp_rows, lane);
@@ -1010,6 +1034,7 @@ hipError_t launch_gsc_fast(const GscParams &p, hipStream_t stream) {
     else hipLaunchKernelGGL((gsc_compress_kernel<float>), grid2, dim3(kFastTaskThreads), 0, stream, pc);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (p.count_only) return launch_gsc_scan(p, stream);   // adds up the counts: comp_lens, and nothing else is wanted
     // up to 32k tokens the relocation adds up the cluster counts before its task itself; longer sequences
     // (more chunks to add up per workgroup) get the scan kernel
     const bool inline_prefix = p.N_max <= 32768;

@@ -423,6 +423,7 @@ hipError_t launch_gsc_merge(const GscMergeArgs &a, hipStream_t stream) {
     p.cap = a.cap;
     p.counts = a.counts; p.comp_lens = a.comp_lens;
     p.base_lens = a.base_lens;
+    p.count_only = a.count_only ? 1 : 0;
     p.chunks_per_item = max(1, min(kMaxChunksPerItem, tuning().gsc_chunks_per_item));
 
     const size_t bh = (size_t)a.B * a.Hkv;

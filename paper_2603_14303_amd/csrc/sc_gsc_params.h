@@ -32,6 +32,7 @@ struct GscParams {
     void *ktmp;           // [B, Hkv, N_max, d] merged keys at provisional rows (fast path)
     void *vtmp;           // [B, Hkv, N_max, d] merged values at provisional rows (fast path)
     int32_t *stmp;        // [B, Hkv, N_max]   cluster sizes at provisional rows (fast path)
+    int count_only;       // fast path: cluster and count only (per-chunk cluster counts and comp_lens); no values are read, no rows written
     int chunks_per_item;
     int grid_x;           // fast path: workgroups per pass and (sequence, head) of the compress kernel
 };

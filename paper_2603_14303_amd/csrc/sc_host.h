@@ -31,6 +31,7 @@ struct GscMergeArgs {
     int32_t *counts, *comp_lens, *cluster_id;
     const int32_t *base_lens = nullptr;   // append mode: rows already in the outputs, [B, Hkv]
     const float *tau_dev = nullptr;       // threshold in device memory (overrides tau)
+    bool count_only = false;              // only comp_lens is produced (bf16 / d = 128 fast path; elsewhere the full merge runs)
     void *ws;
 };
 size_t gsc_merge_workspace_bytes(int B, int Hkv, int N_max, int d);
@@ -96,6 +97,9 @@ hipError_t launch_multi(const MultiArgs &a, hipStream_t stream);
 // matrix-core path alone (bf16, d = 128): partials in a.ws, no state
 size_t multi_fast_workspace_bytes(int B, int Hq, int Hkv, int nq, int cap);
 hipError_t launch_multi_fast(const MultiArgs &a, hipStream_t stream);
+
+// ---- measuring aid: streaming read of a buffer
+hipError_t launch_stream_read_probe(const void *src, size_t bytes, void *sink, hipStream_t stream);
 
 // tuning knobs (read by the launchers; set through sc_tune_set)
 struct Tuning {

@@ -78,6 +78,18 @@ def test_truncated_workloads(name, n, tau):
     print(name, n, tau, "redraws", case["redraws"], "merge_err %.2e" % out["worst_merge_err"], "decode", errs)
 
 
+@pytest.mark.parametrize("base,dtype,d", [("layer32k", "bf16", 64), ("tiny", "f32", 128), ("tiny", "bf16", 128)])
+def test_other_dtype_and_head_dim_combinations(base, dtype, d):
+    # the combinations the header promises beyond the two the workloads use (bf16 / 128 and fp32 / 64):
+    # bf16 with d = 64 and fp32 with d = 128 through sc_gsc_merge (generic kernels) and sc_decode_attn
+    import dataclasses
+    w = dataclasses.replace(wl.get_workload(base), dtype=dtype, head_dim=d, kv_heads=2, q_heads=8)
+    case = build_case(w, 0.7, n_max=1500 + 3)
+    out = g.check_compress(case)
+    errs = g.check_decode(case, out, range(3))
+    print(base, dtype, d, "redraws", case["redraws"], "merge_err %.2e" % out["worst_merge_err"], "decode", errs)
+
+
 def test_layer32k_full_size():
     w = wl.get_workload("layer32k")
     case = build_case(w, 0.7)
