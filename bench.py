@@ -206,7 +206,7 @@ def main():
     n_bufs = L if L > 1 else N_CACHE_BUFS   # merged caches: one per layer, or the rotating buffers
 
     # merged-cache capacity: generous but not N_max, so the cache buffers stay small
-    cap = max(1024, N // 4) if tau < 0.9 else max(1024, N // 2)
+    cap = max(1024, N // 4) if tau < 0.9 else (max(1024, 5 * N // 8) if tau < 0.985 else N + 1)
     offsets = torch.empty((B, N + 2), dtype=torch.int32, device=dev)
     num_chunks = torch.empty((B,), dtype=torch.int32, device=dev)
     bufs = [dict(Kc=torch.empty((B, H, cap, d), dtype=torch.bfloat16, device=dev),

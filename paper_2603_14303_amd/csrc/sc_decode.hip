@@ -35,6 +35,7 @@ constexpr int kDecUnroll = 4;   // loads per step of the generic kernel
 
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef short dec_short4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
@@ -401,23 +402,23 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
 
     // owner-lane state: lane c of a row owns head (c % GP); replicated over the 16/GP lanes of its orbit
     float m_run = -INFINITY, l_run = 0.f;
-    float acc[GP][8];
+    if constexpr (GP == 4) {
+        // Scores on the vector unit, O += P V on the matrix cores (v_mfma_f32_16x16x16_bf16): the 16 rows of
+        // a step are the contraction index, A[m][k] = probability of head m for row k (rows 4..15 of A are
+        // zero), B[k][n] = element 8c + j of row k for the lane's column n = c, one product per j.  The k
+        // index (lane / 16, i) of both operands stands for row 4i + lane / 16, which is register i of the
+        // lane's own group, so B is built from the loaded registers with two byte permutes per product.
+        // The result adds up the rows of all four lane groups: the lane groups share one running maximum
+        // per head, and lanes 0..15 end up with the whole wave's sums: accm[j][i] = head i, element 8c + j.
+        // P enters as two bf16 parts (leading part and remainder), so its rounding error is 2^-18.
+        f32x4_t accm[8];
 #pragma unroll
-    for (int hh = 0; hh < GP; ++hh)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[hh][e] = 0.f;
-
-    while (base < r1) {
-        float pb[NT][16];
-        float al[NT][GP];
-        bool moved[NT];
-#pragma unroll
-        for (int half = 0; half < NT; ++half) {
-            // ---- scores: UH loads x GP heads = 16 partials -> one full dot product per lane
+        for (int j = 0; j < 8; ++j) accm[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        while (base < r1) {
             float part[16];
 #pragma unroll
-            for (int uu = 0; uu < UH; ++uu) {
-                const uint4 kk = kb[half * UH + uu];
+            for (int uu = 0; uu < U; ++uu) {
+                const uint4 kk = kb[uu];
 #pragma unroll
                 for (int hh = 0; hh < GP; ++hh) {
                     float s = dot2_bf16(kk.x, q[hh].x, 0.f);
@@ -430,59 +431,143 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
             // lane c owns (load uu = c / GP, head c % GP)
             int cnt = 0;
 #pragma unroll
-            for (int uu = 0; uu < UH; ++uu) cnt = (c / GP == uu) ? cb[half * UH + uu] : cnt;
+            for (int uu = 0; uu < U; ++uu) cnt = (c / GP == uu) ? cb[uu] : cnt;
             s = (cnt > 0) ? fmaf(s, p.scale_log2, __log2f((float)cnt)) : -INFINITY;
-            const float m_new = orbit_max<GP>(fmaxf(s, m_run));
+            const float m_new = rows_allreduce_max(orbit_max<GP>(fmaxf(s, m_run)));
             const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
             const float alpha = fast_exp2(m_run - m_safe);
             const float pw = fast_exp2(s - m_safe);
-            l_run = fmaf(l_run, alpha, orbit_sum<GP>(pw));
+            l_run = fmaf(l_run, alpha, orbit_sum<GP>(pw));    // per lane group; the groups are added up after the loop
             m_run = m_new;
-            moved[half] = ballot64(alpha != 1.0f) != 0ull;
-            if (moved[half]) BcastAll<GP>::run(alpha, al[half]);
-            BcastAll<16>::run(pw, pb[half]);
-        }
+            if (ballot64(alpha != 1.0f) != 0ull) {
+                float al[GP];
+                BcastAll<GP>::run(alpha, al);
 #pragma unroll
-        for (int half = 0; half < NT; ++half) {
-            if (moved[half]) {
+                for (int j = 0; j < 8; ++j)
 #pragma unroll
-                for (int hh = 0; hh < GP; ++hh)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[hh][e] *= al[half][hh];
+                    for (int i = 0; i < 4; ++i) accm[j][i] *= al[i];
             }
+            // A operand of lane (g, c < 4): head c, rows 4i + g (i = 0..3), which lanes (g, 4i + c) own
+            float pi[4];
+            pi[0] = pw;
+            pi[1] = dpp<0x104>(pw);      // row_shl:4  -- lane c reads lane c + 4 of its 16-lane row
+            pi[2] = dpp<0x108>(pw);
+            pi[3] = dpp<0x10C>(pw);
 #pragma unroll
-            for (int uu = 0; uu < UH; ++uu) {
-                const uint4 vv = vb[half * UH + uu];
-                const float x[8] = {bf16_lo(vv.x), bf16_hi(vv.x), bf16_lo(vv.y), bf16_hi(vv.y),
-                                    bf16_lo(vv.z), bf16_hi(vv.z), bf16_lo(vv.w), bf16_hi(vv.w)};
+            for (int i = 0; i < 4; ++i) pi[i] = (c < GP) ? pi[i] : 0.f;
+            const uint32_t h01 = pack_bf16x2(pi[0], pi[1]), h23 = pack_bf16x2(pi[2], pi[3]);
+            const uint32_t r01 = pack_bf16x2(pi[0] - bf16_lo(h01), pi[1] - bf16_hi(h01));
+            const uint32_t r23 = pack_bf16x2(pi[2] - bf16_lo(h23), pi[3] - bf16_hi(h23));
+            const dec_short4 a_hi = __builtin_bit_cast(dec_short4, make_uint2(h01, h23));
+            const dec_short4 a_lo = __builtin_bit_cast(dec_short4, make_uint2(r01, r23));
 #pragma unroll
-                for (int hh = 0; hh < GP; ++hh)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[hh][e] = fmaf(pb[half][uu * GP + hh], x[e], acc[hh][e]);
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t d0 = dword_of(vb[0], j >> 1), d1 = dword_of(vb[1], j >> 1);
+                const uint32_t d2 = dword_of(vb[2], j >> 1), d3 = dword_of(vb[3], j >> 1);
+                const uint32_t lo = (j & 1) ? pack_hi(d0, d1) : pack_lo(d0, d1);
+                const uint32_t hi = (j & 1) ? pack_hi(d2, d3) : pack_lo(d2, d3);
+                const dec_short4 bb = __builtin_bit_cast(dec_short4, make_uint2(lo, hi));
+                accm[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_hi, bb, accm[j], 0, 0, 0);
+                accm[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_lo, bb, accm[j], 0, 0, 0);
             }
+            base += kRowsPerBlockStep;
+            if (base < r1) issue(base);
         }
-        // the other 15 waves of the workgroup keep the memory pipe busy while this one computes
-        base += kRowsPerBlockStep;
-        if (base < r1) issue(base);
-    }
-    // ---- fold the RPW lane groups of the wave (each saw different rows), then park in LDS
-    {
-        const float mw = rows_allreduce_max(m_run);
-        const float m_safe = (mw == -INFINITY) ? 0.f : mw;
-        const float f = fast_exp2(m_run - m_safe);    // this lane group's factor for head c % GP
-        const float lw = rows_allreduce_sum(l_run * f);
-        float fh[GP];
-        BcastAll<GP>::run(f, fh);
+        // ---- park the wave's sums in LDS (m_run is already the same in all lane groups)
+        const float lw = rows_allreduce_sum(l_run);
+        if (g == 0) {
 #pragma unroll
-        for (int hh = 0; hh < GP; ++hh) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[hh][e] = rows_allreduce_sum(acc[hh][e] * fh[hh]);
-            if (hh < G && g == 0) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) s_buf[(wave * G + hh) * D + 8 * c + e] = acc[hh][e];
+            for (int i = 0; i < G; ++i) {
+                float *dst = s_buf + (wave * G + i) * D + 8 * c;
+                *reinterpret_cast<float4 *>(dst) = make_float4(accm[0][i], accm[1][i], accm[2][i], accm[3][i]);
+                *reinterpret_cast<float4 *>(dst + 4) = make_float4(accm[4][i], accm[5][i], accm[6][i], accm[7][i]);
             }
+            if (c < G) { s_m[wave][c] = m_run; s_l[wave][c] = lw; }
         }
-        if (g == 0 && c < G) { s_m[wave][c] = mw; s_l[wave][c] = lw; }
+    } else {
+        float acc[GP][8];
+    #pragma unroll
+        for (int hh = 0; hh < GP; ++hh)
+    #pragma unroll
+            for (int e = 0; e < 8; ++e) acc[hh][e] = 0.f;
+
+        while (base < r1) {
+            float pb[NT][16];
+            float al[NT][GP];
+            bool moved[NT];
+    #pragma unroll
+            for (int half = 0; half < NT; ++half) {
+                // ---- scores: UH loads x GP heads = 16 partials -> one full dot product per lane
+                float part[16];
+    #pragma unroll
+                for (int uu = 0; uu < UH; ++uu) {
+                    const uint4 kk = kb[half * UH + uu];
+    #pragma unroll
+                    for (int hh = 0; hh < GP; ++hh) {
+                        float s = dot2_bf16(kk.x, q[hh].x, 0.f);
+                        s = dot2_bf16(kk.y, q[hh].y, s);
+                        s = dot2_bf16(kk.z, q[hh].z, s);
+                        part[uu * GP + hh] = dot2_bf16(kk.w, q[hh].w, s);
+                    }
+                }
+                float s = row_transpose_reduce<16>(part, c);
+                // lane c owns (load uu = c / GP, head c % GP)
+                int cnt = 0;
+    #pragma unroll
+                for (int uu = 0; uu < UH; ++uu) cnt = (c / GP == uu) ? cb[half * UH + uu] : cnt;
+                s = (cnt > 0) ? fmaf(s, p.scale_log2, __log2f((float)cnt)) : -INFINITY;
+                const float m_new = orbit_max<GP>(fmaxf(s, m_run));
+                const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+                const float alpha = fast_exp2(m_run - m_safe);
+                const float pw = fast_exp2(s - m_safe);
+                l_run = fmaf(l_run, alpha, orbit_sum<GP>(pw));
+                m_run = m_new;
+                moved[half] = ballot64(alpha != 1.0f) != 0ull;
+                if (moved[half]) BcastAll<GP>::run(alpha, al[half]);
+                BcastAll<16>::run(pw, pb[half]);
+            }
+    #pragma unroll
+            for (int half = 0; half < NT; ++half) {
+                if (moved[half]) {
+    #pragma unroll
+                    for (int hh = 0; hh < GP; ++hh)
+    #pragma unroll
+                        for (int e = 0; e < 8; ++e) acc[hh][e] *= al[half][hh];
+                }
+    #pragma unroll
+                for (int uu = 0; uu < UH; ++uu) {
+                    const uint4 vv = vb[half * UH + uu];
+                    const float x[8] = {bf16_lo(vv.x), bf16_hi(vv.x), bf16_lo(vv.y), bf16_hi(vv.y),
+                                        bf16_lo(vv.z), bf16_hi(vv.z), bf16_lo(vv.w), bf16_hi(vv.w)};
+    #pragma unroll
+                    for (int hh = 0; hh < GP; ++hh)
+    #pragma unroll
+                        for (int e = 0; e < 8; ++e) acc[hh][e] = fmaf(pb[half][uu * GP + hh], x[e], acc[hh][e]);
+                }
+            }
+            // the other 15 waves of the workgroup keep the memory pipe busy while this one computes
+            base += kRowsPerBlockStep;
+            if (base < r1) issue(base);
+        }
+        // ---- fold the RPW lane groups of the wave (each saw different rows), then park in LDS
+        {
+            const float mw = rows_allreduce_max(m_run);
+            const float m_safe = (mw == -INFINITY) ? 0.f : mw;
+            const float f = fast_exp2(m_run - m_safe);    // this lane group's factor for head c % GP
+            const float lw = rows_allreduce_sum(l_run * f);
+            float fh[GP];
+            BcastAll<GP>::run(f, fh);
+    #pragma unroll
+            for (int hh = 0; hh < GP; ++hh) {
+    #pragma unroll
+                for (int e = 0; e < 8; ++e) acc[hh][e] = rows_allreduce_sum(acc[hh][e] * fh[hh]);
+                if (hh < G && g == 0) {
+    #pragma unroll
+                    for (int e = 0; e < 8; ++e) s_buf[(wave * G + hh) * D + 8 * c + e] = acc[hh][e];
+                }
+            }
+            if (g == 0 && c < G) { s_m[wave][c] = mw; s_l[wave][c] = lw; }
+        }
     }
     __syncthreads();
     // ---- fold the waves, write this split's partial

@@ -27,12 +27,13 @@ def _short(name):
     return name.replace("void ", "").split("(")[0]
 
 
-def _counters(dirname):
-    """{(kernel, counter): (dispatches, mean value)} from the .db of one counter pass."""
+def _counters(dirname, largest=False):
+    """{(kernel, counter): (dispatches, mean value)} from the .db of one counter pass; with `largest`, the
+    largest value of a dispatch instead of the mean (a kernel launched on buffers of several sizes)."""
     out = {}
     for db_path in glob.glob(os.path.join(dirname, "**", "*.db"), recursive=True):
         db = sqlite3.connect(db_path)
-        q = "select kernel_name, counter_name, count(*), avg(value) from counters_collection group by kernel_name, counter_name"
+        q = "select kernel_name, counter_name, count(*), %s(value) from counters_collection group by kernel_name, counter_name" % ("max" if largest else "avg")
         for k, c, n, v in db.execute(q):
             out[(_short(k), c)] = (n, v)
     return out
@@ -74,10 +75,15 @@ def main():
     # ------------------------------------------------------------------ HBM traffic
     F, W = _counters(os.path.join(out, "pmc1")), _counters(os.path.join(out, "pmc2"))
     j1 = _last_json(os.path.join(out, "bench_pmc1.json")) or pj
-    copy_f = [v for (k, c), (n, v) in F.items() if "copyBuffer" in k and c == "FETCH_SIZE"]
-    copy_w = [v for (k, c), (n, v) in W.items() if "copyBuffer" in k and c == "WRITE_SIZE"]
+    # the runtime's copy kernel also moves smaller buffers (uploads of the inputs): its largest dispatch is the 512 MiB copy
+    Fmax, Wmax = _counters(os.path.join(out, "pmc1"), True), _counters(os.path.join(out, "pmc2"), True)
+    copy_f = [v for (k, c), (n, v) in Fmax.items() if "copyBuffer" in k and c == "FETCH_SIZE"]
+    copy_w = [v for (k, c), (n, v) in Wmax.items() if "copyBuffer" in k and c == "WRITE_SIZE"]
+    read_f = [v for (k, c), (n, v) in F.items() if "stream_read_kernel" in k and c == "FETCH_SIZE"]
     COPY_KIB = 512.0 * 1024.0     # bench.py copies 512 MiB device to device
-    ff = COPY_KIB / max(copy_f) if copy_f else float("nan")
+    READ_KIB = 1024.0 * 1024.0    # and streams 1 GiB through sc_stream_read_probe
+    ff = READ_KIB / max(read_f) if read_f else float("nan")
+    ff_copy = COPY_KIB / max(copy_f) if copy_f else float("nan")
     wf = COPY_KIB / max(copy_w) if copy_w else float("nan")
     t = ["# HBM traffic per launch from rocprofv3 hardware counters: bench.py %s" % bench_args,
          "# workload: %s" % j1["config"]["workload"],
@@ -85,10 +91,12 @@ def main():
          "#   rocprofv3 --pmc FETCH_SIZE -d $R/gpurun_out/prof_%s/pmc1 -o run -- %s --eager --steps 2 --warmup 1 %s" % (tag, root_cmd, bench_args),
          "#   rocprofv3 --pmc WRITE_SIZE -d $R/gpurun_out/prof_%s/pmc2 -o run -- %s --eager --steps 2 --warmup 1 %s" % (tag, root_cmd, bench_args),
          "# Counter values are KiB per dispatch, averaged over the dispatches of the run.",
-         "# Calibration: the runtime's device-to-device copy kernel (__amd_rocclr_copyBuffer, 16 bytes per lane like the",
-         "# kernels here), which bench.py launches on 512 MiB: FETCH_SIZE reads %.1f KiB, WRITE_SIZE reads %.1f KiB;" % (max(copy_f) if copy_f else float("nan"), max(copy_w) if copy_w else float("nan")),
-         "# scale factors = 524288 KiB / reading (the FETCH_SIZE formula prices the wide read requests of 16-byte-per-lane",
-         "# kernels at half their size).",
+         "# Calibration with kernels of known size that bench.py launches in the same run.  Reads: sc::stream_read_kernel",
+         "# (16 bytes per lane like the kernels here) over 1 GiB reads FETCH_SIZE = %.1f KiB -> fetch_scale = 1048576 / reading" % (max(read_f) if read_f else float("nan")),
+         "# (the FETCH_SIZE formula prices the wide read requests of 16-byte-per-lane kernels at half their size).",
+         "# Writes: the runtime's device-to-device copy kernel (__amd_rocclr_copyBuffer) on 512 MiB, its largest dispatch:",
+         "# WRITE_SIZE = %.1f KiB -> write_scale = 524288 / reading.  (The same copy reads FETCH_SIZE = %.1f KiB, a factor %.3f.)"
+         % (max(copy_w) if copy_w else float("nan"), max(copy_f) if copy_f else float("nan"), ff_copy),
          "workload_tokens %d" % j1["config"]["tokens"], "tau %s" % bench_args_tau(sys.argv[3:], j1),
          "compressed_rows %d" % j1["config"]["compressed_rows"],
          "fetch_scale %.5f" % ff, "write_scale %.5f" % wf]
