@@ -36,10 +36,19 @@ constexpr int kDecUnroll = 4;   // loads per step of the generic kernel
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef short dec_short4 __attribute__((ext_vector_type(4)));
+typedef unsigned int dec_u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
+}
+
+// LDS traffic of one wavefront executes in order; this only keeps the compiler from moving accesses to
+// other lanes' data across the point where the lanes of a wave hand data to each other
+__device__ __forceinline__ void wave_lds_handover() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 }
 
 struct DecParams {
@@ -337,6 +346,10 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
     __shared__ float s_m[WAVES][G];
     __shared__ float s_l[WAVES][G];
     __shared__ int s_last;
+    // per wave: 16 rows of keys turned around for the matrix cores (groups of up to four heads only)
+    constexpr int kKtRowBytes = 2 * D + 16;
+    constexpr int kKtBytes = 16 * kKtRowBytes;
+    __shared__ __attribute__((aligned(16))) char s_kt[GP == 4 ? WAVES * kKtBytes : 16];
 
     // workgroup id = split * (B * Hkv) + (sequence, head): see publish_or_collect
     const int n_bh = p.B * p.Hkv;
@@ -363,98 +376,124 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
     per = (per + kRowsPerBlockStep - 1) / kRowsPerBlockStep * kRowsPerBlockStep;
     const int r0 = min(split * per, rows_total), r1 = min(r0 + per, rows_total);
 
-    const bf16_t *Kbh = reinterpret_cast<const bf16_t *>(p.Kc) + bh * (int64_t)p.cap * D + 8 * c;
-    const bf16_t *Vbh = reinterpret_cast<const bf16_t *>(p.Vc) + bh * (int64_t)p.cap * D + 8 * c;
-    const int32_t *cnt_bh = p.counts + bh * (int64_t)p.cap;
-    const bf16_t *Ktbh = TAIL ? reinterpret_cast<const bf16_t *>(p.Kt) + bh * (int64_t)p.tail_cap * D + 8 * c : nullptr;
-    const bf16_t *Vtbh = TAIL ? reinterpret_cast<const bf16_t *>(p.Vt) + bh * (int64_t)p.tail_cap * D + 8 * c : nullptr;
+    // Rows come through buffer descriptors that end at this split's last row: the hardware returns zeros for
+    // anything beyond, so no load needs a predicate, a branch or a 64-bit address (the launcher checks that
+    // the byte offsets of a (sequence, head) fit in 31 bits).  A row of zeros with size 0 is "no row".
+    const int end_c = min(r1, rows_c);                       // merged rows of this split end here
+    const int end_t = TAIL ? max(r1 - rows_c, 0) : 0;        // tail rows of this split end here
+    const auto k_src = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(reinterpret_cast<const bf16_t *>(p.Kc) + bh * (int64_t)p.cap * D),
+                                                         (short)0, end_c * D * 2, 0x00020000);
+    const auto v_src = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(reinterpret_cast<const bf16_t *>(p.Vc) + bh * (int64_t)p.cap * D),
+                                                         (short)0, end_c * D * 2, 0x00020000);
+    const auto n_src = __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t *>(p.counts + bh * (int64_t)p.cap), (short)0, end_c * 4, 0x00020000);
+    const auto kt_src = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(reinterpret_cast<const bf16_t *>(TAIL ? p.Kt : p.Kc) + (TAIL ? bh * (int64_t)p.tail_cap * D : 0)),
+                                                          (short)0, end_t * D * 2, 0x00020000);
+    const auto vt_src = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(reinterpret_cast<const bf16_t *>(TAIL ? p.Vt : p.Vc) + (TAIL ? bh * (int64_t)p.tail_cap * D : 0)),
+                                                          (short)0, end_t * D * 2, 0x00020000);
 
     uint4 kb[U], vb[U];
     int cb[U];
+    // keys first, then sizes, then values: the scores are formed while the values are still on their way
     auto issue = [&](int base) {
+        const int row0 = base + g;
+        const int off0 = row0 * (D * 2) + 16 * c;
+        int toff[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int row = base + u * RPW + g;
-            if (TAIL && row >= rows_c && row < r1) {
-                kb[u] = *reinterpret_cast<const uint4 *>(Ktbh + (int64_t)(row - rows_c) * D);
-                vb[u] = *reinterpret_cast<const uint4 *>(Vtbh + (int64_t)(row - rows_c) * D);
-                cb[u] = 1;
-            } else if (row < r1) {
-                kb[u] = *reinterpret_cast<const uint4 *>(Kbh + (int64_t)row * D);
-                vb[u] = *reinterpret_cast<const uint4 *>(Vbh + (int64_t)row * D);
-                cb[u] = cnt_bh[row];
-            } else {
-                kb[u] = make_uint4(0, 0, 0, 0);
-                vb[u] = make_uint4(0, 0, 0, 0);
-                cb[u] = 0;      // "no row": its score becomes -inf
-            }
+            // a row before the tail must not turn into a small offset by wrapping around
+            const int rel = row0 + u * RPW - rows_c;
+            toff[u] = (rel >= 0) ? rel * (D * 2) + 16 * c : (int)0x80000000;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            dec_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(k_src, off0 + u * RPW * D * 2, 0, 0);
+            if (TAIL) v |= __builtin_amdgcn_raw_buffer_load_b128(kt_src, toff[u], 0, 0);
+            kb[u] = make_uint4(v.x, v.y, v.z, v.w);
+        }
+        __builtin_amdgcn_sched_barrier(0);     // keep the order of the requests: the scheduler has no reason to
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            cb[u] = (int)__builtin_amdgcn_raw_buffer_load_b32(n_src, (row0 + u * RPW) * 4, 0, 0);
+            if (TAIL) cb[u] = (toff[u] >= 0 && row0 + u * RPW < r1) ? 1 : cb[u];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            dec_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(v_src, off0 + u * RPW * D * 2, 0, 0);
+            if (TAIL) v |= __builtin_amdgcn_raw_buffer_load_b128(vt_src, toff[u], 0, 0);
+            vb[u] = make_uint4(v.x, v.y, v.z, v.w);
         }
     };
     int base = r0 + wave * kRowsPerWaveStep;
     issue(base);
 
-    uint4 q[GP];
-#pragma unroll
-    for (int hh = 0; hh < GP; ++hh) {
-        const int64_t qoff = ((int64_t)b * p.Hq + (int64_t)h * G + (hh < G ? hh : 0)) * D + 8 * c;
-        q[hh] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const bf16_t *>(p.Q) + qoff);
-    }
-
-    // owner-lane state: lane c of a row owns head (c % GP); replicated over the 16/GP lanes of its orbit
     float m_run = -INFINITY, l_run = 0.f;
     if constexpr (GP == 4) {
-        // Scores on the vector unit, O += P V on the matrix cores (v_mfma_f32_16x16x16_bf16): the 16 rows of
-        // a step are the contraction index, A[m][k] = probability of head m for row k (rows 4..15 of A are
-        // zero), B[k][n] = element 8c + j of row k for the lane's column n = c, one product per j.  The k
-        // index (lane / 16, i) of both operands stands for row 4i + lane / 16, which is register i of the
-        // lane's own group, so B is built from the loaded registers with two byte permutes per product.
-        // The result adds up the rows of all four lane groups: the lane groups share one running maximum
-        // per head, and lanes 0..15 end up with the whole wave's sums: accm[j][i] = head i, element 8c + j.
+        // Both products on the matrix cores (v_mfma_f32_16x16x16_bf16), 16 rows per step.
+        //   S = K_c q^T: the rows are spread over the lanes by column (16-byte pieces), the A operand wants
+        //   one row per lane position, so the wave turns its 16 rows around through a 4 KB tile in LDS
+        //   (row stride 272 B: the operand reads are free of bank conflicts).  Register u of lane group g
+        //   is row 4u + g and goes to tile row 4g + u; B holds the query heads (lane position c = head c,
+        //   zero beyond the group).  The result leaves lane (g, c) with the scores of head c for tile
+        //   rows 4g + i = rows 4i + g, i = 0..3: the rows whose sizes the lane group loaded itself.
+        //   O += P V: the 16 rows are the contraction index, A[m][k] = probability of head m for row k, and
+        //   the k index (lane / 16, i) of both operands stands for row 4i + lane / 16: the probabilities
+        //   are used where the first product left them, and B[k][n] = element 8c + j of row k is built
+        //   from the loaded registers with two byte permutes per product, one product per j.
+        // The second product adds up the rows of all four lane groups: they share one running maximum per
+        // head, and lanes 0..15 end up with the whole wave's sums: accm[j][i] = head i, element 8c + j.
         // P enters as two bf16 parts (leading part and remainder), so its rounding error is 2^-18.
+        char *kt = s_kt + wave * kKtBytes;
+        // B operand of the first product: lane (g, c) holds elements 16ks + 4g .. + 3 of head c (zeros for c >= G:
+        // the descriptor ends after the G heads of the group)
+        uint2 qb[8];
+        {
+            const auto q_src = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(reinterpret_cast<const bf16_t *>(p.Q) + ((int64_t)b * p.Hq + (int64_t)h * G) * D),
+                                                                 (short)0, G * D * 2, 0x00020000);
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const u32x2_dec_t v = __builtin_amdgcn_raw_buffer_load_b64(q_src, c * (D * 2) + (16 * ks + 4 * g) * 2, 0, 0);
+                qb[ks] = make_uint2(v.x, v.y);
+            }
+        }
         f32x4_t accm[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) accm[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         while (base < r1) {
-            float part[16];
 #pragma unroll
-            for (int uu = 0; uu < U; ++uu) {
-                const uint4 kk = kb[uu];
+            for (int u = 0; u < U; ++u) *reinterpret_cast<uint4 *>(kt + (4 * g + u) * kKtRowBytes + 16 * c) = kb[u];
+            wave_lds_handover();
+            f32x4_t sc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int hh = 0; hh < GP; ++hh) {
-                    float s = dot2_bf16(kk.x, q[hh].x, 0.f);
-                    s = dot2_bf16(kk.y, q[hh].y, s);
-                    s = dot2_bf16(kk.z, q[hh].z, s);
-                    part[uu * GP + hh] = dot2_bf16(kk.w, q[hh].w, s);
-                }
+            for (int ks = 0; ks < 8; ++ks) {
+                const uint2 a = *reinterpret_cast<const uint2 *>(kt + c * kKtRowBytes + (16 * ks + 4 * g) * 2);
+                sc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(dec_short4, a),
+                                                               __builtin_bit_cast(dec_short4, qb[ks]), sc, 0, 0, 0);
             }
-            float s = row_transpose_reduce<16>(part, c);
-            // lane c owns (load uu = c / GP, head c % GP)
-            int cnt = 0;
+            wave_lds_handover();     // the tile is rewritten in the next step
+            float sv[4];
+            float m_loc = m_run;
 #pragma unroll
-            for (int uu = 0; uu < U; ++uu) cnt = (c / GP == uu) ? cb[uu] : cnt;
-            s = (cnt > 0) ? fmaf(s, p.scale_log2, __log2f((float)cnt)) : -INFINITY;
-            const float m_new = rows_allreduce_max(orbit_max<GP>(fmaxf(s, m_run)));
+            for (int i = 0; i < 4; ++i) {
+                sv[i] = (cb[i] > 0) ? fmaf(sc[i], p.scale_log2, __log2f((float)cb[i])) : -INFINITY;
+                m_loc = fmaxf(m_loc, sv[i]);
+            }
+            const float m_new = rows_allreduce_max(m_loc);
             const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
             const float alpha = fast_exp2(m_run - m_safe);
-            const float pw = fast_exp2(s - m_safe);
-            l_run = fmaf(l_run, alpha, orbit_sum<GP>(pw));    // per lane group; the groups are added up after the loop
+            float pi[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) pi[i] = fast_exp2(sv[i] - m_safe);
+            l_run = fmaf(l_run, alpha, (pi[0] + pi[1]) + (pi[2] + pi[3]));   // per lane group; added up after the loop
             m_run = m_new;
             if (ballot64(alpha != 1.0f) != 0ull) {
                 float al[GP];
-                BcastAll<GP>::run(alpha, al);
+                BcastAll<GP>::run(alpha, al);     // head i sits at lane position i
 #pragma unroll
                 for (int j = 0; j < 8; ++j)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) accm[j][i] *= al[i];
             }
-            // A operand of lane (g, c < 4): head c, rows 4i + g (i = 0..3), which lanes (g, 4i + c) own
-            float pi[4];
-            pi[0] = pw;
-            pi[1] = dpp<0x104>(pw);      // row_shl:4  -- lane c reads lane c + 4 of its 16-lane row
-            pi[2] = dpp<0x108>(pw);
-            pi[3] = dpp<0x10C>(pw);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) pi[i] = (c < GP) ? pi[i] : 0.f;
             const uint32_t h01 = pack_bf16x2(pi[0], pi[1]), h23 = pack_bf16x2(pi[2], pi[3]);
             const uint32_t r01 = pack_bf16x2(pi[0] - bf16_lo(h01), pi[1] - bf16_hi(h01));
             const uint32_t r23 = pack_bf16x2(pi[2] - bf16_lo(h23), pi[3] - bf16_hi(h23));
@@ -485,24 +524,31 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
             if (c < G) { s_m[wave][c] = m_run; s_l[wave][c] = lw; }
         }
     } else {
+        uint4 q[GP];
+#pragma unroll
+        for (int hh = 0; hh < GP; ++hh) {
+            const int64_t qoff = ((int64_t)b * p.Hq + (int64_t)h * G + (hh < G ? hh : 0)) * D + 8 * c;
+            q[hh] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const bf16_t *>(p.Q) + qoff);
+        }
+        // owner-lane state: lane c of a row owns head (c % GP); replicated over the 16/GP lanes of its orbit
         float acc[GP][8];
-    #pragma unroll
+#pragma unroll
         for (int hh = 0; hh < GP; ++hh)
-    #pragma unroll
+#pragma unroll
             for (int e = 0; e < 8; ++e) acc[hh][e] = 0.f;
 
         while (base < r1) {
             float pb[NT][16];
             float al[NT][GP];
             bool moved[NT];
-    #pragma unroll
+#pragma unroll
             for (int half = 0; half < NT; ++half) {
                 // ---- scores: UH loads x GP heads = 16 partials -> one full dot product per lane
                 float part[16];
-    #pragma unroll
+#pragma unroll
                 for (int uu = 0; uu < UH; ++uu) {
                     const uint4 kk = kb[half * UH + uu];
-    #pragma unroll
+#pragma unroll
                     for (int hh = 0; hh < GP; ++hh) {
                         float s = dot2_bf16(kk.x, q[hh].x, 0.f);
                         s = dot2_bf16(kk.y, q[hh].y, s);
@@ -513,7 +559,7 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
                 float s = row_transpose_reduce<16>(part, c);
                 // lane c owns (load uu = c / GP, head c % GP)
                 int cnt = 0;
-    #pragma unroll
+#pragma unroll
                 for (int uu = 0; uu < UH; ++uu) cnt = (c / GP == uu) ? cb[half * UH + uu] : cnt;
                 s = (cnt > 0) ? fmaf(s, p.scale_log2, __log2f((float)cnt)) : -INFINITY;
                 const float m_new = orbit_max<GP>(fmaxf(s, m_run));
@@ -526,22 +572,22 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
                 if (moved[half]) BcastAll<GP>::run(alpha, al[half]);
                 BcastAll<16>::run(pw, pb[half]);
             }
-    #pragma unroll
+#pragma unroll
             for (int half = 0; half < NT; ++half) {
                 if (moved[half]) {
-    #pragma unroll
+#pragma unroll
                     for (int hh = 0; hh < GP; ++hh)
-    #pragma unroll
+#pragma unroll
                         for (int e = 0; e < 8; ++e) acc[hh][e] *= al[half][hh];
                 }
-    #pragma unroll
+#pragma unroll
                 for (int uu = 0; uu < UH; ++uu) {
                     const uint4 vv = vb[half * UH + uu];
                     const float x[8] = {bf16_lo(vv.x), bf16_hi(vv.x), bf16_lo(vv.y), bf16_hi(vv.y),
                                         bf16_lo(vv.z), bf16_hi(vv.z), bf16_lo(vv.w), bf16_hi(vv.w)};
-    #pragma unroll
+#pragma unroll
                     for (int hh = 0; hh < GP; ++hh)
-    #pragma unroll
+#pragma unroll
                         for (int e = 0; e < 8; ++e) acc[hh][e] = fmaf(pb[half][uu * GP + hh], x[e], acc[hh][e]);
                 }
             }
@@ -557,12 +603,12 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
             const float lw = rows_allreduce_sum(l_run * f);
             float fh[GP];
             BcastAll<GP>::run(f, fh);
-    #pragma unroll
+#pragma unroll
             for (int hh = 0; hh < GP; ++hh) {
-    #pragma unroll
+#pragma unroll
                 for (int e = 0; e < 8; ++e) acc[hh][e] = rows_allreduce_sum(acc[hh][e] * fh[hh]);
                 if (hh < G && g == 0) {
-    #pragma unroll
+#pragma unroll
                     for (int e = 0; e < 8; ++e) s_buf[(wave * G + hh) * D + 8 * c + e] = acc[hh][e];
                 }
             }
@@ -842,7 +888,9 @@ template <typename T, int D, int G>
 static hipError_t launch_g(const DecParams &p, hipStream_t stream) {
     const dim3 grid((unsigned)p.max_splits * (unsigned)(p.Hkv * p.B));
     if constexpr (D == 128 && sizeof(T) == 2) {
-        if (p.q_is_bf16) {
+        // the fast kernel addresses the rows of a (sequence, head) with 32-bit byte offsets
+        const int64_t reach = ((int64_t)(p.cap > p.tail_cap ? p.cap : p.tail_cap) + 2 * FastShape<G>::THREADS) * D * 2;
+        if (p.q_is_bf16 && reach < (1ll << 31)) {
             if (p.Kt) hipLaunchKernelGGL((decode_bf16_kernel<D, G, true>), grid, dim3(FastShape<G>::THREADS), 0, stream, p);
             else hipLaunchKernelGGL((decode_bf16_kernel<D, G, false>), grid, dim3(FastShape<G>::THREADS), 0, stream, p);
             return hipGetLastError();
