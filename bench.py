@@ -146,6 +146,8 @@ def _measured_traffic(workload, tau, rows):
     """HBM bytes per launch from the committed rocprofv3 counter summary, if it covers this workload
     (same compressed row count), else None.  Lines of the file: `<key> <value>`; '#' starts a comment."""
     rel = os.path.join("profiles", "hbm_traffic_%s.txt" % workload)
+    if not os.path.exists(os.path.join(ROOT, rel)):
+        rel = os.path.join("profiles", "hbm_traffic_%s_tau%g.txt" % (workload, tau))
     path = os.path.join(ROOT, rel)
     if not os.path.exists(path):
         return None, None

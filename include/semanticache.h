@@ -255,10 +255,12 @@ sc_status sc_gsc_merge_append(const void *K, const void *V, sc_dtype in_dtype,
  *     lo = tau_lo, hi = tau_hi;  `iterations` times:  mid = 0.5f * (lo + hi) in fp32;
  *     rows(mid) <= budget_rows ? lo = mid : hi = mid;   result = lo.
  * tau_lo is assumed to meet the budget (-1.01 merges every chunk into one row and always does if
- * anything can); it is not probed unless iterations is 0.  Every probe is a complete sc_gsc_merge on
- * the caller's stream, the bracket lives in device memory and is moved by a small kernel between the
- * probes: iterations + 1 merges, no host synchronisation.  The last merge runs at the result, so on
- * completion Kc, Vc, counts, comp_lens, cluster_id hold exactly what sc_gsc_merge(tau = result) gives.
+ * anything can); it is not probed unless iterations is 0.  Every probe clusters all chunks on the
+ * caller's stream and only counts the rows (bf16 / d = 128: no values read, nothing merged; other
+ * shapes run complete merges as probes); the bracket lives in device memory and is moved by a small
+ * kernel between the probes: iterations + 1 launches of the clustering, no host synchronisation.  The
+ * last one, at the result, is a complete sc_gsc_merge, so on completion Kc, Vc, counts, comp_lens,
+ * cluster_id hold exactly what sc_gsc_merge(tau = result) gives.
  *
  *   budget_rows     target total of merged rows, e.g. round(0.35 * Hkv * sum of seq_lens)
  *   iterations      0..32 bisection steps (12 narrow [-1, 1] to 5e-4)
@@ -343,8 +345,8 @@ sc_status sc_stream_read_probe(const void *src, size_t bytes, void *sink, void *
  *                          head share one XCC and could use its L2 (the default, 1)
  *   "decode_poll_budget"   polls of the folding workgroup before it gives up (default 2^20); negative:
  *                          give up at once — a host-driven way to exercise the failure path in tests
- *   "decode_mfma_min_group" sc_decode_attn (bf16, d = 128, no tail): query heads per KV head from which the
- *                          matrix-core kernel of sc_multi_attn is used for the single row; 9 = never
+ *   "decode_mfma_min_group" sc_decode_attn (bf16, d = 128): query heads per KV head from which the
+ *                          kernel of sc_multi_attn is used for the single row; 9 = never (the default)
  *   "gsc_fast_path"        0 forces the generic kernels even for bf16 / d = 128
  *   "gsc_chunks_per_task"  fast path: chunks handled by one single-wave workgroup task (1..32)
  *   "gsc_chunks_per_item"  generic path: chunks per work item

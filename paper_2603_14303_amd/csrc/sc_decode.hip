@@ -9,14 +9,14 @@
 // 64/(d/8) rows, and one "step" of a wave is U such loads of K_c and of V_c; the next step's loads
 // are requested as soon as the current step's registers are free.
 //
-// Fast kernel (bf16 cache and query, d = 128; 12 wavefronts per workgroup, 8 for G > 4).  Per step and
-// lane: U*GP partial dot products (GP = G padded to 4 or 8; bf16 pairs go through v_dot2_f32_bf16), a
-// transposed DPP reduction that leaves ONE (row, head) score per lane, the online-softmax update done
-// once per score by its owner lane (exp2 domain, log2(size) bias), and a ds_swizzle broadcast of the 16
-// probabilities back to the lanes that hold the value pieces.  Partials (running max, sum, fp32
-// accumulator) are folded across lane groups and wavefronts and written to the workspace; every split
-// but the last then publishes a flag, the workgroup of the last split waits for the flags (bounded)
-// and folds the S partials into O.  The hand-over is described above publish_or_collect below.
+// Fast kernel (bf16 cache and query, d = 128, up to 8 query heads per KV head; 12 wavefronts per
+// workgroup).  Per step a wave takes 16 rows; both products run on the matrix cores, the scores after
+// the wave has turned its key rows around through a small LDS tile, the output sums straight from the
+// loaded value registers (see the comment inside the kernel).  Softmax is online, per head, in the exp2
+// domain with a log2(size) bias.  Partials (running max, sum, fp32 sums) are folded across the
+// wavefronts and written to the workspace; every split but the last then publishes a flag, the
+// workgroup of the last split waits for the flags (bounded) and folds the S partials into O.  The
+// hand-over is described above publish_or_collect below.
 //
 // Generic kernel (d = 64, fp32 caches or queries): same split-K scheme, plain DPP all-reduce.
 #include "sc_device.h"
@@ -78,23 +78,6 @@ __device__ __forceinline__ int splits_for(int rows, int max_splits, int min_rows
     return s < 1 ? 1 : (s > max_splits ? max_splits : s);
 }
 
-template <int SH> __device__ __forceinline__ float ror_max(float x) { return fmaxf(x, dpp<0x120 + SH>(x)); }
-template <int SH> __device__ __forceinline__ float ror_add(float x) { return x + dpp<0x120 + SH>(x); }
-// reduce over the lanes of a 16-lane row that share (lane % GP): rotations by GP, 2GP, ... < 16
-template <int GP> __device__ __forceinline__ float orbit_max(float x) {
-    if constexpr (GP <= 1) x = ror_max<1>(x);
-    if constexpr (GP <= 2) x = ror_max<2>(x);
-    if constexpr (GP <= 4) x = ror_max<4>(x);
-    if constexpr (GP <= 8) x = ror_max<8>(x);
-    return x;
-}
-template <int GP> __device__ __forceinline__ float orbit_sum(float x) {
-    if constexpr (GP <= 1) x = ror_add<1>(x);
-    if constexpr (GP <= 2) x = ror_add<2>(x);
-    if constexpr (GP <= 4) x = ror_add<4>(x);
-    if constexpr (GP <= 8) x = ror_add<8>(x);
-    return x;
-}
 // value of lane SRC of the own 16-lane row (ds_swizzle bit-mask mode: keep lane bit 4, force the low bits)
 template <int SRC> __device__ __forceinline__ float row_bcast(float x) {
     return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(x), 0x10 | (SRC << 5)));
@@ -317,10 +300,9 @@ __device__ __forceinline__ void combine_splits(const DecParams &p, const float *
 }
 
 template <int G> struct FastShape {
-    static constexpr int GP = G <= 4 ? 4 : 8;         // heads padded to 4 or 8 (padding heads are computed and dropped)
-    static constexpr int WAVES = GP == 8 ? 8 : 12;    // 12 waves x 8 KB of loads in flight per CU, <= 170 VGPRs each
+    static constexpr int WAVES = 12;                  // 12 waves x 8 KB of loads in flight per CU, <= 170 VGPRs each
     static constexpr int THREADS = WAVES * kWave;
-    static constexpr int U = 4;                       // wave-wide loads of K (and of V) per step
+    static constexpr int U = 4;                       // wave-wide loads of K (and of V) per step: 16 rows, one MFMA tile
 };
 
 // TAIL: the rows of a (sequence, KV head) are its merged rows followed by the first tail_lens[b] rows of
@@ -330,12 +312,11 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
     static_assert(D == 128, "16 lanes per row");
     constexpr int LPR = 16;
     constexpr int RPW = kWave / LPR;                       // 4 rows per wave-wide load
-    constexpr int GP = FastShape<G>::GP;
+    static_assert(G >= 1 && G <= 16, "the query heads of a group are the 16 columns of one matrix tile");
     constexpr int WAVES = FastShape<G>::WAVES;
     constexpr int THREADS = FastShape<G>::THREADS;
     constexpr int U = FastShape<G>::U;
-    constexpr int NT = U * GP / 16;                        // transposed reductions per step (2 for GP = 8)
-    constexpr int UH = U / NT;                             // loads covered by one reduction
+    static_assert(U == 4, "one step is one 16-row tile");
     constexpr int kRowsPerWaveStep = RPW * U;
     constexpr int kRowsPerBlockStep = kRowsPerWaveStep * WAVES;
     constexpr int kStride = D + kPartPad;   // floats per (split, head) partial: acc[D], m, l, pad
@@ -346,10 +327,10 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
     __shared__ float s_m[WAVES][G];
     __shared__ float s_l[WAVES][G];
     __shared__ int s_last;
-    // per wave: 16 rows of keys turned around for the matrix cores (groups of up to four heads only)
+    // per wave: 16 rows of keys turned around for the matrix cores
     constexpr int kKtRowBytes = 2 * D + 16;
     constexpr int kKtBytes = 16 * kKtRowBytes;
-    __shared__ __attribute__((aligned(16))) char s_kt[GP == 4 ? WAVES * kKtBytes : 16];
+    __shared__ __attribute__((aligned(16))) char s_kt[WAVES * kKtBytes];
 
     // workgroup id = split * (B * Hkv) + (sequence, head): see publish_or_collect
     const int n_bh = p.B * p.Hkv;
@@ -428,7 +409,7 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
     issue(base);
 
     float m_run = -INFINITY, l_run = 0.f;
-    if constexpr (GP == 4) {
+    {
         // Both products on the matrix cores (v_mfma_f32_16x16x16_bf16), 16 rows per step.
         //   S = K_c q^T: the rows are spread over the lanes by column (16-byte pieces), the A operand wants
         //   one row per lane position, so the wave turns its 16 rows around through a 4 KB tile in LDS
@@ -441,7 +422,8 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
         //   are used where the first product left them, and B[k][n] = element 8c + j of row k is built
         //   from the loaded registers with two byte permutes per product, one product per j.
         // The second product adds up the rows of all four lane groups: they share one running maximum per
-        // head, and lanes 0..15 end up with the whole wave's sums: accm[j][i] = head i, element 8c + j.
+        // head, and the result holds the whole wave's sums: accm[j][i] of lane (g, c) = head 4g + i, element
+        // 8c + j (for groups of up to four heads only lanes 0..15 hold anything).
         // P enters as two bf16 parts (leading part and remainder), so its rounding error is 2^-18.
         char *kt = s_kt + wave * kKtBytes;
         // B operand of the first product: lane (g, c) holds elements 16ks + 4g .. + 3 of head c (zeros for c >= G:
@@ -487,8 +469,14 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
             l_run = fmaf(l_run, alpha, (pi[0] + pi[1]) + (pi[2] + pi[3]));   // per lane group; added up after the loop
             m_run = m_new;
             if (ballot64(alpha != 1.0f) != 0ull) {
-                float al[GP];
-                BcastAll<GP>::run(alpha, al);     // head i sits at lane position i
+                // the factor of head 4g + i sits at lane position 4g + i of every 16-lane row
+                float al[4];
+                if constexpr (G <= 4) {
+                    BcastAll<4>::run(alpha, al);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) al[i] = lane_gather(alpha, 20 * g + i);
+                }
 #pragma unroll
                 for (int j = 0; j < 8; ++j)
 #pragma unroll
@@ -514,106 +502,16 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
         }
         // ---- park the wave's sums in LDS (m_run is already the same in all lane groups)
         const float lw = rows_allreduce_sum(l_run);
-        if (g == 0) {
 #pragma unroll
-            for (int i = 0; i < G; ++i) {
-                float *dst = s_buf + (wave * G + i) * D + 8 * c;
+        for (int i = 0; i < 4; ++i) {
+            const int hh = 4 * g + i;
+            if (hh < G) {
+                float *dst = s_buf + (wave * G + hh) * D + 8 * c;
                 *reinterpret_cast<float4 *>(dst) = make_float4(accm[0][i], accm[1][i], accm[2][i], accm[3][i]);
                 *reinterpret_cast<float4 *>(dst + 4) = make_float4(accm[4][i], accm[5][i], accm[6][i], accm[7][i]);
             }
-            if (c < G) { s_m[wave][c] = m_run; s_l[wave][c] = lw; }
         }
-    } else {
-        uint4 q[GP];
-#pragma unroll
-        for (int hh = 0; hh < GP; ++hh) {
-            const int64_t qoff = ((int64_t)b * p.Hq + (int64_t)h * G + (hh < G ? hh : 0)) * D + 8 * c;
-            q[hh] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const bf16_t *>(p.Q) + qoff);
-        }
-        // owner-lane state: lane c of a row owns head (c % GP); replicated over the 16/GP lanes of its orbit
-        float acc[GP][8];
-#pragma unroll
-        for (int hh = 0; hh < GP; ++hh)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[hh][e] = 0.f;
-
-        while (base < r1) {
-            float pb[NT][16];
-            float al[NT][GP];
-            bool moved[NT];
-#pragma unroll
-            for (int half = 0; half < NT; ++half) {
-                // ---- scores: UH loads x GP heads = 16 partials -> one full dot product per lane
-                float part[16];
-#pragma unroll
-                for (int uu = 0; uu < UH; ++uu) {
-                    const uint4 kk = kb[half * UH + uu];
-#pragma unroll
-                    for (int hh = 0; hh < GP; ++hh) {
-                        float s = dot2_bf16(kk.x, q[hh].x, 0.f);
-                        s = dot2_bf16(kk.y, q[hh].y, s);
-                        s = dot2_bf16(kk.z, q[hh].z, s);
-                        part[uu * GP + hh] = dot2_bf16(kk.w, q[hh].w, s);
-                    }
-                }
-                float s = row_transpose_reduce<16>(part, c);
-                // lane c owns (load uu = c / GP, head c % GP)
-                int cnt = 0;
-#pragma unroll
-                for (int uu = 0; uu < UH; ++uu) cnt = (c / GP == uu) ? cb[half * UH + uu] : cnt;
-                s = (cnt > 0) ? fmaf(s, p.scale_log2, __log2f((float)cnt)) : -INFINITY;
-                const float m_new = orbit_max<GP>(fmaxf(s, m_run));
-                const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-                const float alpha = fast_exp2(m_run - m_safe);
-                const float pw = fast_exp2(s - m_safe);
-                l_run = fmaf(l_run, alpha, orbit_sum<GP>(pw));
-                m_run = m_new;
-                moved[half] = ballot64(alpha != 1.0f) != 0ull;
-                if (moved[half]) BcastAll<GP>::run(alpha, al[half]);
-                BcastAll<16>::run(pw, pb[half]);
-            }
-#pragma unroll
-            for (int half = 0; half < NT; ++half) {
-                if (moved[half]) {
-#pragma unroll
-                    for (int hh = 0; hh < GP; ++hh)
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) acc[hh][e] *= al[half][hh];
-                }
-#pragma unroll
-                for (int uu = 0; uu < UH; ++uu) {
-                    const uint4 vv = vb[half * UH + uu];
-                    const float x[8] = {bf16_lo(vv.x), bf16_hi(vv.x), bf16_lo(vv.y), bf16_hi(vv.y),
-                                        bf16_lo(vv.z), bf16_hi(vv.z), bf16_lo(vv.w), bf16_hi(vv.w)};
-#pragma unroll
-                    for (int hh = 0; hh < GP; ++hh)
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) acc[hh][e] = fmaf(pb[half][uu * GP + hh], x[e], acc[hh][e]);
-                }
-            }
-            // the other 15 waves of the workgroup keep the memory pipe busy while this one computes
-            base += kRowsPerBlockStep;
-            if (base < r1) issue(base);
-        }
-        // ---- fold the RPW lane groups of the wave (each saw different rows), then park in LDS
-        {
-            const float mw = rows_allreduce_max(m_run);
-            const float m_safe = (mw == -INFINITY) ? 0.f : mw;
-            const float f = fast_exp2(m_run - m_safe);    // this lane group's factor for head c % GP
-            const float lw = rows_allreduce_sum(l_run * f);
-            float fh[GP];
-            BcastAll<GP>::run(f, fh);
-#pragma unroll
-            for (int hh = 0; hh < GP; ++hh) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[hh][e] = rows_allreduce_sum(acc[hh][e] * fh[hh]);
-                if (hh < G && g == 0) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) s_buf[(wave * G + hh) * D + 8 * c + e] = acc[hh][e];
-                }
-            }
-            if (g == 0 && c < G) { s_m[wave][c] = mw; s_l[wave][c] = lw; }
-        }
+        if (g == 0 && c < G) { s_m[wave][c] = m_run; s_l[wave][c] = lw; }
     }
     __syncthreads();
     // ---- fold the waves, write this split's partial
@@ -916,10 +814,10 @@ static hipError_t launch_td(const DecParams &p, int G, hipStream_t stream) {
 }
 
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream) {
-    // Wide head groups: the VALU kernel spends 4*d flops per head and row on the vector units and becomes
-    // issue-bound (0.36-0.46 of peak bandwidth at G = 7); the matrix-core kernel for blocks of query
-    // rows treats the G heads as one 16-row tile and streams faster there.  Its partials go behind the
-    // flags, which it neither needs nor touches.
+    // Optional route (knob, off by default): a single query row through the kernel for blocks of query rows,
+    // which treats the G heads as one 16-row tile, writes partials and folds them in a second launch.  The
+    // decode kernel above measured level or slightly ahead of it for every group size (35.3 against 36.1 us
+    // at G = 7 on a ragged batch of 32).  Its partials go behind the flags, which it neither needs nor touches.
     if (a.kv_dtype == DType::BF16 && a.q_dtype == DType::BF16 && a.d == 128 &&
         a.Hq / a.Hkv >= tuning().decode_mfma_min_group) {
         MultiArgs m;

@@ -107,7 +107,7 @@ struct Tuning {
     int decode_min_rows = 192;      // rows of the merged cache a split should at least get
     int decode_local_handover = 1;  // 0: split partials always go through memory, also when a head's splits share an XCC
     int decode_poll_budget = 1 << 20;   // polls (about 0.3 us each) of the folding workgroup before it gives up; negative: give up at once (host-driven test of the failure path)
-    int decode_mfma_min_group = 5;  // query heads per KV head from which single-row decode runs on the matrix-core kernel (9 = never)
+    int decode_mfma_min_group = 9;  // query heads per KV head from which single-row decode runs on the multi-row kernel (9 = never)
     int gsc_chunks_per_item = 16;   // chunks handled by one workgroup work item
     int gsc_grid_x = 0;             // workgroups per (sequence, KV head); <= 0 picks it from B*Hkv
     int gsc_chunks_per_task = 2;    // fast path: chunks handled by one single-wave workgroup

@@ -214,3 +214,28 @@ def test_launch_shape_knobs_do_not_change_results(knobs):
         for k, v in old.items():
             sc.tune_set(k, v)
     print(knobs, "merge_err %.2e" % out["worst_merge_err"], "decode", errs)
+
+
+def test_decode_capacity_beyond_32bit_row_offsets():
+    # the fast decode kernel addresses the rows of a (sequence, head) with 32-bit byte offsets; a cache
+    # whose capacity does not fit is served by the generic kernel: same result within the decode tolerance
+    rows, d, G = 3000 + 7, 128, 4
+    rng = np.random.default_rng(11)
+    Ks = torch.from_numpy(rng.standard_normal((1, 1, rows, d)).astype(np.float32)).to(g.DEV).to(torch.bfloat16)
+    Vs = torch.from_numpy(rng.standard_normal((1, 1, rows, d)).astype(np.float32)).to(g.DEV).to(torch.bfloat16)
+    cs = torch.from_numpy(rng.integers(1, 9, (1, 1, rows)).astype(np.int32)).to(g.DEV)
+    lens = torch.tensor([[rows]], dtype=torch.int32, device=g.DEV)
+    Q = torch.from_numpy(rng.standard_normal((1, G, d)).astype(np.float32)).to(g.DEV).to(torch.bfloat16)
+    O_small, lse_small = sc.sc_decode_attn(Q, Ks, Vs, cs, lens, want_lse=True)
+    cap = (1 << 31) // (d * 2) + 5
+    Kb = torch.empty((1, 1, cap, d), dtype=torch.bfloat16, device=g.DEV)
+    Vb = torch.empty_like(Kb)
+    cb = torch.empty((1, 1, cap), dtype=torch.int32, device=g.DEV)
+    Kb[:, :, :rows], Vb[:, :, :rows], cb[:, :, :rows] = Ks, Vs, cs
+    O_big, lse_big = sc.sc_decode_attn(Q, Kb, Vb, cb, lens, want_lse=True)
+    torch.cuda.synchronize()
+    want_O, want_l = oracle.decode_attn(Q.float().cpu().numpy().astype(np.float64), Ks.float().cpu().numpy().astype(np.float64),
+                                        Vs.float().cpu().numpy().astype(np.float64), cs.cpu().numpy(), lens.cpu().numpy())
+    for O, lse in ((O_small, lse_small), (O_big, lse_big)):
+        assert np.abs(O.float().cpu().numpy() - want_O).max() <= 4e-3 * max(1.0, np.abs(want_O).max())
+        assert np.abs(lse.cpu().numpy() - want_l).max() <= 1e-3
