@@ -247,6 +247,27 @@ sc_status sc_gsc_merge_append(const void *K, const void *V, sc_dtype in_dtype,
                               void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * sc_gsc_merge_global — sc_gsc_merge when the whole sequence of every (sequence, KV head) is ONE chunk:
+ * Alg. 1 (Sec. 2.3) over all its tokens, no delimiter rows, then Eq. 3.  This is the "no chunking"
+ * variant of the paper's chunking ablation (Sec. 3.4), for which the chunk-by-chunk kernels of
+ * sc_gsc_merge are slow by construction; the result is what sc_segment on an all-zero mask followed by
+ * sc_gsc_merge gives (same integers; sums in row order).  bf16 inputs with d = 128 and N_max <= 32768 run
+ * a dedicated path (all pairwise comparisons on the matrix cores, a block-sequential resolution of the
+ * seeds, a gather by cluster); other shapes are handed to sc_gsc_merge's kernels with one-chunk offsets.
+ * Arguments, layouts, overflow behaviour (comp_lens = -1) and errors as for sc_gsc_merge, without offsets /
+ * num_chunks;  ws: sc_gsc_merge_global_workspace_bytes(B, Hkv, N_max, d) bytes (about N_max^2 / 8 bytes
+ * per (sequence, KV head) on the dedicated path: 1.1 GB for 8 heads of 32768 tokens).
+ */
+size_t sc_gsc_merge_global_workspace_bytes(int B, int Hkv, int N_max, int d);
+sc_status sc_gsc_merge_global(const void *K, const void *V, sc_dtype in_dtype,
+                              int64_t stride_b, int64_t stride_h, int64_t stride_n,
+                              const int32_t *seq_lens,
+                              int B, int Hkv, int N_max, int d, float tau,
+                              void *Kc, void *Vc, sc_dtype out_dtype, int cap,
+                              int32_t *counts, int32_t *comp_lens, int32_t *cluster_id,
+                              void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------------
  * sc_gsc_merge_budget — sc_gsc_merge with the threshold chosen for a target cache size.  The paper
  * reports at cache budgets (Sec. 3.1: 20 / 35 / 50 % of the entries kept) without giving the rule
  * that turns a budget into the threshold of Alg. 1; this call takes the largest threshold a bisection

@@ -81,6 +81,11 @@ def load_library() -> ctypes.CDLL:
     lib.sc_multi_attn_tail.restype = i32
     lib.sc_multi_attn_tail.argtypes = [vp, i32, i32, vp, vp, i32, i32, vp, vp, vp, vp, i32, vp, i32, i32, i32, i32, i32,
                                        f32, vp, i32, vp, vp, sz, vp]
+    lib.sc_gsc_merge_global_workspace_bytes.restype = sz
+    lib.sc_gsc_merge_global_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    lib.sc_gsc_merge_global.restype = i32
+    lib.sc_gsc_merge_global.argtypes = [vp, vp, i32, i64, i64, i64, vp, i32, i32, i32, i32, ctypes.c_float,
+                                        vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.sc_gsc_merge_budget_workspace_bytes.restype = sz
     lib.sc_gsc_merge_budget_workspace_bytes.argtypes = [i32, i32, i32, i32]
     lib.sc_gsc_merge_budget.restype = i32
@@ -98,6 +103,7 @@ EXPORTED = [
     "sc_decode_attn_static", "sc_decode_attn_tail", "sc_gsc_merge_append",
     "sc_multi_attn_workspace_bytes", "sc_multi_attn", "sc_multi_attn_tail",
     "sc_gsc_merge_budget_workspace_bytes", "sc_gsc_merge_budget",
+    "sc_gsc_merge_global_workspace_bytes", "sc_gsc_merge_global",
 ]
 
 
@@ -375,6 +381,33 @@ def sc_gsc_merge_budget(K, V, offsets, num_chunks, budget_rows: int, tau_lo: flo
                                  _ptr(cluster_id), _ptr(tau), _ptr(rows), workspace.ptr, workspace.nbytes, _stream())
     _check(st, "sc_gsc_merge_budget")
     return Kc, Vc, counts, comp_lens, cluster_id, tau, rows
+
+
+def sc_gsc_merge_global(K, V, tau: float, seq_lens=None, cap: Optional[int] = None, out_dtype=None,
+                        want_cluster_id: bool = False, workspace: Optional[Workspace] = None):
+    """sc_gsc_merge with the whole sequence of every (sequence, KV head) as one chunk (no offsets).
+    K, V [B, Hkv, N_max, d] -> (Kc, Vc, counts, comp_lens, cluster_id)."""
+    torch = _torch()
+    lib = load_library()
+    _require_cuda(K, V, seq_lens)
+    if K.dim() != 4 or K.shape != V.shape or K.stride() != V.stride() or K.stride(3) != 1 or K.dtype != V.dtype:
+        raise SemantiCacheError("K and V must be [B, Hkv, N_max, d] with identical strides and dtype")
+    B, H, N, d = K.shape
+    cap = N if cap is None else int(cap)
+    out_dtype = K.dtype if out_dtype is None else out_dtype
+    dev = K.device
+    Kc = torch.empty((B, H, cap, d), dtype=out_dtype, device=dev)
+    Vc = torch.empty((B, H, cap, d), dtype=out_dtype, device=dev)
+    counts = torch.empty((B, H, cap), dtype=torch.int32, device=dev)
+    comp_lens = torch.empty((B, H), dtype=torch.int32, device=dev)
+    cluster_id = torch.full((B, H, N), -9, dtype=torch.int32, device=dev) if want_cluster_id else None
+    if workspace is None:
+        workspace = Workspace(lib.sc_gsc_merge_global_workspace_bytes(B, H, N, d), dev)
+    st = lib.sc_gsc_merge_global(_ptr(K), _ptr(V), _dtype_code(K), K.stride(0), K.stride(1), K.stride(2), _ptr(seq_lens),
+                                 B, H, N, d, float(tau), _ptr(Kc), _ptr(Vc), _dtype_code(Kc), cap, _ptr(counts),
+                                 _ptr(comp_lens), _ptr(cluster_id), workspace.ptr, workspace.nbytes, _stream())
+    _check(st, "sc_gsc_merge_global")
+    return Kc, Vc, counts, comp_lens, cluster_id
 
 
 def stream_read_probe(buf, sink) -> None:

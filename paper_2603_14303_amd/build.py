@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsemanticache.so")
-SOURCES = ["sc_api.hip", "sc_segment.hip", "sc_gsc_merge.hip", "sc_gsc_fast.hip", "sc_decode.hip", "sc_multi.hip", "sc_budget.hip", "sc_probe.hip"]
+SOURCES = ["sc_api.hip", "sc_segment.hip", "sc_gsc_merge.hip", "sc_gsc_fast.hip", "sc_gsc_global.hip", "sc_decode.hip", "sc_multi.hip", "sc_budget.hip", "sc_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -198,6 +198,28 @@ sc_status sc_gsc_merge_append(const void *K, const void *V, sc_dtype in_dtype, i
                       stream);
 }
 
+size_t sc_gsc_merge_global_workspace_bytes(int B, int Hkv, int N_max, int d) {
+    if (B <= 0 || Hkv <= 0 || N_max <= 0) return 0;
+    return gsc_global_workspace_bytes(B, Hkv, N_max, d);
+}
+
+sc_status sc_gsc_merge_global(const void *K, const void *V, sc_dtype in_dtype, int64_t stride_b, int64_t stride_h,
+                              int64_t stride_n, const int32_t *seq_lens, int B, int Hkv, int N_max, int d, float tau,
+                              void *Kc, void *Vc, sc_dtype out_dtype, int cap, int32_t *counts, int32_t *comp_lens,
+                              int32_t *cluster_id, void *ws, size_t ws_bytes, void *stream) {
+    if (B <= 0 || Hkv <= 0 || N_max <= 0) return SC_ERR_INVALID_ARG;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SC_ERR_WORKSPACE;
+    // the start of the workspace takes the one-chunk offsets; everything else is checked as for sc_gsc_merge
+    int32_t *offsets = reinterpret_cast<int32_t *>(ws), *num_chunks = offsets + 2 * B;
+    GscMergeArgs a;
+    const sc_status st = gsc_check_and_fill(K, V, in_dtype, stride_b, stride_h, stride_n, seq_lens, offsets, 2, num_chunks, B, Hkv,
+                                            N_max, d, tau, Kc, Vc, out_dtype, cap, counts, nullptr, false, comp_lens, cluster_id,
+                                            ws, ws_bytes, a);
+    if (st != SC_OK) return st;
+    if (ws_bytes < gsc_global_workspace_bytes(B, Hkv, N_max, d)) return SC_ERR_WORKSPACE;
+    return runtime_status(launch_gsc_global(a, static_cast<hipStream_t>(stream)));
+}
+
 size_t sc_gsc_merge_budget_workspace_bytes(int B, int Hkv, int N_max, int d) {
     if (B <= 0 || Hkv <= 0 || N_max <= 0) return 0;
     return align_up(gsc_merge_workspace_bytes(B, Hkv, N_max, d), 256) + gsc_budget_state_bytes();

@@ -37,6 +37,10 @@ struct GscMergeArgs {
 size_t gsc_merge_workspace_bytes(int B, int Hkv, int N_max, int d);
 hipError_t launch_gsc_merge(const GscMergeArgs &a, hipStream_t stream);
 
+// ---- sc_gsc_merge_global: the whole sequence as one chunk (a.offsets / a.num_chunks are not used)
+size_t gsc_global_workspace_bytes(int B, int Hkv, int N_max, int d);
+hipError_t launch_gsc_global(const GscMergeArgs &a, hipStream_t stream);
+
 // ---- sc_gsc_merge_budget: bisection on the threshold, all on the device
 size_t gsc_budget_state_bytes();
 hipError_t launch_gsc_budget(GscMergeArgs a, long long budget_rows, float tau_lo, float tau_hi, int iterations,

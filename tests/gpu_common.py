@@ -57,10 +57,18 @@ def rowwise_err(got: np.ndarray, ref: np.ndarray) -> float:
 
 
 def run_compress(case, out_dtype, cap=None, want_cid=True, offsets=None, num_chunks=None, seq_lens_dev=None):
-    """Upload case (from helpers.build_case) and run sc_segment (unless given) + sc_gsc_merge."""
+    """Upload case (from helpers.build_case) and run sc_segment (unless given) + sc_gsc_merge; a case
+    marked "global_call" goes through sc_gsc_merge_global instead (it must have one chunk per sequence)."""
     w = case["workload"]
     bf16 = w.dtype == "bf16"
     K, V = to_device(case["K"], bf16), to_device(case["V"], bf16)
+    if case.get("global_call"):
+        assert not case["mask"].any()
+        sl = torch.from_numpy(case["seq_lens"].astype(np.int32)).to(DEV)
+        Kc, Vc, counts, lens, cid = sc.sc_gsc_merge_global(K, V, case["tau"], seq_lens=sl, cap=cap, out_dtype=out_dtype,
+                                                           want_cluster_id=want_cid)
+        torch.cuda.synchronize()
+        return dict(K=K, V=V, offsets=None, num_chunks=None, seq_lens=sl, Kc=Kc, Vc=Vc, counts=counts, comp_lens=lens, cid=cid)
     if offsets is None:
         offsets, num_chunks, seq_lens_dev = run_segment(case["mask"], case["seq_lens"])
     Kc, Vc, counts, lens, cid = sc.sc_gsc_merge(K, V, offsets, num_chunks, case["tau"], seq_lens=seq_lens_dev, cap=cap,
