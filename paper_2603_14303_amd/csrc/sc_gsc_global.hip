@@ -331,10 +331,12 @@ __global__ __launch_bounds__(kGlResolveThreads) void glob_resolve_kernel(GlobPar
             // ---- earliest seed of an earlier block that resembles the row
             const int cnt = valid ? s_lcnt[J & 1][lane] : 0;
             int seed_row = -1;
-            bool slow = cnt > kGlList;                 // incomplete list: the words decide
+            bool slow = false;
             {
+                // the list holds the row's kGlList earliest candidates: if one of them is a seed, the earliest seed
+                // is among them; if none is and the list is incomplete, the words decide
                 const int cmax = __builtin_amdgcn_readfirstlane(wave_max_i32(min(cnt, kGlList)));
-                bool done = slow;
+                bool done = false;
                 for (int e = 0; e < cmax; ++e) {
                     const int ent = s_list[J & 1][lane][e];
                     const int i = (e < cnt) ? (ent & 0x7FFFFFFF) : 0;      // beyond the list: whatever the buffer held before
@@ -345,6 +347,7 @@ __global__ __launch_bounds__(kGlResolveThreads) void glob_resolve_kernel(GlobPar
                         else slow = true;                // unsure: decided below, in list order
                     }
                 }
+                if (!done && cnt > kGlList) slow = true;
             }
             uint64_t slow_rows = ballot64(slow);
             while (slow_rows != 0ull) {
@@ -353,16 +356,15 @@ __global__ __launch_bounds__(kGlResolveThreads) void glob_resolve_kernel(GlobPar
                 const int jr = J * kGlBlock + r;
                 const int cr = __builtin_amdgcn_readlane(cnt, r);
                 int found = -1;
-                if (cr <= kGlList) {
-                    for (int e = 0; e < cr && found < 0; ++e) {
-                        const int ent = s_list[J & 1][r][e];
-                        const int i = ent & 0x7FFFFFFF;
-                        if (((s_mask[i >> 6] >> (i & 63)) & 1ull) == 0ull) continue;
-                        bool ok = ent >= 0;
-                        if (!ok) ok = gl_cosine_exceeds_f64(Kbh + (int64_t)i * p.stride_n, Kbh + (int64_t)jr * p.stride_n, p.tau, lane);
-                        if (ok) found = i;
-                    }
-                } else {
+                for (int e = 0; e < min(cr, kGlList) && found < 0; ++e) {
+                    const int ent = s_list[J & 1][r][e];
+                    const int i = ent & 0x7FFFFFFF;
+                    if (((s_mask[i >> 6] >> (i & 63)) & 1ull) == 0ull) continue;
+                    bool ok = ent >= 0;
+                    if (!ok) ok = gl_cosine_exceeds_f64(Kbh + (int64_t)i * p.stride_n, Kbh + (int64_t)jr * p.stride_n, p.tau, lane);
+                    if (ok) found = i;
+                }
+                if (found < 0 && cr > kGlList) {
                     for (int I0 = 0; I0 < J && found < 0; I0 += kWave) {
                         const int I = I0 + lane;
                         unsigned long long yy = 0ull, cc = 0ull;
@@ -403,6 +405,22 @@ __global__ __launch_bounds__(kGlResolveThreads) void glob_resolve_kernel(GlobPar
             const uint64_t y = dy & gl_bits_below(lane), u = du & gl_bits_below(lane);
             uint64_t todo = ballot64(open), seeds = 0ull;
             int my_seed = 0;
+            {
+                // Shortcut: guess that a free row is a seed iff no earlier free row of the block resembles it.  If every
+                // other free row then resembles an earlier guessed seed, and no unsure pair is involved, induction over
+                // the rows shows that the guess is the outcome of Alg. 1 (a guessed seed has no earlier similar free
+                // row, hence no earlier similar seed; any other row joins the first guessed seed it resembles).
+                const uint64_t free_before = todo & gl_bits_below(lane);
+                const bool guess = open && (y & free_before) == 0ull;
+                const uint64_t S = ballot64(guess);
+                const uint64_t hits = y & S;
+                const bool fine = !open || ((u & free_before) == 0ull && (guess || hits != 0ull));
+                if (ballot64(fine) == ~0ull) {
+                    seeds = S;
+                    my_seed = guess ? lane : (hits != 0ull ? first_bit(hits) : 0);
+                    todo = 0ull;
+                }
+            }
             while (todo != 0ull) {
                 const int s = __builtin_amdgcn_readfirstlane(first_bit(todo));     // lowest free row: nobody before it took it
                 const bool cand = ((todo >> lane) & 1ull) != 0ull && lane > s;
@@ -455,13 +473,14 @@ __global__ __launch_bounds__(kGlResolveThreads) void glob_resolve_kernel(GlobPar
             // rank of row j among the members of its cluster = members filed so far + earlier rows of this block in
             // the same cluster.  All lanes read the old sizes first, then the first row of every cluster in the block
             // files the new size (distinct clusters, distinct addresses): no chain of dependent LDS updates.
-            const int key = valid ? mine : -1 - lane;          // rows that do not exist match nobody
             int lower = 0, total = 0;
-#pragma unroll
-            for (int l = 0; l < kWave; ++l) {
-                const bool same = __builtin_amdgcn_readlane(key, l) == key;
-                total += same ? 1 : 0;
-                lower += (same && l < lane) ? 1 : 0;
+            uint64_t rem = ballot64(valid);
+            while (rem != 0ull) {      // once per cluster that has rows in the block
+                const int l0 = __builtin_amdgcn_readfirstlane(first_bit(rem));
+                const int c0 = __builtin_amdgcn_readlane(mine, l0);
+                const uint64_t same = ballot64(valid && mine == c0);
+                if ((same >> lane) & 1ull) { lower = __popcll(same & gl_bits_below(lane)); total = __popcll(same); }
+                rem &= ~same;
             }
             const int before = valid ? (int)s_csz[mine] : 0;
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
