@@ -381,6 +381,25 @@ def main():
 
         multi_ms = timed([capture(lambda i=i: multi_only(i)) for i in range(2)], 8, 8)
 
+        # the whole sequence as one chunk (the "no chunking" variant of the ablation): the call of its own
+        ws_g = sc.Workspace(sc.load_library().sc_gsc_merge_global_workspace_bytes(B, H, N, d), dev)
+        glob_out = [None]
+
+        def global_round():
+            for i in range(2):
+                glob_out[0] = sc.sc_gsc_merge_global(t["K"][i % len(t["K"])], t["V"][i % len(t["V"])], tau, seq_lens=t["lens"],
+                                                     cap=N, workspace=ws_g)
+        global_round()
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for _ in range(3):
+            global_round()
+        ev1.record()
+        torch.cuda.synchronize()
+        global_ms = ev0.elapsed_time(ev1) / 6
+        global_rows = int(glob_out[0][3].sum().item())
+
     e = 2
     rows_mean = float(rows_all.mean())
     # algorithmic bytes of one call (one layer): inputs read once, merged rows written once / read once
@@ -428,6 +447,11 @@ def main():
                          "decode_tail_GBps": tail_bytes / (dec_tail_ms * 1e-3) / 1e9,
                          "segment_plus_append_us": append_ms * 1e3, "rows_appended_per_head": added.ravel().tolist()[:64]}
         multi_bytes = rows_mean * (2 * d * e + 4) + 2 * NQ * B * Hq * d * e
+        pair_flops = 2.0 * d * sum(int(x) * (int(x) + 1) / 2 for x in host["lens"]) * H      # all pairs i < j of every (sequence, head)
+        out["one_chunk"] = {"sc_gsc_merge_global_ms": global_ms, "rows": global_rows, "workspace_GB": ws_g.nbytes / 1e9,
+                            "Mtok_per_s": n_tokens / (global_ms * 1e-3) / 1e6,
+                            "pair_TFLOPs": pair_flops / (global_ms * 1e-3) / 1e12,
+                            "note": "eager launches; pair_TFLOPs counts the n^2/2 * d MACs of all pairwise comparisons over the whole call"}
         out["multi_query"] = {"query_rows": NQ, "sc_multi_attn_us": multi_ms * 1e3,
                               "GBps": multi_bytes / (multi_ms * 1e-3) / 1e9,
                               "vs_row_by_row_decode": NQ * dec_call_ms / multi_ms}

@@ -7,7 +7,7 @@
 // advance, so the work is split into a dense part for the whole chip and a short sequential part:
 //   norms    reciprocal norms of all rows.
 //   pairs    all pairwise comparisons "Sim(i, j) > tau" for i < j on the matrix cores
-//            (v_mfma_f32_16x16x16_bf16, 64 x 64 rows per product block): one 64-bit word per (row j,
+//            (v_mfma_f32_16x16x32_bf16, 64 x 64 rows per product block): one 64-bit word per (row j,
 //            block of 64 earlier rows), "surely above" and "inside the +-1e-4 band" (decided later in
 //            fp64), stored column block by column block so that both this kernel and the next one
 //            move whole 512-byte runs.  n^2 * d MACs: 69 GMAC and 2 x 67 MB of bits per head at 32k.
@@ -31,12 +31,14 @@ typedef short gl_short4 __attribute__((ext_vector_type(4)));
 typedef float gl_float4 __attribute__((ext_vector_type(4)));
 typedef unsigned int gl_u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int gl_u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 gl_bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kGlD = 128;
 constexpr int kGlBlock = 64;                    // rows per block
 constexpr int kGlTileRowBytes = 272;            // 256 B of keys + 16 B pad: conflict-free operand reads
 constexpr int kGlPairWaves = 4;                 // row blocks per workgroup of the pairs kernel
 constexpr int kGlResolveThreads = 1024;
+constexpr int kGlSegment = 64;                  // column blocks per work item of the pairs kernel
 constexpr int kGlList = 32;                     // candidate list entries kept per row
 
 struct GlobParams {
@@ -128,17 +130,28 @@ __global__ __launch_bounds__(256) void glob_norms_kernel(GlobParams p) {
 // ------------------------------------------------------------------------------------------------
 // pairs: workgroup (JG, bh) owns the row blocks J = 4 JG + wave and walks the column blocks I = 0 .. max J.
 // The rows of block J are the B operand and stay in registers (lane (g, c): row 16 Jt + c, elements
-// 16 ks + 4 g .. + 3); the rows of block I pass through an LDS tile shared by the four wavefronts and are
+// 32 ks + 8 g .. + 7 -- v_mfma_f32_16x16x32_bf16, the form that runs at the full bf16 rate of this chip); the rows of block I pass through an LDS tile shared by the four wavefronts and are
 // the A operand.  The product tile leaves lane (g, c) with the dot products of row 16 Jt + c of block J
 // and rows 16 It + 4 g + i of block I: four bits of that row's word, completed by an OR over the lane groups.
 __global__ __launch_bounds__(kGlPairWaves *kWave, 2) void glob_pairs_kernel(GlobParams p) {
-    __shared__ __attribute__((aligned(16))) char s_tile[kGlBlock * kGlTileRowBytes];
-    __shared__ float s_rinv[kGlBlock];
+    __shared__ __attribute__((aligned(16))) char s_tiles[2][kGlBlock * kGlTileRowBytes];      // two tiles: one worked on, one being filled
+    __shared__ float s_rinvs[2][kGlBlock];
     const int bh = blockIdx.y, b = bh / p.Hkv, h = bh - b * p.Hkv;
     const int n = gl_seq_len(p, b);
     const int nb = (n + kGlBlock - 1) / kGlBlock;
     const int njg = (nb + kGlPairWaves - 1) / kGlPairWaves;
-    const int JG = (int)gridDim.x - 1 - (int)blockIdx.x;      // the longest walks are dispatched first
+    // Work item = (group JG of four row blocks, segment of kGlSegment column blocks): the walks over the column
+    // blocks have about the same length whatever the row.  Groups 16 q .. 16 q + 15 have q + 1 segments each
+    // (kGlSegment = 64 column blocks = 16 groups), so 8 q (q + 1) items come before group 16 q.
+    int JG, seg;
+    {
+        const int x = (int)gridDim.x - 1 - (int)blockIdx.x;      // the longest rows first
+        int q = 0;
+        while (8 * (q + 1) * (q + 2) <= x) ++q;
+        const int rem = x - 8 * q * (q + 1);
+        JG = 16 * q + rem / (q + 1);
+        seg = rem % (q + 1);
+    }
     if (JG >= njg) return;
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -149,7 +162,7 @@ __global__ __launch_bounds__(kGlPairWaves *kWave, 2) void glob_pairs_kernel(Glob
     const float *rinv_bh = p.rinv + (int64_t)bh * p.nbp * 64;
     const int sb = (int)p.stride_n * 2;      // bytes between rows
     // rows of block J as B operands, through a descriptor that ends after the sequence's last row
-    uint2 bq[4][8];
+    uint4 bq[4][4];
     float hn[4], wn[4];
     bool bad_j = false;      // a row of block J without a usable norm (also: beyond the end of the sequence)
     {
@@ -159,9 +172,9 @@ __global__ __launch_bounds__(kGlPairWaves *kWave, 2) void glob_pairs_kernel(Glob
 #pragma unroll
         for (int Jt = 0; Jt < 4; ++Jt) {
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                const gl_u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(src, (16 * Jt + c) * sb + (16 * ks + 4 * g) * 2, 0, 0);
-                bq[Jt][ks] = make_uint2(v.x, v.y);
+            for (int ks = 0; ks < 4; ++ks) {
+                const gl_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(src, (16 * Jt + c) * sb + (32 * ks + 8 * g) * 2, 0, 0);
+                bq[Jt][ks] = make_uint4(v.x, v.y, v.z, v.w);
             }
             const float rn = active ? rinv_bh[J * kGlBlock + 16 * Jt + c] : __builtin_nanf("");
             bad_j = bad_j || !(rn == rn);
@@ -171,7 +184,9 @@ __global__ __launch_bounds__(kGlPairWaves *kWave, 2) void glob_pairs_kernel(Glob
         }
     }
     bad_j = ballot64(bad_j) != 0ull;
-    const int I_last = min(JG * kGlPairWaves + kGlPairWaves - 1, nb - 1);
+    const int I_first = seg * kGlSegment;
+    const int I_last = min(min(JG * kGlPairWaves + kGlPairWaves - 1, nb - 1), I_first + kGlSegment - 1);
+    if (I_first > I_last) return;
     // the tile of block I: thread t brings rows t / 16 + 16 r, piece t % 16
     const int lrow = tid >> 4, lc = tid & 15;
     uint4 pre[4];
@@ -187,18 +202,23 @@ __global__ __launch_bounds__(kGlPairWaves *kWave, 2) void glob_pairs_kernel(Glob
         }
         if (tid < kGlBlock) pre_r = rinv_bh[I * kGlBlock + tid];
     };
-    // lane r of an active wavefront is row r of block J: its candidates in earlier blocks, in ascending order
-    const int my_row = J * kGlBlock + lane;
-    int32_t *my_list = p.lists + ((int64_t)bh * p.nbp * kGlBlock + my_row) * kGlList;
-    int n_cand = 0;
-    fetch(0);
-    for (int I = 0; I <= I_last; ++I) {
-        __syncthreads();          // everybody is done with the previous tile
+    auto park = [&](int I) {
+        char *t = s_tiles[I & 1];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) *reinterpret_cast<uint4 *>(s_tile + (lrow + 16 * r) * kGlTileRowBytes + 16 * lc) = pre[r];
-        if (tid < kGlBlock) s_rinv[tid] = pre_r;
-        __syncthreads();
-        if (I < I_last) fetch(I + 1);      // on its way while this tile is worked on
+        for (int r = 0; r < 4; ++r) *reinterpret_cast<uint4 *>(t + (lrow + 16 * r) * kGlTileRowBytes + 16 * lc) = pre[r];
+        if (tid < kGlBlock) s_rinvs[I & 1][tid] = pre_r;
+    };
+    fetch(I_first);
+    park(I_first);
+    if (I_first < I_last) fetch(I_first + 1);
+    for (int I = I_first; I <= I_last; ++I) {
+        __syncthreads();          // tile I is complete; everybody is done with tile I - 1, whose buffer takes tile I + 1 now
+        if (I < I_last) {
+            park(I + 1);
+            if (I + 1 < I_last) fetch(I + 2);      // on its way while this tile is worked on
+        }
+        const char *s_tile = s_tiles[I & 1];
+        const float *s_rinv = s_rinvs[I & 1];
         if (!active || I > J) continue;    // wave-uniform
         uint32_t yl[4], yh[4], ul[4], uh[4];
 #pragma unroll
@@ -209,12 +229,12 @@ __global__ __launch_bounds__(kGlPairWaves *kWave, 2) void glob_pairs_kernel(Glob
 #pragma unroll
             for (int Jt = 0; Jt < 4; ++Jt) acc[Jt] = gl_float4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                const uint2 a = *reinterpret_cast<const uint2 *>(s_tile + (16 * It + c) * kGlTileRowBytes + (16 * ks + 4 * g) * 2);
+            for (int ks = 0; ks < 4; ++ks) {
+                const uint4 a = *reinterpret_cast<const uint4 *>(s_tile + (16 * It + c) * kGlTileRowBytes + (32 * ks + 8 * g) * 2);
 #pragma unroll
                 for (int Jt = 0; Jt < 4; ++Jt)
-                    acc[Jt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(gl_short4, a),
-                                                                        __builtin_bit_cast(gl_short4, bq[Jt][ks]), acc[Jt], 0, 0, 0);
+                    acc[Jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(gl_bf16x8, a),
+                                                                      __builtin_bit_cast(gl_bf16x8, bq[Jt][ks]), acc[Jt], 0, 0, 0);
             }
             const gl_float4 rm = *reinterpret_cast<const gl_float4 *>(s_rinv + 16 * It + 4 * g);
             // sim(m, n) > t  <=>  dot * rinv_m > t * norm_n:  dd = (tau + band) * norm_n - dot * rinv_m is negative
@@ -272,18 +292,47 @@ __global__ __launch_bounds__(kGlPairWaves *kWave, 2) void glob_pairs_kernel(Glob
         const bool any_u = ballot64((mul | muh) != 0u) != 0ull;
         if (any_u || I == J) p.U[w] = ((unsigned long long)muh << 32) | mul;      // a block's own words are always read
         if (lane == 0) p.uflag[((long long)bh * p.nbp + J) * p.nbp + I] = any_u ? 1 : 0;
-        if (I < J && my_row < n) {
-            uint64_t yw = ((uint64_t)myh << 32) | myl, uw = ((uint64_t)muh << 32) | mul;
-            uint64_t cw = yw | uw;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// lists: one wavefront per row block J, lane r = row r.  The row's candidates in earlier blocks (set bits
+// of its words, column block after column block) in ascending order; bit 31 of an entry = unsure.  The
+// first kGlList are kept, the count says how many there were.
+__global__ __launch_bounds__(kWave) void glob_lists_kernel(GlobParams p) {
+    const int bh = blockIdx.y, b = bh / p.Hkv;
+    const int n = gl_seq_len(p, b);
+    const int nb = (n + kGlBlock - 1) / kGlBlock;
+    const int J = (int)gridDim.x - 1 - (int)blockIdx.x;       // the longest rows first
+    if (J >= nb) return;
+    const int lane = threadIdx.x, row = J * kGlBlock + lane;
+    const unsigned long long *Y = p.Y + (long long)bh * p.tri, *U = p.U + (long long)bh * p.tri;
+    const unsigned char *fl = p.uflag + ((long long)bh * p.nbp + J) * p.nbp;
+    int32_t *my_list = p.lists + ((int64_t)bh * p.nbp * kGlBlock + row) * kGlList;
+    int n_cand = 0;
+    constexpr int kBatch = 8;
+    for (int I0 = 0; I0 < J; I0 += kBatch) {
+        unsigned long long yw[kBatch], uw[kBatch];
+#pragma unroll
+        for (int k = 0; k < kBatch; ++k) {
+            const int I = I0 + k;
+            const bool in = I < J;
+            const long long w = gl_col_base(in ? I : 0, p.nbp) + (long long)(row - (in ? I : 0) * kGlBlock);
+            yw[k] = in ? Y[w] : 0ull;
+            uw[k] = (in && fl[in ? I : 0] != 0) ? U[w] : 0ull;
+        }
+#pragma unroll
+        for (int k = 0; k < kBatch; ++k) {
+            uint64_t cw = row < n ? (yw[k] | uw[k]) : 0ull;      // rows beyond the end have no list
             while (cw != 0ull) {
                 const int bit = first_bit(cw);
                 cw &= cw - 1ull;
-                if (n_cand < kGlList) my_list[n_cand] = (I * kGlBlock + bit) | (((yw >> bit) & 1ull) ? 0 : (int)0x80000000);
+                if (n_cand < kGlList) my_list[n_cand] = ((I0 + k) * kGlBlock + bit) | (((yw[k] >> bit) & 1ull) ? 0 : (int)0x80000000);
                 n_cand += 1;
             }
         }
     }
-    if (active && my_row < n) p.lcount[(int64_t)bh * p.nbp * kGlBlock + my_row] = n_cand;
+    if (row < n) p.lcount[(int64_t)bh * p.nbp * kGlBlock + row] = n_cand;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -653,13 +702,26 @@ hipError_t launch_gsc_global(const GscMergeArgs &a, hipStream_t stream) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int njg = (p.nbp + kGlPairWaves - 1) / kGlPairWaves;
-    hipLaunchKernelGGL(glob_pairs_kernel, dim3((unsigned)njg, (unsigned)BH), dim3(kGlPairWaves * kWave), 0, stream, p);
+    int items = 0;      // see the kernel: group JG has JG / 16 + 1 segments
+    for (int jg = 0; jg < njg; ++jg) items += jg / 16 + 1;
+    hipLaunchKernelGGL(glob_pairs_kernel, dim3((unsigned)items, (unsigned)BH), dim3(kGlPairWaves * kWave), 0, stream, p);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(glob_lists_kernel, dim3((unsigned)p.nbp, (unsigned)BH), dim3(kWave), 0, stream, p);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     const size_t dyn = npad * sizeof(unsigned short);
-    if (dyn > 48 * 1024) {   // a host-side setting of the kernel, not a stream operation
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(glob_resolve_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+    if (dyn > 48 * 1024) {   // a host-side setting of the kernel (per device), not a stream operation
+        int dev = 0;
+        e = hipGetDevice(&dev);
         if (e != hipSuccess) return e;
+        static bool raised[64];
+        if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+        if (!raised[dev]) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(glob_resolve_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+            if (e != hipSuccess) return e;
+            raised[dev] = true;
+        }
     }
     hipLaunchKernelGGL(glob_resolve_kernel, dim3((unsigned)BH), dim3(kGlResolveThreads), dyn, stream, p);
     e = hipGetLastError();
