@@ -26,6 +26,7 @@ namespace sc {
 
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2f_t;
 typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8f_t __attribute__((ext_vector_type(8)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
 
@@ -267,43 +268,54 @@ __device__ __forceinline__ void membership_mfma_b(const RowRegs &x, const uint32
 }
 
 // keys and values of a window in one sweep: the keys come back from the LDS copy made by gram_bitmatrix
-// (16 rows at a time), the values are in registers; both share the 0/1 operand
+// (32 rows at a time), the values are in registers; both share the 0/1 operand.  v_mfma_f32_16x16x32_bf16:
+// contraction step qq covers rows 32 qq .. 32 qq + 31, its index (lane / 16, i), i = 0..7, stands for row
+// 32 qq + 4 i + lane / 16 = register 8 qq + i of the lane's own group.
 __device__ __forceinline__ void membership_mfma_kv(const char *lds, const RowRegs &xv, const uint32_t (&ob)[4], int want,
                                                    int q_hi, int lane, floatx4_t (&DK)[8], floatx4_t (&DV)[8], floatx4_t &Dn) {
     const int g = lane >> 4, c = lane & 15;
-    const short4_t ones = {0x3F80, 0x3F80, 0x3F80, 0x3F80};
+    const uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        if (q < q_hi) {
-            uint4 r[4];
+    for (int qq = 0; qq < 2; ++qq) {
+        if (2 * qq < q_hi) {
+            uint4 r[8];
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                r[i] = *reinterpret_cast<const uint4 *>(lds + (4 * (4 * q + i) + g) * kLdsRowBytes + 16 * c);
-            short4_t a;
-            a[0] = (((ob[q] >> 0) & 0xFFu) == (uint32_t)want) ? (short)0x3F80 : (short)0;
-            a[1] = (((ob[q] >> 8) & 0xFFu) == (uint32_t)want) ? (short)0x3F80 : (short)0;
-            a[2] = (((ob[q] >> 16) & 0xFFu) == (uint32_t)want) ? (short)0x3F80 : (short)0;
-            a[3] = (((ob[q] >> 24) & 0xFFu) == (uint32_t)want) ? (short)0x3F80 : (short)0;
+            for (int i = 0; i < 8; ++i)
+                r[i] = *reinterpret_cast<const uint4 *>(lds + (4 * (8 * qq + i) + g) * kLdsRowBytes + 16 * c);
+            uint32_t aw[4];
+#pragma unroll
+            for (int h2 = 0; h2 < 2; ++h2) {
+                const uint32_t b4 = ob[2 * qq + h2];
+                const uint32_t m0 = (((b4 >> 0) & 0xFFu) == (uint32_t)want) ? 0x3F80u : 0u;
+                const uint32_t m1 = (((b4 >> 8) & 0xFFu) == (uint32_t)want) ? 0x3F80u : 0u;
+                const uint32_t m2 = (((b4 >> 16) & 0xFFu) == (uint32_t)want) ? 0x3F80u : 0u;
+                const uint32_t m3 = (((b4 >> 24) & 0xFFu) == (uint32_t)want) ? 0x3F80u : 0u;
+                aw[2 * h2] = m0 | (m1 << 16);
+                aw[2 * h2 + 1] = m2 | (m3 << 16);
+            }
+            const bf16x8f_t a = __builtin_bit_cast(bf16x8f_t, make_uint4(aw[0], aw[1], aw[2], aw[3]));
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 {
-                    const uint32_t d0 = dword_of(r[0], j >> 1), d1 = dword_of(r[1], j >> 1);
-                    const uint32_t d2 = dword_of(r[2], j >> 1), d3 = dword_of(r[3], j >> 1);
-                    const uint32_t lo = (j & 1) ? pack_hi(d0, d1) : pack_lo(d0, d1);
-                    const uint32_t hi = (j & 1) ? pack_hi(d2, d3) : pack_lo(d2, d3);
-                    const uint2 bb = make_uint2(lo, hi);
-                    DK[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, __builtin_bit_cast(short4_t, bb), DK[j], 0, 0, 0);
+                    uint32_t w[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const uint32_t d0 = dword_of(r[2 * t], j >> 1), d1 = dword_of(r[2 * t + 1], j >> 1);
+                        w[t] = (j & 1) ? pack_hi(d0, d1) : pack_lo(d0, d1);
+                    }
+                    DK[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8f_t, make_uint4(w[0], w[1], w[2], w[3])), DK[j], 0, 0, 0);
                 }
                 {
-                    const uint32_t d0 = dword_of(xv.r[4 * q + 0], j >> 1), d1 = dword_of(xv.r[4 * q + 1], j >> 1);
-                    const uint32_t d2 = dword_of(xv.r[4 * q + 2], j >> 1), d3 = dword_of(xv.r[4 * q + 3], j >> 1);
-                    const uint32_t lo = (j & 1) ? pack_hi(d0, d1) : pack_lo(d0, d1);
-                    const uint32_t hi = (j & 1) ? pack_hi(d2, d3) : pack_lo(d2, d3);
-                    const uint2 bb = make_uint2(lo, hi);
-                    DV[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, __builtin_bit_cast(short4_t, bb), DV[j], 0, 0, 0);
+                    uint32_t w[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const uint32_t d0 = dword_of(xv.r[8 * qq + 2 * t], j >> 1), d1 = dword_of(xv.r[8 * qq + 2 * t + 1], j >> 1);
+                        w[t] = (j & 1) ? pack_hi(d0, d1) : pack_lo(d0, d1);
+                    }
+                    DV[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8f_t, make_uint4(w[0], w[1], w[2], w[3])), DV[j], 0, 0, 0);
                 }
             }
-            Dn = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, ones, Dn, 0, 0, 0);
+            Dn = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8f_t, ones), Dn, 0, 0, 0);
         }
     }
 }
@@ -311,9 +323,9 @@ __device__ __forceinline__ void membership_mfma_kv(const char *lds, const RowReg
 // ------------------------------------------------------------------------------------------------
 // All pairwise similarities of a window at once (Eq. 2 for every pair the seeds of Alg. 1 can ask for).
 // The window's rows are parked in LDS (row stride 272 B) and read back in the operand layout of
-// v_mfma_f32_16x16x16_bf16 (lane l: row l%16 of a 16-row tile, elements 4*(l/16)..+3 of a 16-element
+// v_mfma_f32_16x16x32_bf16 (lane l: row l%16 of a 16-row tile, elements 8*(l/16)..+7 of a 32-element
 // slice); a tile of keys is both the A operand (rows m) and the B operand (rows n) of the Gram tile
-// G[m][n] = k_m . k_n.  The ten upper-triangle tiles of the 64 x 64 Gram matrix take 80 MFMAs.
+// G[m][n] = k_m . k_n.  The ten upper-triangle tiles of the 64 x 64 Gram matrix take 40 MFMAs.
 // Each lane then turns its 4 x 10 dot products into cosines, compares them with tau and files the
 // outcome as bit m of a per-column word; an OR over the four lane groups completes the words, and lane
 // r (row order) ends up with  yes[r]: bit m set iff Sim(m, r) > tau + band   (m < r or same tile)
@@ -328,13 +340,15 @@ __device__ __forceinline__ uint32_t or_rows(uint32_t x) {   // OR over the four 
 // Gram tiles (I, J), I <= J < NT, of the rows parked in LDS; tile k = index in the 4 x 4 upper triangle
 template <int NT>
 __device__ __forceinline__ void gram_tiles(const char *lds, int g, int c, floatx4_t (&acc)[10]) {
+    // v_mfma_f32_16x16x32_bf16: 32 elements of the contraction per product (lane l: elements 8 * (l / 16) .. + 7
+    // of a 32-element slice), the form that runs at the full bf16 rate of this chip
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-        short4_t a[NT];
+    for (int ks = 0; ks < 4; ++ks) {
+        bf16x8f_t a[NT];
 #pragma unroll
         for (int I = 0; I < NT; ++I) {
-            const uint2 v = *reinterpret_cast<const uint2 *>(lds + (16 * I + c) * kLdsRowBytes + (16 * ks + 4 * g) * 2);
-            a[I] = __builtin_bit_cast(short4_t, v);
+            const uint4 v = *reinterpret_cast<const uint4 *>(lds + (16 * I + c) * kLdsRowBytes + (32 * ks + 8 * g) * 2);
+            a[I] = __builtin_bit_cast(bf16x8f_t, v);
         }
 #pragma unroll
         for (int I = 0; I < NT; ++I)
@@ -342,7 +356,7 @@ __device__ __forceinline__ void gram_tiles(const char *lds, int g, int c, floatx
             for (int J = I; J < NT; ++J) {
                 constexpr int base[4] = {0, 4, 7, 9};
                 const int k = base[I] + (J - I);
-                acc[k] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a[I], a[J], acc[k], 0, 0, 0);
+                acc[k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[I], a[J], acc[k], 0, 0, 0);
             }
     }
 }
