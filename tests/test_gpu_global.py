@@ -74,3 +74,71 @@ def test_other_shapes_go_through_the_ordinary_kernels(base, knob):
         if knob:
             sc.tune_set(knob, old)
     print(base, "rows", out["comp_lens"].tolist(), "merge_err %.2e" % out["worst_merge_err"])
+
+
+def _run_rows(K, V, tau):
+    """K, V [n, 128] float arrays (bf16-exact) as one (sequence, head): GPU call and oracle on one-chunk offsets."""
+    import oracle
+    n = K.shape[0]
+    Kd = torch.from_numpy(K).to(g.DEV).to(torch.bfloat16).view(1, 1, n, 128)
+    Vd = torch.from_numpy(V).to(g.DEV).to(torch.bfloat16).view(1, 1, n, 128)
+    Kc, Vc, counts, lens, cid = sc.sc_gsc_merge_global(Kd, Vd, tau, out_dtype=torch.float32, want_cluster_id=True)
+    torch.cuda.synchronize()
+    ref = oracle.compress_head(K.astype(np.float64), V.astype(np.float64), np.array([0, n + 1], np.int32), tau)
+    assert lens.item() == ref["n_rows"]
+    assert np.array_equal(cid[0, 0].cpu().numpy(), ref["cid"])
+    r = ref["n_rows"]
+    assert np.array_equal(counts[0, 0, :r].cpu().numpy(), ref["counts"][:r])
+    assert g.rowwise_err(Kc[0, 0, :r].cpu().numpy(), ref["Kc"][:r]) <= 1e-3
+    assert g.rowwise_err(Vc[0, 0, :r].cpu().numpy(), ref["Vc"][:r]) <= 1e-3
+    return ref
+
+
+def _bf16_exact(x):
+    return torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16).float().numpy()
+
+
+def test_more_candidates_than_a_list_holds_and_none_is_a_seed():
+    # Row j resembles 40 rows b_k of an earlier block, all of which were absorbed by a seed that j does not
+    # resemble; the seed that does take j comes after them.  j's candidate list (32 entries) then holds no
+    # seed although j has one: the kernel must go back to the bit arrays.  Unit vectors in a plane:
+    # a at 0, b_k at 18, j at 36, s at 50 degrees, tau = 0.9 (cos 18 = 0.951, cos 36 = 0.809, cos 14 = 0.970, cos 32 = 0.848).
+    rng = np.random.default_rng(3)
+    n, d = 200, 128
+    e0, e1 = np.zeros(d), np.zeros(d)
+    e0[5], e1[77] = 1.0, 1.0
+
+    def at(deg, scale=1.0):
+        return scale * (np.cos(np.radians(deg)) * e0 + np.sin(np.radians(deg)) * e1)
+    K = np.zeros((n, d))
+    filler = rng.standard_normal((n, d))
+    filler[:, 5] = 0
+    filler[:, 77] = 0                      # orthogonal to the plane: resembles nothing in it
+    K[:] = filler
+    K[0] = at(0)
+    for k in range(40):
+        K[3 + k] = at(18, 1.0 + 0.1 * k)    # block 0: absorbed by row 0
+    K[70] = at(50)                          # block 1: a seed (resembles neither a nor the b_k)
+    K[150] = at(36)                         # block 2: candidates = 40 b_k (no seeds) and then row 70
+    K[151] = at(36.5, 3.0)
+    K = _bf16_exact(K)
+    V = _bf16_exact(rng.standard_normal((n, d)))
+    ref = _run_rows(K, V, 0.9)
+    assert ref["cid"][150] == ref["cid"][70] and ref["cid"][3] == ref["cid"][0] and ref["cid"][150] != ref["cid"][0]
+
+
+def test_zero_rows_duplicates_and_scaled_rows():
+    # zero rows resemble nothing (also inside a block and across blocks), exact duplicates and scaled copies merge
+    rng = np.random.default_rng(5)
+    n, d = 300, 128
+    K = rng.standard_normal((n, d))
+    K[10] = 0; K[11] = 0; K[200] = 0
+    K[50] = K[40]; K[130] = K[40] * 3.0; K[270] = K[40] * 0.01; K[271] = K[41]
+    K = _bf16_exact(K)
+    K[130] = _bf16_exact(K[40] * 4.0)       # exact in bf16: a power of two
+    K[270] = _bf16_exact(K[40] * 0.0078125)
+    V = _bf16_exact(rng.standard_normal((n, d)))
+    ref = _run_rows(K, V, 0.999)
+    for j in (50, 130, 270):
+        assert ref["cid"][j] == ref["cid"][40]
+    assert ref["cid"][271] == ref["cid"][41] and len({ref["cid"][10], ref["cid"][11], ref["cid"][200]}) == 3
