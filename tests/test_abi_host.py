@@ -207,6 +207,26 @@ def test_gsc_merge_budget_rejects_bad_arguments(lib):
     assert call(ws=None) == 4 and call(wsb=need - 1) == 4
 
 
+def test_gsc_merge_global_rejects_bad_arguments(lib):
+    f = lib.sc_gsc_merge_global
+    need = lib.sc_gsc_merge_global_workspace_bytes(1, 2, 1024, 128)
+    # room for the one-chunk offsets, the ordinary kernels' workspace and the bit arrays (n^2 / 8 bytes per array and head)
+    assert need > lib.sc_gsc_merge_workspace_bytes(1, 2, 1024, 128) and need > 2 * 2 * 1024 * 1024 // 16
+    assert lib.sc_gsc_merge_global_workspace_bytes(0, 2, 1024, 128) == 0
+    ok = dict(K=FAKE, V=FAKE, idt=1, sb=2 * 1024 * 128, sh=1024 * 128, sn=128, lens=None, B=1, H=2, N=1024, d=128, tau=0.7,
+              Kc=FAKE, Vc=FAKE, odt=1, cap=1024, counts=FAKE, clens=FAKE, cid=None, ws=FAKE, wsb=need)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["K"], a["V"], a["idt"], a["sb"], a["sh"], a["sn"], a["lens"], a["B"], a["H"], a["N"], a["d"], a["tau"],
+                 a["Kc"], a["Vc"], a["odt"], a["cap"], a["counts"], a["clens"], a["cid"], a["ws"], a["wsb"], None)
+    for k in ("K", "V", "Kc", "Vc", "counts", "clens"):
+        assert call(**{k: None}) == 1, k
+    assert call(B=0) == 1 and call(N=0) == 1 and call(tau=float("nan")) == 1 and call(sn=64) == 1
+    assert call(cap=0) == 3 and call(d=96) == 2 and call(idt=7) == 2
+    assert call(ws=None) == 4 and call(wsb=need - 1) == 4 and call(ws=FAKE + 16) == 4
+
+
 def test_check_lengths_rejects_bad_arguments(lib):
     import ctypes
     bad = ctypes.c_int(7)
