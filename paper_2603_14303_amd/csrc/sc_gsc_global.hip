@@ -25,9 +25,10 @@
 #include "sc_gsc_params.h"
 #include "sc_host.h"
 
+#include <mutex>
+
 namespace sc {
 
-typedef short gl_short4 __attribute__((ext_vector_type(4)));
 typedef float gl_float4 __attribute__((ext_vector_type(4)));
 typedef unsigned int gl_u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int gl_u32x2 __attribute__((ext_vector_type(2)));
@@ -715,8 +716,10 @@ hipError_t launch_gsc_global(const GscMergeArgs &a, hipStream_t stream) {
         int dev = 0;
         e = hipGetDevice(&dev);
         if (e != hipSuccess) return e;
+        static std::mutex mu;
         static bool raised[64];
         if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+        std::lock_guard<std::mutex> lock(mu);
         if (!raised[dev]) {
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(glob_resolve_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
             if (e != hipSuccess) return e;
