@@ -1,16 +1,17 @@
 // sc_segment: delimiter mask -> chunk offsets (paper Sec. 2.2, Eq. 1).
 //
-// One workgroup of 1024 threads walks one sequence in tiles of 16 KiB of mask: every thread reads
-// 16 mask bytes with one 16-byte load, turns them into a 16-bit "is delimiter" word, a block-wide
-// exclusive scan of the popcounts gives each thread the rank of its first delimiter, and the
-// positions are scattered to offsets[rank + 1].  Pure integer work, HBM traffic = the mask once.
+// One workgroup of 1024 threads walks one sequence in tiles of 32 KiB of mask: every thread reads
+// 32 mask bytes with two 16-byte loads (both in flight together), turns them into a 64-bit "is
+// delimiter" word, a block-wide exclusive scan of the popcounts gives each thread the rank of its first
+// delimiter, and the positions are scattered to offsets[rank + 1].  A tile costs three barriers, so a
+// 32k-token sequence is one tile.  Pure integer work, HBM traffic = the mask once.
 #include "sc_device.h"
 #include "sc_host.h"
 
 namespace sc {
 
 constexpr int kSegThreads = 1024;
-constexpr int kSegBytesPerThread = 16;
+constexpr int kSegBytesPerThread = 32;
 
 __device__ __forceinline__ uint32_t nonzero_bytes4(uint32_t w) {
     // bit k set iff byte k of w is nonzero
@@ -41,16 +42,23 @@ __global__ __launch_bounds__(kSegThreads) void segment_kernel(
     int running = 0;  // delimiters found in earlier tiles
     for (int base = 0; base < n; base += kSegThreads * kSegBytesPerThread) {
         const int i0 = base + tid * kSegBytesPerThread;
-        uint32_t bits = 0;
+        uint64_t bits = 0;
         if (i0 + kSegBytesPerThread <= n && aligned) {
-            const uint4 v = *reinterpret_cast<const uint4 *>(row + i0);
-            bits = nonzero_bytes4(v.x) | (nonzero_bytes4(v.y) << 4) | (nonzero_bytes4(v.z) << 8) |
-                   (nonzero_bytes4(v.w) << 12);
+            constexpr int kLoads = kSegBytesPerThread / 16;
+            uint4 v[kLoads];
+#pragma unroll
+            for (int q = 0; q < kLoads; ++q) v[q] = *reinterpret_cast<const uint4 *>(row + i0 + 16 * q);
+#pragma unroll
+            for (int q = 0; q < kLoads; ++q) {
+                const uint32_t b16 = nonzero_bytes4(v[q].x) | (nonzero_bytes4(v[q].y) << 4) | (nonzero_bytes4(v[q].z) << 8) |
+                                     (nonzero_bytes4(v[q].w) << 12);
+                bits |= (uint64_t)b16 << (16 * q);
+            }
         } else {
             for (int k = 0; k < kSegBytesPerThread; ++k)
-                if (i0 + k < n && row[i0 + k] != 0) bits |= 1u << k;
+                if (i0 + k < n && row[i0 + k] != 0) bits |= 1ull << k;
         }
-        const int cnt = __popc(bits);
+        const int cnt = __popcll(bits);
         // inclusive scan inside the wave
         int incl = cnt;
 #pragma unroll
@@ -75,7 +83,7 @@ __global__ __launch_bounds__(kSegThreads) void segment_kernel(
         int rank = running + s_wave_total[wave] + incl - cnt;  // delimiters before this thread's bytes
         const int tile_total = s_tile_total;
         while (bits) {
-            const int k = __ffs(bits) - 1;
+            const int k = __ffsll((unsigned long long)bits) - 1;
             bits &= bits - 1;
             rank += 1;
             if (rank < offsets_cap) off[rank] = i0 + k + 1;
