@@ -142,3 +142,44 @@ def test_zero_rows_duplicates_and_scaled_rows():
     for j in (50, 130, 270):
         assert ref["cid"][j] == ref["cid"][40]
     assert ref["cid"][271] == ref["cid"][41] and len({ref["cid"][10], ref["cid"][11], ref["cid"][200]}) == 3
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_structures_as_one_chunk(seed):
+    # the key mixtures of test_gpu_random.py (centres drawn per stretch, duplicates, zero rows, rows scaled by 0.01
+    # and 30, thresholds inside the similarity bands) clustered as ONE chunk per sequence: ragged batch of three
+    import oracle
+    from test_gpu_random import _random_mask, _random_keys
+    rng = np.random.default_rng(1000 + seed)
+    B, H, d = 3, 2, 128
+    N = int(rng.integers(100, 1200))
+    lens = rng.integers(1, N + 1, size=B).astype(np.int32)
+    lens[0] = N
+    K = np.zeros((B, H, N, d), np.float32)
+    V = np.zeros_like(K)
+    for b in range(B):
+        n = int(lens[b])
+        shape_mask = _random_mask(rng, n)          # shapes the keys only; the clustering sees no boundary
+        for h in range(H):
+            K[b, h, :n], V[b, h, :n] = _random_keys(rng, shape_mask, n, d, True)
+    tau = float(rng.choice([0.3, 0.7, 0.9, 0.97, 0.985, 0.995, 0.9999, -0.5]))
+    dK, dV = g.to_device(K, True), g.to_device(V, True)
+    sl = torch.from_numpy(lens).to(g.DEV)
+    Kc, Vc, counts, clens, cid = sc.sc_gsc_merge_global(dK, dV, tau, seq_lens=sl, out_dtype=torch.float32, want_cluster_id=True)
+    torch.cuda.synchronize()
+    compared = 0
+    for b in range(B):
+        n = int(lens[b])
+        for h in range(H):
+            r = oracle.compress_head(K[b, h, :n], V[b, h, :n], np.array([0, n + 1], np.int32), tau)
+            if r["chunk_margin"].min() <= 1e-9:
+                continue                                             # a coin toss in fp64 itself: not a parity case
+            compared += 1
+            rows = r["n_rows"]
+            assert int(clens[b, h]) == rows, (seed, b, h, int(clens[b, h]), rows)
+            assert np.array_equal(cid[b, h, :n].cpu().numpy(), r["cid"]), (seed, b, h)
+            assert np.array_equal(counts[b, h, :rows].cpu().numpy(), r["counts"][:rows]), (seed, b, h)
+            assert g.rowwise_err(Kc[b, h, :rows].cpu().numpy(), r["Kc"][:rows]) <= 1e-3
+            assert g.rowwise_err(Vc[b, h, :rows].cpu().numpy(), r["Vc"][:rows]) <= 1e-3
+    assert compared >= (B * H + 1) // 2, (seed, compared)
+    print("seed", seed, "compared", compared, "N", N, "tau", tau, "rows", clens.cpu().numpy().tolist())
