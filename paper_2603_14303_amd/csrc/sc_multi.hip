@@ -5,15 +5,16 @@
 // -- (query j, head g of the group), nq * G of them -- are cut into blocks of 32 = two MFMA tiles; a
 // workgroup of four wavefronts owns one block and one contiguous range of cache rows (split-K), its
 // wavefronts take alternate 32-row steps of that range.  Per step and wavefront:
-//   * S^T = K_c Q^T with v_mfma_f32_16x16x16_bf16: the cache rows are the A operand, the query rows the
+//   * S^T = K_c Q^T with v_mfma_f32_16x16x32_bf16: the cache rows are the A operand, the query rows the
 //     B operand, both loaded straight from memory in operand layout (lane l: row l%16, 16-byte piece
 //     l/16 + 4j of the row; the contraction index may be permuted freely as long as both sides agree).
 //     The result lands with the query row on l%16 and four cache rows per lane, which is exactly the A
 //     layout of the second product, so the probabilities never move between lanes.
 //   * scale, + log2(size) bias, online softmax per query row (exp2 domain): in-lane over the lane's
 //     cache rows, then over the four lane groups with two row swaps.
-//   * O += P V with the same MFMA; P enters as two bf16 parts (leading part + remainder, two products), V rows
-//     loaded 16 bytes per lane and regrouped with v_perm into the B operand (column 8c + j on lane c).
+//   * O += P V with the same MFMA (the 32 rows of a step are one contraction); P enters as two bf16 parts
+//     (leading part + remainder, two products), V rows loaded 16 bytes per lane and regrouped with v_perm
+//     into the B operand (column 8c + j on lane c).
 // The four wavefronts fold through LDS, the workgroup writes one partial (acc[128], m, l) per query
 // row, and a second small kernel folds the splits.  Two launches instead of a hand-over inside the
 // kernel: the call is for several rows at once, a few microseconds of launch matter less than for
@@ -25,7 +26,6 @@
 
 namespace sc {
 
-typedef short mq_short4 __attribute__((ext_vector_type(4)));
 typedef float mq_float4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMqD = 128;
@@ -60,10 +60,8 @@ __device__ __forceinline__ int mq_splits_for(int rows, int max_splits, int min_r
     const int s = (rows + min_rows - 1) / min_rows;
     return s < 1 ? 1 : (s > max_splits ? max_splits : s);
 }
-__device__ __forceinline__ mq_short4 mq_op(uint32_t lo, uint32_t hi) {
-    const uint2 u = make_uint2(lo, hi);
-    return __builtin_bit_cast(mq_short4, u);
-}
+typedef __bf16 mq_bf16x8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ mq_bf16x8 mq_op8(const uint4 &u) { return __builtin_bit_cast(mq_bf16x8, u); }
 // max / sum over the four 16-lane rows of a wavefront, same position in the row
 __device__ __forceinline__ float mq_rows_max(float x) {
     auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -183,19 +181,17 @@ __global__ __launch_bounds__(kMqThreads, QT == 1 ? 2 : 1) void multi_attn_kernel
             for (int qt = 0; qt < QT; ++qt) {
                 mq_float4 s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    s = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(mq_op(kop[t][jj].x, kop[t][jj].y),
-                                                                 mq_op(qop[qt][jj].x, qop[qt][jj].y), s, 0, 0, 0);
-                    s = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(mq_op(kop[t][jj].z, kop[t][jj].w),
-                                                                 mq_op(qop[qt][jj].z, qop[qt][jj].w), s, 0, 0, 0);
-                }
+                for (int jj = 0; jj < 4; ++jj)     // a 16-byte piece per lane is one 32-element slice of the contraction
+                    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(mq_op8(kop[t][jj]), mq_op8(qop[qt][jj]), s, 0, 0, 0);
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
                     z[t][qt][i] = (cnt[t][i] > 0 && (!TAIL || base + 16 * t + 4 * kq + i < limit[qt]))
                                       ? fmaf(s[i], p.scale_log2, __log2f((float)cnt[t][i])) : -INFINITY;
             }
         // ---- online softmax per query row
-        mq_short4 pa[2][QT], pb[2][QT];   // probabilities as bf16 pairs: leading part and remainder
+        // probabilities as bf16: leading part and remainder; a lane's eight cache rows (4 of each half step) are
+        // its share of the 32-row contraction of the second product
+        uint4 pa[QT], pb[QT];
         float alpha[QT];
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
@@ -219,8 +215,8 @@ __global__ __launch_bounds__(kMqThreads, QT == 1 ? 2 : 1) void multi_attn_kernel
                 const uint32_t r01 = pack_bf16x2(e0 - bf16_lo(p01), e1 - bf16_hi(p01));
                 const uint32_t r23 = pack_bf16x2(e2 - bf16_lo(p23), e3 - bf16_hi(p23));
                 psum += (e0 + e1) + (e2 + e3);
-                pa[t][qt] = mq_op(p01, p23);
-                pb[t][qt] = mq_op(r01, r23);
+                if (t == 0) { pa[qt].x = p01; pa[qt].y = p23; pb[qt].x = r01; pb[qt].y = r23; }
+                else { pa[qt].z = p01; pa[qt].w = p23; pb[qt].z = r01; pb[qt].w = r23; }
             }
             l_run[qt] = fmaf(l_run[qt], alpha[qt], psum);
         }
@@ -240,21 +236,22 @@ __global__ __launch_bounds__(kMqThreads, QT == 1 ? 2 : 1) void multi_attn_kernel
         }
         // ---- O += P V
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int jn = 0; jn < 8; ++jn) {
+            uint32_t w[4];
 #pragma unroll
-            for (int jn = 0; jn < 8; ++jn) {
+            for (int t = 0; t < 2; ++t) {
                 const uint32_t d0 = dword_of(vr[t][0], jn >> 1), d1 = dword_of(vr[t][1], jn >> 1);
                 const uint32_t d2 = dword_of(vr[t][2], jn >> 1), d3 = dword_of(vr[t][3], jn >> 1);
-                const uint32_t lo = (jn & 1) ? pack_hi(d0, d1) : pack_lo(d0, d1);
-                const uint32_t hi = (jn & 1) ? pack_hi(d2, d3) : pack_lo(d2, d3);
-                const mq_short4 bb = mq_op(lo, hi);
-#pragma unroll
-                for (int qt = 0; qt < QT; ++qt)
-                {
-                    o[qt][jn] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa[t][qt], bb, o[qt][jn], 0, 0, 0);
-                    o[qt][jn] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pb[t][qt], bb, o[qt][jn], 0, 0, 0);
-                }
+                w[2 * t] = (jn & 1) ? pack_hi(d0, d1) : pack_lo(d0, d1);
+                w[2 * t + 1] = (jn & 1) ? pack_hi(d2, d3) : pack_lo(d2, d3);
             }
+            const mq_bf16x8 bb = mq_op8(make_uint4(w[0], w[1], w[2], w[3]));
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt) {
+                o[qt][jn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(mq_op8(pa[qt]), bb, o[qt][jn], 0, 0, 0);
+                o[qt][jn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(mq_op8(pb[qt]), bb, o[qt][jn], 0, 0, 0);
+            }
+        }
     };
     // two register sets: the loads of the next step fly while this one is computed
     {
