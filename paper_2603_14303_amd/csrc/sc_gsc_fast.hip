@@ -959,20 +959,24 @@ __global__ __launch_bounds__(kFastTaskThreads) void gsc_relocate_kernel(GscParam
         int basev;
         if (INLINE_PREFIX) {
             // rows of the chunks before the task: every one of them is closed by a delimiter
-            int part0 = 0, part1 = 0, part2 = 0, part3 = 0;
-            int m = lane;
-            for (; m + 3 * kWave < m0; m += 4 * kWave) {
-                part0 += pcount_bh[m] & kPcountMask;
-                part1 += pcount_bh[m + kWave] & kPcountMask;
-                part2 += pcount_bh[m + 2 * kWave] & kPcountMask;
-                part3 += pcount_bh[m + 3 * kWave] & kPcountMask;
+            // 2048 counts per round, four per lane and load, through a descriptor that ends at the task's first
+            // chunk (what lies beyond reads as zero): all loads of a round are in flight together, and a
+            // sequence of up to 32k tokens with chunks of 16 rows or more needs one round
+            const __amdgpu_buffer_rsrc_t pc_src = __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t *>(pcount_bh), (short)0, m0 * 4, 0x00020000);
+            const int mine_raw = (lane < nch) ? pcount_bh[m0 + lane] : 0;
+            int before = 0;
+            for (int mb = 0; mb < m0; mb += 32 * kWave) {
+                u32x4_t t[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) t[j] = __builtin_amdgcn_raw_buffer_load_b128(pc_src, (mb + 4 * kWave * j + 4 * lane) * 4, 0, 0);
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    before += (int)(((t[j].x & kPcountMask) + (t[j].y & kPcountMask)) + ((t[j].z & kPcountMask) + (t[j].w & kPcountMask)));
             }
-            for (; m < m0; m += kWave) part0 += pcount_bh[m] & kPcountMask;
-            int before = (part0 + part1) + (part2 + part3);
 #pragma unroll
             for (int d = 32; d >= 1; d >>= 1) before += __shfl_xor(before, d, kWave);
             // lane j: first output row of chunk m0 + j (lane nch: one past the task)
-            int mine = (lane < nch) ? (pcount_bh[m0 + lane] & kPcountMask) + ((m0 + lane < M - 1) ? 1 : 0) : 0;
+            int mine = (lane < nch) ? (mine_raw & kPcountMask) + ((m0 + lane < M - 1) ? 1 : 0) : 0;
             int incl = mine;
 #pragma unroll
             for (int d = 1; d < kWave; d <<= 1) {
