@@ -36,6 +36,7 @@ constexpr int kDecUnroll = 4;   // loads per step of the generic kernel
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef short dec_short4 __attribute__((ext_vector_type(4)));
+typedef __bf16 dec_bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned int dec_u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -410,7 +411,9 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
 
     float m_run = -INFINITY, l_run = 0.f;
     {
-        // Both products on the matrix cores (v_mfma_f32_16x16x16_bf16), 16 rows per step.
+        // Both products on the matrix cores, 16 rows per step (v_mfma_f32_16x16x32_bf16 for the scores, whose
+        // contraction runs over the 128 elements of a row; v_mfma_f32_16x16x16_bf16 for the sums, whose
+        // contraction is the 16 rows of the step).
         //   S = K_c q^T: the rows are spread over the lanes by column (16-byte pieces), the A operand wants
         //   one row per lane position, so the wave turns its 16 rows around through a 4 KB tile in LDS
         //   (row stride 272 B: the operand reads are free of bank conflicts).  Register u of lane group g
@@ -426,16 +429,16 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
         // 8c + j (for groups of up to four heads only lanes 0..15 hold anything).
         // P enters as two bf16 parts (leading part and remainder), so its rounding error is 2^-18.
         char *kt = s_kt + wave * kKtBytes;
-        // B operand of the first product: lane (g, c) holds elements 16ks + 4g .. + 3 of head c (zeros for c >= G:
+        // B operand of the first product: lane (g, c) holds elements 32ks + 8g .. + 7 of head c (zeros for c >= G:
         // the descriptor ends after the G heads of the group)
-        uint2 qb[8];
+        uint4 qb[4];
         {
             const auto q_src = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(reinterpret_cast<const bf16_t *>(p.Q) + ((int64_t)b * p.Hq + (int64_t)h * G) * D),
                                                                  (short)0, G * D * 2, 0x00020000);
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                const u32x2_dec_t v = __builtin_amdgcn_raw_buffer_load_b64(q_src, c * (D * 2) + (16 * ks + 4 * g) * 2, 0, 0);
-                qb[ks] = make_uint2(v.x, v.y);
+            for (int ks = 0; ks < 4; ++ks) {
+                const dec_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(q_src, c * (D * 2) + (32 * ks + 8 * g) * 2, 0, 0);
+                qb[ks] = make_uint4(v.x, v.y, v.z, v.w);
             }
         }
         f32x4_t accm[8];
@@ -447,10 +450,10 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
             wave_lds_handover();
             f32x4_t sc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                const uint2 a = *reinterpret_cast<const uint2 *>(kt + c * kKtRowBytes + (16 * ks + 4 * g) * 2);
-                sc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(dec_short4, a),
-                                                               __builtin_bit_cast(dec_short4, qb[ks]), sc, 0, 0, 0);
+            for (int ks = 0; ks < 4; ++ks) {
+                const uint4 a = *reinterpret_cast<const uint4 *>(kt + c * kKtRowBytes + (32 * ks + 8 * g) * 2);
+                sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(dec_bf16x8, a),
+                                                             __builtin_bit_cast(dec_bf16x8, qb[ks]), sc, 0, 0, 0);
             }
             wave_lds_handover();     // the tile is rewritten in the next step
             float sv[4];
