@@ -103,3 +103,45 @@ def test_random_structures(bf16, d, seed):
     # exact ties are possible (duplicated rows at tau just below 1) but must stay the exception
     assert compared >= (B * H + 1) // 2, (seed, compared, skipped)
     print("seed", seed, "compared", compared, "skipped", skipped, "N", N, "lens", lens.tolist(), "tau", tau, "rows", clens.cpu().numpy().tolist(), "err %.1e" % worst)
+
+
+@pytest.mark.parametrize("bf16,d,seed", [(True, 128, 300), (False, 64, 301)])
+def test_thousands_of_short_chunks(bf16, d, seed):
+    """A delimiter every few tokens: more chunks than one round of the relocation's count sum holds (2048)
+    and more tasks than the compress grid has workgroups per head, on a ragged batch."""
+    rng = np.random.default_rng(seed)
+    B, H, N = 2, 2, 24576
+    lens = np.array([N, 15001], np.int32)
+    mask = np.zeros((B, N), np.uint8)
+    K = np.zeros((B, H, N, d), np.float32)
+    V = np.zeros_like(K)
+    for b in range(B):
+        n = int(lens[b])
+        p = np.cumsum(rng.integers(1, 8, size=n)) - 1
+        mask[b, p[p < n]] = 1
+        for h in range(H):
+            K[b, h, :n], V[b, h, :n] = _random_keys(rng, mask[b], n, d, bf16)
+    tau = 0.9
+    dK, dV = g.to_device(K, bf16), g.to_device(V, bf16)
+    off, nch, sl = g.check_segment(mask, lens)
+    assert int(nch.min()) > 2048 and int(nch.max()) > 6000
+    Kc, Vc, counts, clens, cid = sc.sc_gsc_merge(dK, dV, off, nch, tau, seq_lens=sl, out_dtype=torch.float32,
+                                                 want_cluster_id=True)
+    torch.cuda.synchronize()
+    compared = 0
+    for b in range(B):
+        n = int(lens[b])
+        o = oracle.segment(mask[b], n)
+        for h in range(H):
+            r = oracle.compress_head(K[b, h, :n], V[b, h, :n], o, tau)
+            if r["chunk_margin"].min() <= 1e-9:
+                continue
+            compared += 1
+            rows = r["n_rows"]
+            assert int(clens[b, h]) == rows, (b, h, int(clens[b, h]), rows)
+            assert np.array_equal(cid[b, h, :n].cpu().numpy(), r["cid"]), (b, h)
+            assert np.array_equal(counts[b, h, :rows].cpu().numpy(), r["counts"][:rows]), (b, h)
+            ek = g.rowwise_err(Kc[b, h, :rows].cpu().numpy(), r["Kc"][:rows])
+            ev = g.rowwise_err(Vc[b, h, :rows].cpu().numpy(), r["Vc"][:rows])
+            assert ek <= 1e-3 and ev <= 1e-3, (b, h, ek, ev)
+    assert compared >= 2, compared
