@@ -1053,10 +1053,11 @@ hipError_t launch_gsc_fast(const GscParams &p, hipStream_t stream) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (p.count_only) return launch_gsc_scan(p, stream);   // adds up the counts: comp_lens, and nothing else is wanted
-    // Up to 128k tokens the relocation adds up the cluster counts before its task itself (one round of loads
-    // per 2048 chunks: a few rounds at the usual tens of tokens per chunk); longer sequences get the scan
-    // kernel, which does the sum once per (sequence, head).
-    const bool inline_prefix = p.N_max <= 131072;
+    // Up to 32k tokens the relocation adds up the cluster counts before its task itself (one round of loads
+    // per 2048 chunks; a sequence that is all delimiters costs sixteen rounds per workgroup, 0.8 ms per call);
+    // longer sequences get the scan kernel, which does the sum once per (sequence, head) whatever the
+    // number of chunks.
+    const bool inline_prefix = p.N_max <= 32768;
     if (!inline_prefix) {
         e = launch_gsc_scan(p, stream);
         if (e != hipSuccess) return e;
