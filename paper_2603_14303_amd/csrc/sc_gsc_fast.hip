@@ -948,6 +948,7 @@ __global__ __launch_bounds__(kFastTaskThreads) void gsc_relocate_kernel(GscParam
     bool base_bad = false;
     const int base_rows = (INLINE_PREFIX && APPEND) ? gsc_base_rows(p, bh, base_bad) : 0;
 
+    int summed = 0, summed_to = 0;      // INLINE_PREFIX: cluster counts of the chunks [0, summed_to), added up
     for (int task = wg_x; task < tasks; task += p.grid_x) {
         TaskOffsets to;
         to.m0 = task * C;
@@ -962,19 +963,25 @@ __global__ __launch_bounds__(kFastTaskThreads) void gsc_relocate_kernel(GscParam
             // 2048 counts per round, four per lane and load, through a descriptor that ends at the task's first
             // chunk (what lies beyond reads as zero): all loads of a round are in flight together, and a
             // sequence of up to 32k tokens with chunks of 16 rows or more needs one round
-            const __amdgpu_buffer_rsrc_t pc_src = __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t *>(pcount_bh), (short)0, m0 * 4, 0x00020000);
+            // A workgroup that takes several tasks (more tasks than workgroups: very short chunks) carries the
+            // sum on from its previous task instead of starting at the first chunk again.
+            const __amdgpu_buffer_rsrc_t pc_src = __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t *>(pcount_bh + summed_to), (short)0,
+                                                                                    (m0 - summed_to) * 4, 0x00020000);
             const int mine_raw = (lane < nch) ? pcount_bh[m0 + lane] : 0;
-            int before = 0;
-            for (int mb = 0; mb < m0; mb += 32 * kWave) {
+            int part = 0;
+            for (int mb = 0; mb < m0 - summed_to; mb += 32 * kWave) {
                 u32x4_t t[8];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) t[j] = __builtin_amdgcn_raw_buffer_load_b128(pc_src, (mb + 4 * kWave * j + 4 * lane) * 4, 0, 0);
 #pragma unroll
                 for (int j = 0; j < 8; ++j)
-                    before += (int)(((t[j].x & kPcountMask) + (t[j].y & kPcountMask)) + ((t[j].z & kPcountMask) + (t[j].w & kPcountMask)));
+                    part += (int)(((t[j].x & kPcountMask) + (t[j].y & kPcountMask)) + ((t[j].z & kPcountMask) + (t[j].w & kPcountMask)));
             }
 #pragma unroll
-            for (int d = 32; d >= 1; d >>= 1) before += __shfl_xor(before, d, kWave);
+            for (int d = 32; d >= 1; d >>= 1) part += __shfl_xor(part, d, kWave);
+            summed += part;
+            summed_to = m0;
+            const int before = summed;
             // lane j: first output row of chunk m0 + j (lane nch: one past the task)
             int mine = (lane < nch) ? (mine_raw & kPcountMask) + ((m0 + lane < M - 1) ? 1 : 0) : 0;
             int incl = mine;
