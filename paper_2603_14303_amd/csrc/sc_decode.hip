@@ -19,6 +19,7 @@
 // hand-over is described above publish_or_collect below.
 //
 // Generic kernel (d = 64, fp32 caches or queries): same split-K scheme, plain DPP all-reduce.
+#include <type_traits>
 #include "sc_device.h"
 #include "sc_host.h"
 
@@ -375,8 +376,11 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
 
     uint4 kb[U], vb[U];
     int cb[U];
-    // keys first, then sizes, then values: the scores are formed while the values are still on their way
-    auto issue = [&](int base) {
+    // keys first, then sizes, then values: the scores are formed while the values are still on their way.
+    // WHERE: 0 = the 16 rows of the step are merged rows, 1 = all of them are tail rows, 2 = the one step per
+    // (sequence, head) that holds the last merged and the first tail rows: only that one asks both sources.
+    auto issue_from = [&](int base, auto where) {
+        constexpr int WHERE = decltype(where)::value;
         const int row0 = base + g;
         const int off0 = row0 * (D * 2) + 16 * c;
         int toff[U];
@@ -388,23 +392,32 @@ __global__ __launch_bounds__(FastShape<G>::THREADS) void decode_bf16_kernel(DecP
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            dec_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(k_src, off0 + u * RPW * D * 2, 0, 0);
-            if (TAIL) v |= __builtin_amdgcn_raw_buffer_load_b128(kt_src, toff[u], 0, 0);
+            dec_u32x4 v = {0u, 0u, 0u, 0u};
+            if (WHERE != 1) v = __builtin_amdgcn_raw_buffer_load_b128(k_src, off0 + u * RPW * D * 2, 0, 0);
+            if (WHERE == 1) v = __builtin_amdgcn_raw_buffer_load_b128(kt_src, toff[u], 0, 0);
+            if (WHERE == 2) v |= __builtin_amdgcn_raw_buffer_load_b128(kt_src, toff[u], 0, 0);
             kb[u] = make_uint4(v.x, v.y, v.z, v.w);
         }
         __builtin_amdgcn_sched_barrier(0);     // keep the order of the requests: the scheduler has no reason to
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            cb[u] = (int)__builtin_amdgcn_raw_buffer_load_b32(n_src, (row0 + u * RPW) * 4, 0, 0);
-            if (TAIL) cb[u] = (toff[u] >= 0 && row0 + u * RPW < r1) ? 1 : cb[u];
+            cb[u] = (WHERE != 1) ? (int)__builtin_amdgcn_raw_buffer_load_b32(n_src, (row0 + u * RPW) * 4, 0, 0) : 0;
+            if (WHERE != 0) cb[u] = (toff[u] >= 0 && row0 + u * RPW < r1) ? 1 : cb[u];
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            dec_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(v_src, off0 + u * RPW * D * 2, 0, 0);
-            if (TAIL) v |= __builtin_amdgcn_raw_buffer_load_b128(vt_src, toff[u], 0, 0);
+            dec_u32x4 v = {0u, 0u, 0u, 0u};
+            if (WHERE != 1) v = __builtin_amdgcn_raw_buffer_load_b128(v_src, off0 + u * RPW * D * 2, 0, 0);
+            if (WHERE == 1) v = __builtin_amdgcn_raw_buffer_load_b128(vt_src, toff[u], 0, 0);
+            if (WHERE == 2) v |= __builtin_amdgcn_raw_buffer_load_b128(vt_src, toff[u], 0, 0);
             vb[u] = make_uint4(v.x, v.y, v.z, v.w);
         }
+    };
+    auto issue = [&](int base) {      // (base and rows_c are the same for the whole wavefront)
+        if (!TAIL || base + kRowsPerWaveStep <= rows_c) issue_from(base, std::integral_constant<int, 0>{});
+        else if (base >= rows_c) issue_from(base, std::integral_constant<int, 1>{});
+        else issue_from(base, std::integral_constant<int, 2>{});
     };
     int base = r0 + wave * kRowsPerWaveStep;
     issue(base);
