@@ -92,12 +92,12 @@ def _cpu_baseline(w, host, tau):
     independent (sequence, head) units; then the decode steps on the oracle's own merged cache, one core."""
     import multiprocessing as mp
     import oracle
-    reps = 3 if w.batch * w.kv_heads <= 16 else 1
     units = []
     t0 = time.perf_counter()
     tokens = 0
     caches = []
-    for rep in range(reps):
+    reps, rep = 1, 0
+    while rep < reps:
         caches = []
         for b in range(w.batch):
             n = int(host["lens"][b])
@@ -107,6 +107,9 @@ def _cpu_baseline(w, host, tau):
                 if rep == 0:
                     units.append((host["K"][b, h, :n], host["V"][b, h, :n], off, tau))
             tokens += n
+        if rep == 0:      # about eight seconds of one core for the compression sample, whatever the workload
+            reps = max(1, min(64, int(round(8.0 / max(time.perf_counter() - t0, 1e-3)))))
+        rep += 1
     t_comp = time.perf_counter() - t0
     # all host cores: the same single-thread code, one process per core over the independent units
     cores = len(os.sched_getaffinity(0))
@@ -124,14 +127,16 @@ def _cpu_baseline(w, host, tau):
     except Exception as e:   # no fork, no /dev/shm: the one-core figure stands alone
         all_cores = {"error": repr(e)}
     t0 = time.perf_counter()
-    steps = min(host["Q"].shape[0], 16)
-    G = w.group
-    for s in range(steps):
+    steps, s, G = min(host["Q"].shape[0], 4), 0, w.group
+    while s < steps:
         for b in range(w.batch):
             for h in range(w.kv_heads):
                 r = caches[b * w.kv_heads + h]
                 for g in range(G):
                     oracle.decode_head(host["Q"][s, b, h * G + g], r["Kc"], r["Vc"], r["counts"], r["n_rows"])
+        s += 1
+        if s == steps and steps == min(host["Q"].shape[0], 4):      # about three seconds of decode steps
+            steps = max(steps, min(host["Q"].shape[0], int(3.0 / max((time.perf_counter() - t0) / s, 1e-4))))
     t_dec = (time.perf_counter() - t0) / steps
     return {
         "value": tokens / t_comp / 1e6, "unit": "Mtok/s", "cores": 1, "kind": "oracle",
