@@ -1,6 +1,6 @@
 #!/bin/bash
 # Profiles `bench.py` for one workload with rocprofv3 and writes raw output plus text summaries under
-# $OUT (default gpurun_out/prof_<tag>): a kernel trace with statistics, the HBM traffic counters
+# $OUT (default: prof_<tag> under the output folder of the repository): a kernel trace with statistics, the HBM traffic counters
 # (FETCH_SIZE, WRITE_SIZE: one counter per run) and two passes of SQ counters (instruction mix, matrix-core
 # busy cycles, wait cycles).  The program follows `--` directly in every rocprofv3 command.
 #
