@@ -162,6 +162,17 @@ __device__ __forceinline__ int lane_gather(int x, int src_lane) {
 }
 
 __device__ __forceinline__ uint64_t ballot64(bool pred) { return __ballot(pred); }
+// 16 bytes that are read (written) once by this launch and not again soon: the non-temporal hint keeps
+// them from displacing lines that are (provisional rows, partials, offsets)
+typedef unsigned int stream_u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load16_stream(const void *p) {
+    const stream_u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const stream_u32x4_t *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store16_stream(void *p, const uint4 &v) {
+    const stream_u32x4_t t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<stream_u32x4_t *>(p));
+}
 __device__ __forceinline__ int first_bit(uint64_t m) { return __ffsll((unsigned long long)m) - 1; }
 
 // fp64 sum over the wave, every lane gets the total: DPP moves inside the rows of 16 lanes and row

@@ -81,6 +81,10 @@ struct RowRegs {
 };
 
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+// cache policy of the key/value row loads: nt = read once by this launch.  Every input row is read exactly once;
+// without the hint the rows displace the provisional rows (which the relocation reads back) from the caches
+// (32k-token layer: 54.7 -> 50.7 us per call; with it the relocation's own reads and writes carry the hint too)
+constexpr int kAuxReadOnce = 2;
 
 // Rows [first_row, first_row + nrows) through a buffer descriptor that ends after the last wanted row:
 // the hardware returns zeros for every access beyond it, so no lane needs a predicate or a 64-bit
@@ -102,7 +106,7 @@ __device__ __forceinline__ RowSource row_source(const bf16_t *base, int64_t stri
 __device__ __forceinline__ void load_rows(RowRegs &x, const RowSource &rs) {
 #pragma unroll
     for (int t = 0; t < 16; ++t) {
-        const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rs.rsrc, rs.voff + t * rs.step, 0, 0);
+        const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rs.rsrc, rs.voff + t * rs.step, 0, kAuxReadOnce);
         x.r[t] = make_uint4(v.x, v.y, v.z, v.w);
     }
 }
@@ -1021,8 +1025,8 @@ __global__ __launch_bounds__(kFastTaskThreads) void gsc_relocate_kernel(GscParam
                     const uint4 *vs = reinterpret_cast<const uint4 *>(vtmp_c + ((int64_t)src0 + (ok ? o : 0)) * kFastD);
 #pragma unroll
                     for (int q = 0; q < NP; ++q) {
-                        kk[k][q] = ok ? ks[q] : make_uint4(0, 0, 0, 0);
-                        vv[k][q] = ok ? vs[q] : make_uint4(0, 0, 0, 0);
+                        kk[k][q] = ok ? load16_stream(ks + q) : make_uint4(0, 0, 0, 0);
+                        vv[k][q] = ok ? load16_stream(vs + q) : make_uint4(0, 0, 0, 0);
                     }
                 }
 #pragma unroll
@@ -1032,7 +1036,7 @@ __global__ __launch_bounds__(kFastTaskThreads) void gsc_relocate_kernel(GscParam
                         uint4 *kd = reinterpret_cast<uint4 *>(Kc_c + (out0 + o) * kFastD);
                         uint4 *vd = reinterpret_cast<uint4 *>(Vc_c + (out0 + o) * kFastD);
 #pragma unroll
-                        for (int q = 0; q < NP; ++q) { kd[q] = kk[k][q]; vd[q] = vv[k][q]; }
+                        for (int q = 0; q < NP; ++q) { store16_stream(kd + q, kk[k][q]); store16_stream(vd + q, vv[k][q]); }
                     }
                 }
             }

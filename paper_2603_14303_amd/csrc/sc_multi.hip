@@ -142,6 +142,11 @@ __global__ __launch_bounds__(kMqThreads, QT == 1 ? 2 : 1) void multi_attn_kernel
         uint4 kop[2][4], vr[2][4];
         int cnt[2][4];
     };
+    // With one block of query rows every cache row is read once by the launch: the loads carry the
+    // non-temporal hint.  Several row blocks read the cache again, from the caches: no hint then.
+    auto get16 = [&](const bf16_t *ptr) {
+        return (p.row_blocks == 1) ? load16_stream(ptr) : *reinterpret_cast<const uint4 *>(ptr);
+    };
     auto load_step = [&](int base, StepRegs &x) {
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
@@ -150,9 +155,8 @@ __global__ __launch_bounds__(kMqThreads, QT == 1 ? 2 : 1) void multi_attn_kernel
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj)
                 x.kop[t][jj] = (krow >= r1) ? make_uint4(0, 0, 0, 0)
-                               : (TAIL && krow >= rows_c)
-                                     ? *reinterpret_cast<const uint4 *>(Ktbh + (int64_t)(krow - rows_c) * kMqD + 8 * (kq + 4 * jj))
-                                     : *reinterpret_cast<const uint4 *>(Kbh + (int64_t)krow * kMqD + 8 * (kq + 4 * jj));
+                               : (TAIL && krow >= rows_c) ? get16(Ktbh + (int64_t)(krow - rows_c) * kMqD + 8 * (kq + 4 * jj))
+                                                          : get16(Kbh + (int64_t)krow * kMqD + 8 * (kq + 4 * jj));
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int vrow = row0 + 4 * kq + i;
@@ -160,10 +164,10 @@ __global__ __launch_bounds__(kMqThreads, QT == 1 ? 2 : 1) void multi_attn_kernel
                     x.vr[t][i] = make_uint4(0, 0, 0, 0);
                     x.cnt[t][i] = 0;
                 } else if (TAIL && vrow >= rows_c) {
-                    x.vr[t][i] = *reinterpret_cast<const uint4 *>(Vtbh + (int64_t)(vrow - rows_c) * kMqD + 8 * c);
+                    x.vr[t][i] = get16(Vtbh + (int64_t)(vrow - rows_c) * kMqD + 8 * c);
                     x.cnt[t][i] = 1;
                 } else {
-                    x.vr[t][i] = *reinterpret_cast<const uint4 *>(Vbh + (int64_t)vrow * kMqD + 8 * c);
+                    x.vr[t][i] = get16(Vbh + (int64_t)vrow * kMqD + 8 * c);
                     x.cnt[t][i] = cnt_bh[vrow];
                 }
             }
