@@ -203,7 +203,13 @@ template <typename TO>
 __device__ __forceinline__ void store_tile(const floatx4_t (&D)[8], const floatx4_t &Dn, int ot, int n_out, TO *dst,
                                            int64_t dst_row0, int64_t row_limit, int lane) {
     const int g = lane >> 4;
-    TO *dst_c = dst + 8 * (lane & 15);   // dst is wave-uniform: only the column piece is per lane
+    // The provisional rows are read by the next launch from any chiplet: they are written through to the
+    // memory side (sc1) instead of staying dirty in this chiplet's L2 until the kernel ends.  dst is
+    // wave-uniform; its rows from dst_row0 on behind a descriptor, the lane's piece as offset.
+    constexpr int kRowBytes = kFastD * (int)sizeof(TO);
+    const int rows_left = (int)min(row_limit - dst_row0, (int64_t)(1 << 21));      // (n_out rows at most are stored)
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(dst + dst_row0 * kFastD, (short)0, rows_left * kRowBytes, 0x00020000);
+    constexpr int kAuxThrough = 16;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int o = 16 * ot + 4 * g + i;
@@ -213,7 +219,16 @@ __device__ __forceinline__ void store_tile(const floatx4_t (&D)[8], const floatx
             float v[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) v[j] = D[j][i] * inv;
-            store8(dst_c + (dst_row0 + o) * kFastD, v);
+            const int off = o * kRowBytes + 8 * (lane & 15) * (int)sizeof(TO);
+            if constexpr (sizeof(TO) == 2) {
+                const u32x4_t t = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
+                __builtin_amdgcn_raw_buffer_store_b128(t, rs, off, 0, kAuxThrough);
+            } else {
+                const u32x4_t t0 = {__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
+                const u32x4_t t1 = {__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])};
+                __builtin_amdgcn_raw_buffer_store_b128(t0, rs, off, 0, kAuxThrough);
+                __builtin_amdgcn_raw_buffer_store_b128(t1, rs, off + 16, 0, kAuxThrough);
+            }
         }
     }
 }
