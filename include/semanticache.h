@@ -348,8 +348,9 @@ sc_status sc_multi_attn(const void *Q, sc_dtype q_dtype, int nq,
 /* ------------------------------------------------------------------------------------------------
  * sc_stream_read_probe — a measuring aid for benchmarks, not a step of the method: reads the first
  * `bytes` bytes (rounded down to a multiple of 16) of a device buffer once, 16 bytes per lane, fully
- * coalesced, eight loads in flight per lane, i.e. with the access pattern of the kernels above and
- * nothing else to do.  Timing it on a buffer much larger than the caches gives the HBM read bandwidth
+ * coalesced, eight non-temporal loads in flight per lane, one workgroup of twelve wavefronts per CU on a
+ * contiguous slab of its own (the fastest of the shapes measured on MI355X), and nothing else to do.
+ * Timing it on a buffer much larger than the caches gives the HBM read bandwidth
  * a kernel can attain on the device, to put beside the nominal peak the rooflines are quoted against.
  *   src             device buffer, 16-byte aligned
  *   sink            device scratch of at least 4 KiB that the kernel writes to (contents meaningless)
