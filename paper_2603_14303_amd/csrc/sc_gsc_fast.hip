@@ -1064,11 +1064,19 @@ __global__ __launch_bounds__(kFastTaskThreads) void gsc_relocate_kernel(GscParam
 
 // ------------------------------------------------------------------------------------------------
 hipError_t launch_gsc_fast(const GscParams &p, hipStream_t stream) {
-    // single-wave workgroups loop over the tasks of their (sequence, head); about 6000 of them keep the
-    // 2048 wave slots of the chip fed without spending time on dispatching workgroups that find no task
+    // Single-wave workgroups, each looping over the tasks x, x + grid_x, ... of its (sequence, head).  A
+    // workgroup that takes one task is faster than one that walks several, and the host cannot know how many
+    // tasks there are: with chunks of a few dozen tokens, about one per 21 tokens per chunk of the task.  A
+    // small call gets a workgroup per expected task; a large one, where the many workgroups that find no task
+    // (a microsecond of one wave slot each) would cost more than the walking, one per two.  Shorter chunks
+    // make the workgroups loop, longer ones leave more of them without a task.
     const int max_tasks = (p.N_max + 1 + p.chunks_per_item - 1) / p.chunks_per_item;
     int gx = tuning().gsc_grid_x;
-    if (gx <= 0) gx = max(16, min(1024, 6144 / max(1, p.B * p.Hkv)));
+    if (gx <= 0) {
+        const int64_t rows_in_call = (int64_t)p.B * p.Hkv * p.N_max;
+        const int tokens_per_wg = 21 * p.chunks_per_item * (rows_in_call <= (int64_t(1) << 19) ? 1 : 2);
+        gx = max(16, p.N_max / tokens_per_wg);
+    }
     gx = max(1, min(max_tasks, gx));
     GscParams pc = p;
     pc.grid_x = gx;
