@@ -260,28 +260,49 @@ __device__ __forceinline__ void orow_to_operand_bytes_lds(char *lds_idx, int rel
     wave_lds_fence();
 }
 
-// D[j][i] += sum over rows of [index byte of row == want] * x[row][8c + j]; Dn[i] += number of such rows
-__device__ __forceinline__ void membership_mfma_b(const RowRegs &x, const uint32_t (&ob)[4], int want, int q_hi,
-                                                  floatx4_t (&D)[8], floatx4_t &Dn) {
-    const short4_t ones = {0x3F80, 0x3F80, 0x3F80, 0x3F80};
+// For T consecutive tiles of sixteen output rows, t = 0..T-1:  D[t][j][i] += sum over rows of
+// [index byte of row == 16 t + 4 (lane / 16) + i] * x[row][8c + j];  Dn[t][i] += number of such rows.  Rows in
+// registers, on v_mfma_f32_16x16x32_bf16 (contraction step qq covers rows 32 qq .. 32 qq + 31; index
+// (lane / 16, i), i = 0..7, stands for row 32 qq + 4 i + lane / 16 = register 8 qq + i): the B operand is built once
+// per column group and shared by the tiles.  Index bytes are relative to the first of the T tiles.
+template <int T>
+__device__ __forceinline__ void membership_mfma_tiles(const RowRegs &x, const uint32_t (&ob)[4], int c, int q_hi,
+                                                      floatx4_t (&D)[T][8], floatx4_t (&Dn)[T]) {
+    const uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        if (q < q_hi) {
-            short4_t a;
-            a[0] = (((ob[q] >> 0) & 0xFFu) == (uint32_t)want) ? (short)0x3F80 : (short)0;
-            a[1] = (((ob[q] >> 8) & 0xFFu) == (uint32_t)want) ? (short)0x3F80 : (short)0;
-            a[2] = (((ob[q] >> 16) & 0xFFu) == (uint32_t)want) ? (short)0x3F80 : (short)0;
-            a[3] = (((ob[q] >> 24) & 0xFFu) == (uint32_t)want) ? (short)0x3F80 : (short)0;
+    for (int qq = 0; qq < 2; ++qq) {
+        if (2 * qq < q_hi) {
+            bf16x8f_t a[T];
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const uint32_t want = (uint32_t)(c + 16 * t);
+                uint32_t aw[4];
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2) {
+                    const uint32_t b4 = ob[2 * qq + h2];
+                    const uint32_t m0 = (((b4 >> 0) & 0xFFu) == want) ? 0x3F80u : 0u;
+                    const uint32_t m1 = (((b4 >> 8) & 0xFFu) == want) ? 0x3F80u : 0u;
+                    const uint32_t m2 = (((b4 >> 16) & 0xFFu) == want) ? 0x3F80u : 0u;
+                    const uint32_t m3 = (((b4 >> 24) & 0xFFu) == want) ? 0x3F80u : 0u;
+                    aw[2 * h2] = m0 | (m1 << 16);
+                    aw[2 * h2 + 1] = m2 | (m3 << 16);
+                }
+                a[t] = __builtin_bit_cast(bf16x8f_t, make_uint4(aw[0], aw[1], aw[2], aw[3]));
+            }
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const uint32_t d0 = dword_of(x.r[4 * q + 0], j >> 1), d1 = dword_of(x.r[4 * q + 1], j >> 1);
-                const uint32_t d2 = dword_of(x.r[4 * q + 2], j >> 1), d3 = dword_of(x.r[4 * q + 3], j >> 1);
-                const uint32_t lo = (j & 1) ? pack_hi(d0, d1) : pack_lo(d0, d1);
-                const uint32_t hi = (j & 1) ? pack_hi(d2, d3) : pack_lo(d2, d3);
-                const uint2 bb = make_uint2(lo, hi);
-                D[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, __builtin_bit_cast(short4_t, bb), D[j], 0, 0, 0);
+                uint32_t w[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const uint32_t d0 = dword_of(x.r[8 * qq + 2 * k], j >> 1), d1 = dword_of(x.r[8 * qq + 2 * k + 1], j >> 1);
+                    w[k] = (j & 1) ? pack_hi(d0, d1) : pack_lo(d0, d1);
+                }
+                const bf16x8f_t bop = __builtin_bit_cast(bf16x8f_t, make_uint4(w[0], w[1], w[2], w[3]));
+#pragma unroll
+                for (int t = 0; t < T; ++t) D[t][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t], bop, D[t][j], 0, 0, 0);
             }
-            Dn = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, ones, Dn, 0, 0, 0);
+#pragma unroll
+            for (int t = 0; t < T; ++t) Dn[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[t], __builtin_bit_cast(bf16x8f_t, ones), Dn[t], 0, 0, 0);
         }
     }
 }
@@ -887,13 +908,22 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                 }
                 if (nseeds > 16) {
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // cluster index stores are done
+                    // kExtraTiles tiles of sixteen clusters per sweep over the chunk, keys and values in sweeps
+                    // of their own (the accumulators of both, or of a third tile, would not fit the registers).
+                    // The read-once hint stays on these loads: without it the large configurations lose more
+                    // to the displaced provisional rows than the sweeps gain from finding their rows cached.
+                    constexpr int kExtraTiles = 2;
                     for (int src = 0; src < 2; ++src) {
                         const bf16_t *Xbh = (src == 0) ? Kbh : Vbh;
                         TO *dst_c = (src == 0) ? ktmp_c : vtmp_c;
-                        for (int ot = 1; ot * 16 < nseeds; ++ot) {
-                            floatx4_t D[8], Dm = {0.f, 0.f, 0.f, 0.f};
+                        for (int ot = 1; ot * 16 < nseeds; ot += kExtraTiles) {
+                            floatx4_t D[kExtraTiles][8], Dm[kExtraTiles];
 #pragma unroll
-                            for (int j = 0; j < 8; ++j) D[j] = Dm;
+                            for (int t = 0; t < kExtraTiles; ++t) {
+                                Dm[t] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                                for (int j = 0; j < 8; ++j) D[t][j] = Dm[t];
+                            }
                             for (int rb = 0; rb < l; rb += kWin) {
                                 const int R = min(kWin, l - rb);
                                 RowRegs x;
@@ -903,10 +933,15 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                                     my_o = __hip_atomic_load(cid32_bh + start + rb + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                                 uint32_t ob[4];
                                 orow_to_operand_bytes(my_o - 16 * ot, lane, ob);
-                                membership_mfma_b(x, ob, c, (R + 15) >> 4, D, Dm);
+                                membership_mfma_tiles<kExtraTiles>(x, ob, c, (R + 15) >> 4, D, Dm);
                             }
-                            store_tile<TO>(D, Dm, ot, nseeds, dst_c, (int64_t)start, tmp_rows, lane);
-                            if (src == 1) store_sizes(Dm, ot, nseeds, stmp_bh, (int64_t)start, tmp_rows, lane);
+#pragma unroll
+                            for (int t = 0; t < kExtraTiles; ++t) {
+                                if ((ot + t) * 16 < nseeds) {
+                                    store_tile<TO>(D[t], Dm[t], ot + t, nseeds, dst_c, (int64_t)start, tmp_rows, lane);
+                                    if (src == 1) store_sizes(Dm[t], ot + t, nseeds, stmp_bh, (int64_t)start, tmp_rows, lane);
+                                }
+                            }
                         }
                     }
                 }
