@@ -62,8 +62,7 @@ constexpr int kLdsRowBytes = 272;                         // 256 B of keys + 16 
 constexpr int kLdsRinvOff = kWin * kLdsRowBytes;          // 64 reciprocal norms
 constexpr int kLdsBitsOff = kLdsRinvOff + 256;            // per row: yes lo/hi, unsure lo/hi (16 B)
 constexpr int kLdsIdxOff = kLdsBitsOff + kWin * 16;       // 64 output-index bytes
-constexpr int kLdsCrossOff = kLdsIdxOff + 64;             // per row: carried seeds it resembles (16 yes + 16 unsure bits)
-constexpr int kLdsSeedRinvOff = kLdsCrossOff + kWin * 4;  // reciprocal norms of the first 16 seeds of a long chunk
+constexpr int kLdsSeedRinvOff = kLdsIdxOff + 64;          // reciprocal norms of the first 16 seeds of a long chunk
 constexpr int kLdsWaveBytes = kLdsSeedRinvOff + 64;
 
 __device__ __forceinline__ void wave_lds_fence() {
@@ -541,6 +540,17 @@ __device__ __forceinline__ bool cosine_exceeds_f64_lds(const char *lds, int row_
     return dot / (sqrt(ss) * sqrt(cc)) > (double)tau;   // NaN compares false
 }
 
+__device__ __forceinline__ int nth_set_bit(uint64_t m, int k) {   // position of the k-th set bit, 0 <= k < popcount(m)
+    int pos = 0;
+#pragma unroll
+    for (int w = 32; w >= 1; w >>= 1) {
+        const uint64_t part = (m >> pos) & ((1ull << w) - 1ull);
+        const int cnt = __popcll(part);
+        if (k >= cnt) { k -= cnt; pos += w; }
+    }
+    return pos;
+}
+
 // ------------------------------------------------------------------------------------------------
 // Work decomposition shared by both passes: a task is `chunks_per_item` (<= 32) consecutive chunks of
 // one (sequence, head), handled by one single-wavefront workgroup, so a finished task frees its
@@ -739,15 +749,14 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                 const int l = to.at(idx + 1) - 1 - start;
                 const bool closed = (start + l) < n;
                 int nseeds = 0;
-                uint2 sa[8];
+                uint4 sa[4];   // lane (c, g): elements 32 ks + 8 g .. + 7 of the key of seed c (the MFMA's A operand)
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks) sa[ks] = make_uint2(0u, 0u);
+                for (int ks = 0; ks < 4; ++ks) sa[ks] = make_uint4(0u, 0u, 0u, 0u);
                 floatx4_t DK[8], DV[8], Dn = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int j = 0; j < 8; ++j) DK[j] = DV[j] = Dn;
                 float *s_rinv = reinterpret_cast<float *>(s_lds + kLdsRinvOff);
                 float *s_seed_rinv = reinterpret_cast<float *>(s_lds + kLdsSeedRinvOff);
-                uint32_t *s_cross = reinterpret_cast<uint32_t *>(s_lds + kLdsCrossOff);
                 for (int rb = 0; rb < l; rb += kWin) {
                     int lane = lane_id;
                     asm volatile("" : "+v"(lane));
@@ -771,40 +780,43 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                     // (rare) are fetched again
                     for (int sg = 0; sg * 16 < seeds_before && todo != 0ull; ++sg) {
                         const int ns = min(16, seeds_before - 16 * sg);
-                        uint2 sb[8];
+                        uint4 sb[4];
                         floatx4_t rs;
                         if (sg == 0) {
 #pragma unroll
-                            for (int ks = 0; ks < 8; ++ks) sb[ks] = sa[ks];
+                            for (int ks = 0; ks < 4; ++ks) sb[ks] = sa[ks];
                             rs = *reinterpret_cast<const floatx4_t *>(s_seed_rinv + 4 * g);
                         } else {
                             const int srow_c = (c < ns) ? __hip_atomic_load(seed_bh + start + 16 * sg + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
-                            const bf16_t *sp = Kbh + (int64_t)(start + srow_c) * p.stride_n + 4 * g;
+                            const bf16_t *sp = Kbh + (int64_t)(start + srow_c) * p.stride_n + 8 * g;
 #pragma unroll
-                            for (int ks = 0; ks < 8; ++ks)
-                                sb[ks] = (c < ns) ? *reinterpret_cast<const uint2 *>(sp + 16 * ks) : make_uint2(0u, 0u);
+                            for (int ks = 0; ks < 4; ++ks)
+                                sb[ks] = (c < ns) ? *reinterpret_cast<const uint4 *>(sp + 32 * ks) : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
                             for (int i = 0; i < 4; ++i) {
                                 const int sl = 16 * sg + 4 * g + i;
                                 rs[i] = (4 * g + i < ns) ? __int_as_float(__hip_atomic_load(stmp_bh + start + sl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) : 0.f;
                             }
                         }
-                        s_cross[lane] = 0u;
-                        wave_lds_fence();
+                        // (seed x row) products: lane (c, g) gets seeds 4g .. 4g+3 against row 16 J + c
                         floatx4_t cx[4];
 #pragma unroll
                         for (int J = 0; J < 4; ++J) cx[J] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                        for (int ks = 0; ks < 8; ++ks) {
-                            const short4_t a = __builtin_bit_cast(short4_t, sb[ks]);
+                        for (int ks = 0; ks < 4; ++ks) {
+                            const bf16x8f_t a = __builtin_bit_cast(bf16x8f_t, sb[ks]);
 #pragma unroll
                             for (int J = 0; J < 4; ++J) {
                                 if (J < nt) {
-                                    const uint2 v = *reinterpret_cast<const uint2 *>(s_lds + (16 * J + c) * kLdsRowBytes + (16 * ks + 4 * g) * 2);
-                                    cx[J] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, __builtin_bit_cast(short4_t, v), cx[J], 0, 0, 0);
+                                    const uint4 v = *reinterpret_cast<const uint4 *>(s_lds + (16 * J + c) * kLdsRowBytes + (32 * ks + 8 * g) * 2);
+                                    cx[J] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8f_t, v), cx[J], 0, 0, 0);
                                 }
                             }
                         }
+                        // per row one word: bit s = surely similar to seed s of the group, bit 16 + s = inside the
+                        // band.  A lane has the bits of its four seeds; an OR over the four lane groups completes
+                        // the word of row 16 J + c, and lane r keeps the word of row r.
+                        uint32_t cw = 0u;
 #pragma unroll
                         for (int J = 0; J < 4; ++J) {
                             if (J < nt) {
@@ -819,11 +831,10 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                                     w |= (yy ? 1u : 0u) << (4 * g + i);
                                     w |= (uu ? 1u : 0u) << (16 + 4 * g + i);
                                 }
-                                __hip_atomic_fetch_or(s_cross + 16 * J + c, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                                w = or_rows(w);
+                                if (g == J) cw = w;
                             }
                         }
-                        wave_lds_fence();
-                        const uint32_t cw = s_cross[lane];
                         const uint32_t valid = (1u << ns) - 1u;
                         const bool open = (todo >> lane) & 1ull;
                         uint32_t cyes = open ? (cw & valid) : 0u;
@@ -849,21 +860,34 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                         todo &= ~ballot64(cyes != 0u);
                     }
                     // seeds inside the block, from the bit matrix
+                    // (the rows still open are decided among themselves; the new seeds continue the chunk's numbering)
                     int new_row = -1;   // lane (c, g): block row of the seed that takes register slot c in this block
+                    uint64_t new_seeds = 0ull;
+                    {
+                        // the shortcut of the window path, over the open rows: a row is a seed iff no earlier open
+                        // row resembles it, provided every other open row then resembles an earlier such seed
+                        const uint64_t earlier_open = bits_below(lane) & todo;
+                        const bool is_open = (todo >> lane) & 1ull;
+                        const bool guess = is_open && ((yes_row & earlier_open) == 0ull);
+                        const uint64_t S = ballot64(guess);
+                        const uint64_t mine = yes_row & earlier_open & S;
+                        const bool fine = !is_open || (((unsure_row & earlier_open) == 0ull) && (guess || mine != 0ull));
+                        if (ballot64(fine) == ~0ull) {
+                            if (is_open) my_o = nseeds + __popcll(S & bits_below(guess ? lane : first_bit(mine)));
+                            const int k = c - nseeds;
+                            if (k >= 0 && k < __popcll(S)) new_row = nth_set_bit(S, k);
+                            new_seeds = S;
+                            nseeds += __popcll(S);
+                            todo = 0ull;
+                        }
+                    }
                     while (todo != 0ull) {
                         const int i = __builtin_amdgcn_readfirstlane(first_bit(todo));
                         todo &= ~(1ull << i);
+                        new_seeds |= 1ull << i;
                         const int o = nseeds;
                         nseeds += 1;
                         if (o < 16 && c == o) new_row = i;
-                        if (lane == 0) {
-                            // seed list of the chunk: row, and reciprocal norm (in the size staging area, which
-                            // gets its final contents only after the last block)
-                            const float ri = s_rinv[i];
-                            if (o < 16) s_seed_rinv[o] = ri;
-                            __hip_atomic_store(seed_bh + start + o, rb + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            __hip_atomic_store(stmp_bh + start + o, __float_as_int(ri), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        }
                         const bool cand = (todo >> lane) & 1ull;
                         bool yes = cand && ((yes_row >> i) & 1ull);
                         uint64_t recheck = ballot64(cand && ((unsure_row >> i) & 1ull));
@@ -877,11 +901,20 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                         todo &= ~got;
                         if (lane == i || yes) my_o = o;
                     }
+                    // seed list of the chunk, filed by the new seeds themselves once the block is decided: row,
+                    // and reciprocal norm (in the size staging area, which gets its final contents only after
+                    // the last block)
+                    if ((new_seeds >> lane) & 1ull) {
+                        const float ri = s_rinv[lane];
+                        if (my_o < 16) s_seed_rinv[my_o] = ri;
+                        __hip_atomic_store(seed_bh + start + my_o, rb + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        __hip_atomic_store(stmp_bh + start + my_o, __float_as_int(ri), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
                     // new seeds move into their register slots (keys still parked in LDS)
                     if (ballot64(new_row >= 0) != 0ull) {
 #pragma unroll
-                        for (int ks = 0; ks < 8; ++ks) {
-                            const uint2 v = *reinterpret_cast<const uint2 *>(s_lds + max(new_row, 0) * kLdsRowBytes + (16 * ks + 4 * g) * 2);
+                        for (int ks = 0; ks < 4; ++ks) {
+                            const uint4 v = *reinterpret_cast<const uint4 *>(s_lds + max(new_row, 0) * kLdsRowBytes + (32 * ks + 8 * g) * 2);
                             if (new_row >= 0) sa[ks] = v;
                         }
                     }
