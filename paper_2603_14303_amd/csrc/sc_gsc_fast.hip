@@ -540,6 +540,55 @@ __device__ __forceinline__ bool cosine_exceeds_f64_lds(const char *lds, int row_
     return dot / (sqrt(ss) * sqrt(cc)) > (double)tau;   // NaN compares false
 }
 
+// Alg. 1 over the open rows of a window or block without walking the seeds one by one.  Seeds are taken in row
+// order and a seed absorbs every open row of its chunk that resembles it, so a row joins the FIRST seed before
+// it that it resembles and is a seed itself iff there is none: the seed set T is the one set with
+//     r in T  <=>  no row of T before r (in r's chunk) resembles r            (induction over r: unique).
+// With F(S) = { r : no row of S before r resembles r }, T is the only fixed point of F.  Starting from the rows
+// that nothing earlier resembles (all of them seeds), F is applied until the set stops changing; when
+// "resembles" is transitive inside the chunks, the usual case, that is the first application.  Lane r brings,
+// restricted to the open rows before r in its own chunk, the rows it surely resembles (ye) and those inside
+// the band around tau (ue).  A pair inside the band can change the outcome only if its earlier row is a seed
+// that the later row, a seed itself, might resemble after all, or one before the seed the later row joins: the
+// first such pair of every row is settled in fp64 (the keys are parked in LDS) and the fixed point is taken
+// again.  Returns false, with nothing decided, if the set has not settled after a few applications of F or
+// pairs keep turning up: the caller then takes the seeds one at a time.
+__device__ __forceinline__ bool first_fit_fixed_point(const char *lds, uint64_t ye, uint64_t ue, bool is_open, float tau, int lane,
+                                                      uint64_t &seeds, int &my_seed) {
+    for (int pass = 0; pass < 8; ++pass) {
+        uint64_t S = ballot64(is_open && ye == 0ull);
+        bool settled = false;
+        for (int it = 0; it < 8 && !settled; ++it) {
+            const uint64_t S2 = ballot64(is_open && (ye & S) == 0ull);
+            settled = S2 == S;
+            S = S2;
+        }
+        if (!settled) return false;
+        const bool is_seed = (S >> lane) & 1ull;
+        const uint64_t mine = ye & S;                                   // not empty unless the row is a seed
+        const int first = is_seed ? lane : first_bit(mine);
+        const uint64_t doubt = ue & S & (is_seed ? ~0ull : bits_below(first & 63));
+        uint64_t doubtful = ballot64(is_open && doubt != 0ull);
+        if (doubtful == 0ull) {
+            seeds = S;
+            my_seed = is_open ? first : -1;
+            return true;
+        }
+        const int sd_mine = first_bit(doubt);
+        while (doubtful != 0ull) {
+            const int j = first_bit(doubtful);
+            doubtful &= doubtful - 1ull;
+            const int sd = __builtin_amdgcn_readlane(sd_mine, j);
+            const bool res = cosine_exceeds_f64_lds(lds, sd, j, tau, lane);
+            if (lane == j) {
+                ue &= ~(1ull << sd);
+                if (res) ye |= 1ull << sd;
+            }
+        }
+    }
+    return false;
+}
+
 __device__ __forceinline__ int nth_set_bit(uint64_t m, int k) {   // position of the k-th set bit, 0 <= k < popcount(m)
     int pos = 0;
 #pragma unroll
@@ -677,22 +726,8 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                 uint64_t seedmask = 0ull;
                 int my_seed = -1;
                 {
-                    // Shortcut: guess that a row is a seed iff no earlier row of its chunk resembles it.  If
-                    // every other row then resembles an earlier guessed seed (true whenever "resembles" is
-                    // transitive inside the chunks, the usual case), induction over the rows shows the guess
-                    // IS the outcome of Alg. 1: a guessed seed has no earlier similar row, hence no earlier
-                    // similar seed; any other row has an earlier similar seed and joins the first of them.
                     const uint64_t earlier = bits_below(lane) & my_range;
-                    const bool row_ok = lane < R;
-                    const bool guess = row_ok && ((yes_row & earlier) == 0ull);
-                    const uint64_t S = ballot64(guess);
-                    const uint64_t mine = yes_row & earlier & S;
-                    const bool fine = !row_ok || (((unsure_row & earlier) == 0ull) && (guess || mine != 0ull));
-                    if (ballot64(fine) == ~0ull) {
-                        seedmask = S;
-                        my_seed = guess ? lane : (row_ok ? (__ffsll((unsigned long long)mine) - 1) : -1);
-                        todo = 0ull;
-                    }
+                    if (first_fit_fixed_point(s_lds, yes_row & earlier, unsure_row & earlier, lane < R, tau, lane, seedmask, my_seed)) todo = 0ull;
                 }
                 while (todo != 0ull) {
                     const uint64_t mine = todo & my_range;
@@ -864,16 +899,12 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                     int new_row = -1;   // lane (c, g): block row of the seed that takes register slot c in this block
                     uint64_t new_seeds = 0ull;
                     {
-                        // the shortcut of the window path, over the open rows: a row is a seed iff no earlier open
-                        // row resembles it, provided every other open row then resembles an earlier such seed
                         const uint64_t earlier_open = bits_below(lane) & todo;
                         const bool is_open = (todo >> lane) & 1ull;
-                        const bool guess = is_open && ((yes_row & earlier_open) == 0ull);
-                        const uint64_t S = ballot64(guess);
-                        const uint64_t mine = yes_row & earlier_open & S;
-                        const bool fine = !is_open || (((unsure_row & earlier_open) == 0ull) && (guess || mine != 0ull));
-                        if (ballot64(fine) == ~0ull) {
-                            if (is_open) my_o = nseeds + __popcll(S & bits_below(guess ? lane : first_bit(mine)));
+                        uint64_t S = 0ull;
+                        int my_seed = -1;
+                        if (first_fit_fixed_point(s_lds, yes_row & earlier_open, unsure_row & earlier_open, is_open, tau, lane, S, my_seed)) {
+                            if (is_open) my_o = nseeds + __popcll(S & bits_below(my_seed));
                             const int k = c - nseeds;
                             if (k >= 0 && k < __popcll(S)) new_row = nth_set_bit(S, k);
                             new_seeds = S;

@@ -60,7 +60,7 @@ def _random_keys(rng, mask, n, d, bf16):
     return K, V
 
 
-@pytest.mark.parametrize("bf16,d,seed", [(True, 128, s) for s in range(12)] + [(False, 64, s) for s in range(100, 106)])
+@pytest.mark.parametrize("bf16,d,seed", [(True, 128, s) for s in range(24)] + [(False, 64, s) for s in range(100, 106)])
 def test_random_structures(bf16, d, seed):
     rng = np.random.default_rng(seed)
     B, H = 3, 2
@@ -145,3 +145,61 @@ def test_thousands_of_short_chunks(bf16, d, seed):
             ev = g.rowwise_err(Vc[b, h, :rows].cpu().numpy(), r["Vc"][:rows])
             assert ek <= 1e-3 and ev <= 1e-3, (b, h, ek, ev)
     assert compared >= 2, compared
+
+
+@pytest.mark.parametrize("seed,long_chunks", [(400, False), (401, True), (402, True)])
+def test_threshold_inside_a_narrow_band_of_similarities(seed, long_chunks):
+    """Every chunk is one tight bundle: all pairwise cosines lie within a few 1e-4 of each other and tau is
+    their median, so a large share of the pairs falls inside the band that the fp32 Gram product cannot
+    decide, "resembles" is far from transitive, and whether a row is a seed hinges on fp64 decisions about
+    earlier rows.  Cluster indices must still equal the oracle's."""
+    rng = np.random.default_rng(seed)
+    B, H, N, d = 1, 3, 2600, 128
+    lens = np.array([N], np.int32)
+    mask = np.zeros((B, N), np.uint8)
+    gaps = rng.integers(70, 260, size=N // 70 + 1) if long_chunks else rng.choice([9, 17, 24, 33, 48, 63], size=N // 9 + 1)
+    p = np.cumsum(gaps) - 1
+    mask[0, p[p < N]] = 1
+    cid_tok = np.concatenate([[0], np.cumsum(mask[0, :N - 1])]).astype(np.int64)
+    K = np.zeros((B, H, N, d), np.float32)
+    V = wl.round_to_bf16(rng.standard_normal((B, H, N, d)).astype(np.float32))
+    taus = []
+    for h in range(H):
+        centre = rng.standard_normal((int(cid_tok.max()) + 1, d)).astype(np.float32)
+        centre /= np.linalg.norm(centre, axis=1, keepdims=True)
+        noise = rng.standard_normal((N, d)).astype(np.float32) / np.sqrt(d)
+        K[0, h] = wl.round_to_bf16(centre[cid_tok] + 0.05 * noise)
+    # one threshold for all heads: the median cosine over the pairs inside the chunks of head 0
+    k0 = K[0, 0].astype(np.float64)
+    k0 /= np.linalg.norm(k0, axis=1, keepdims=True)
+    cos = []
+    for c in range(int(cid_tok.max()) + 1):
+        rows = np.nonzero((cid_tok == c) & (mask[0] == 0))[0]
+        if len(rows) > 1:
+            gm = k0[rows] @ k0[rows].T
+            cos.append(gm[np.triu_indices(len(rows), 1)])
+    cos = np.concatenate(cos)
+    tau = float(np.float32(np.median(cos)))
+    in_band = float(np.mean(np.abs(cos - tau) < 1e-4))
+    assert in_band > 0.1, in_band
+    dK, dV = g.to_device(K, True), g.to_device(V, True)
+    off, nch, sl = g.check_segment(mask, lens)
+    Kc, Vc, counts, clens, cid = sc.sc_gsc_merge(dK, dV, off, nch, tau, seq_lens=sl, out_dtype=torch.float32,
+                                                 want_cluster_id=True)
+    torch.cuda.synchronize()
+    o = oracle.segment(mask[0], N)
+    compared = 0
+    for h in range(H):
+        r = oracle.compress_head(K[0, h], V[0, h], o, tau)
+        if r["chunk_margin"].min() <= 1e-9:
+            continue
+        compared += 1
+        rows = r["n_rows"]
+        assert int(clens[0, h]) == rows, (h, int(clens[0, h]), rows)
+        assert np.array_equal(cid[0, h].cpu().numpy(), r["cid"]), h
+        assert np.array_equal(counts[0, h, :rows].cpu().numpy(), r["counts"][:rows]), h
+        ek = g.rowwise_err(Kc[0, h, :rows].cpu().numpy(), r["Kc"][:rows])
+        ev = g.rowwise_err(Vc[0, h, :rows].cpu().numpy(), r["Vc"][:rows])
+        assert ek <= 1e-3 and ev <= 1e-3, (h, ek, ev)
+    assert compared >= 2, compared
+    print("seed", seed, "tau", tau, "pairs inside the band %.2f" % in_band, "rows", clens.cpu().numpy().tolist())
