@@ -203,3 +203,48 @@ def test_threshold_inside_a_narrow_band_of_similarities(seed, long_chunks):
         assert ek <= 1e-3 and ev <= 1e-3, (h, ek, ev)
     assert compared >= 2, compared
     print("seed", seed, "tau", tau, "pairs inside the band %.2f" % in_band, "rows", clens.cpu().numpy().tolist())
+
+
+def test_chains_where_every_row_resembles_only_its_neighbours():
+    """Keys that turn by a fixed angle from row to row: a row resembles its neighbours and nobody else, so
+    seeds and members alternate along the chunk and whether a row is a seed depends on every row before
+    it.  A set-at-once decision of the seeds needs as many steps as the chunk has rows; chunks of 10 to
+    200 rows (inside a window, filling one, spanning several blocks) must come out as in the oracle."""
+    rng = np.random.default_rng(77)
+    d, H = 128, 2
+    lengths = [10, 40, 63, 5, 100, 30, 200, 64, 17, 130, 48, 48, 90]
+    N = sum(lengths) + len(lengths)
+    mask = np.zeros((1, N), np.uint8)
+    K = np.zeros((1, H, N, d), np.float32)
+    pos = 0
+    for L in lengths:
+        for h in range(H):
+            theta = 0.15 if h == 0 else 0.11                       # cos 0.9888 / 0.9940; two steps: 0.9553 / 0.9759
+            basis = np.linalg.qr(rng.standard_normal((d, 2)))[0]    # a random plane
+            # (a chunk too long for one turn of the circle repeats angles: runs of identical rows in the chain)
+            ang = theta * np.arange(L) if theta * L < 6.0 else np.cumsum(np.r_[0.0, rng.choice([theta, 0.0], size=L - 1, p=[0.3, 0.7])])
+            K[0, h, pos:pos + L] = np.cos(ang)[:, None] * basis[:, 0] + np.sin(ang)[:, None] * basis[:, 1]
+            K[0, h, pos + L] = rng.standard_normal(d)
+        mask[0, pos + L] = 1
+        pos += L + 1
+    K = wl.round_to_bf16(K * 3.0)
+    V = wl.round_to_bf16(rng.standard_normal((1, H, N, d)).astype(np.float32))
+    lens = np.array([N], np.int32)
+    dK, dV = g.to_device(K, True), g.to_device(V, True)
+    off, nch, sl = g.check_segment(mask, lens)
+    o = oracle.segment(mask[0], N)
+    for tau in (0.97, 0.985):
+        Kc, Vc, counts, clens, cid = sc.sc_gsc_merge(dK, dV, off, nch, tau, seq_lens=sl, out_dtype=torch.float32,
+                                                     want_cluster_id=True)
+        torch.cuda.synchronize()
+        for h in range(H):
+            r = oracle.compress_head(K[0, h], V[0, h], o, tau)
+            assert r["chunk_margin"].min() > 1e-9, (tau, h, r["chunk_margin"].min())
+            rows = r["n_rows"]
+            assert int(clens[0, h]) == rows, (tau, h, int(clens[0, h]), rows)
+            assert np.array_equal(cid[0, h].cpu().numpy(), r["cid"]), (tau, h)
+            assert np.array_equal(counts[0, h, :rows].cpu().numpy(), r["counts"][:rows]), (tau, h)
+            ek = g.rowwise_err(Kc[0, h, :rows].cpu().numpy(), r["Kc"][:rows])
+            ev = g.rowwise_err(Vc[0, h, :rows].cpu().numpy(), r["Vc"][:rows])
+            assert ek <= 1e-3 and ev <= 1e-3, (tau, h, ek, ev)
+        print("tau", tau, "rows", clens.cpu().numpy().tolist())
