@@ -220,7 +220,7 @@ def main():
                  Vc=torch.empty((B, H, cap, d), dtype=torch.bfloat16, device=dev),
                  counts=torch.empty((B, H, cap), dtype=torch.int32, device=dev),
                  lens=torch.empty((B, H), dtype=torch.int32, device=dev)) for _ in range(n_bufs)]
-    ws_g = sc.gsc_merge_workspace(B, H, N, d, dev)
+    ws_g = sc.gsc_merge_workspace(B, H, N, d, dev, torch.bfloat16)
     ws_d = sc.decode_attn_workspace(B, Hq, H, cap, d, dev)
     O = torch.empty((B, Hq, d), dtype=torch.bfloat16, device=dev)
 

@@ -129,8 +129,15 @@ sc_status sc_segment(const uint8_t *mask, int64_t mask_stride_b, const int32_t *
  *
  * Host errors: NULL required pointer, B/Hkv/N_max/cap <= 0, d not in {64,128}, bad dtype,
  * misaligned base pointers or strides not multiples of 16 bytes, workspace too small.
+ *
+ * Workspace: sc_gsc_merge_workspace_bytes(B, Hkv, N_max, d) bytes serve either output type.  The
+ * largest part holds the merged rows of Eq. 3 at provisional positions, in the output type:
+ * sc_gsc_merge_workspace_bytes_for(..., out_dtype) is what a call with that out_dtype needs (for
+ * bf16 about half: 544 instead of 1056 bytes per token and KV head at d = 128), and sc_gsc_merge and
+ * sc_gsc_merge_append accept a workspace of that size.  0 for a non-positive size or an unknown type.
  */
 size_t sc_gsc_merge_workspace_bytes(int B, int Hkv, int N_max, int d);
+size_t sc_gsc_merge_workspace_bytes_for(int B, int Hkv, int N_max, int d, sc_dtype out_dtype);
 sc_status sc_gsc_merge(const void *K, const void *V, sc_dtype in_dtype,
                        int64_t stride_b, int64_t stride_h, int64_t stride_n,
                        const int32_t *seq_lens,

@@ -54,6 +54,8 @@ def load_library() -> ctypes.CDLL:
     lib.sc_segment.argtypes = [vp, i64, vp, i32, i32, vp, i64, i32, vp, vp, sz, vp]
     lib.sc_gsc_merge_workspace_bytes.restype = sz
     lib.sc_gsc_merge_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    lib.sc_gsc_merge_workspace_bytes_for.restype = sz
+    lib.sc_gsc_merge_workspace_bytes_for.argtypes = [i32, i32, i32, i32, i32]
     lib.sc_gsc_merge.restype = i32
     lib.sc_gsc_merge.argtypes = [vp, vp, i32, i64, i64, i64, vp, vp, i64, vp, i32, i32, i32, i32, f32,
                                  vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
@@ -98,7 +100,7 @@ def load_library() -> ctypes.CDLL:
 EXPORTED = [
     "sc_status_string", "sc_last_runtime_error", "sc_version", "sc_tune_set", "sc_tune_get",
     "sc_check_lengths", "sc_stream_read_probe", "sc_segment_workspace_bytes", "sc_segment",
-    "sc_gsc_merge_workspace_bytes", "sc_gsc_merge",
+    "sc_gsc_merge_workspace_bytes", "sc_gsc_merge_workspace_bytes_for", "sc_gsc_merge",
     "sc_decode_attn_workspace_bytes", "sc_decode_attn_init_workspace", "sc_decode_attn",
     "sc_decode_attn_static", "sc_decode_attn_tail", "sc_gsc_merge_append",
     "sc_multi_attn_workspace_bytes", "sc_multi_attn", "sc_multi_attn_tail",
@@ -186,8 +188,13 @@ class Workspace:
         return self.buf.data_ptr()
 
 
-def gsc_merge_workspace(B: int, Hkv: int, N_max: int, d: int, device) -> Workspace:
-    return Workspace(load_library().sc_gsc_merge_workspace_bytes(B, Hkv, N_max, d), device)
+def gsc_merge_workspace(B: int, Hkv: int, N_max: int, d: int, device, out_dtype=None) -> Workspace:
+    """Workspace of sc_gsc_merge / sc_gsc_merge_append; with out_dtype (a torch dtype) sized for that output type only."""
+    lib = load_library()
+    if out_dtype is None:
+        return Workspace(lib.sc_gsc_merge_workspace_bytes(B, Hkv, N_max, d), device)
+    code = SC_BF16 if out_dtype == _torch().bfloat16 else SC_F32
+    return Workspace(lib.sc_gsc_merge_workspace_bytes_for(B, Hkv, N_max, d, code), device)
 
 
 def sc_gsc_merge(K, V, offsets, num_chunks, tau: float, seq_lens=None, cap: Optional[int] = None,
@@ -218,7 +225,7 @@ def sc_gsc_merge(K, V, offsets, num_chunks, tau: float, seq_lens=None, cap: Opti
     if cluster_id is None and want_cluster_id:
         cluster_id = torch.full((B, H, N), -9, dtype=torch.int32, device=dev)
     if workspace is None:
-        workspace = gsc_merge_workspace(B, H, N, d, dev)
+        workspace = gsc_merge_workspace(B, H, N, d, dev, Kc.dtype)
     for t in (Kc, Vc, counts, comp_lens):
         if not t.is_contiguous():
             raise SemantiCacheError("outputs must be contiguous")

@@ -129,6 +129,10 @@ size_t sc_gsc_merge_workspace_bytes(int B, int Hkv, int N_max, int d) {
     if (B <= 0 || Hkv <= 0 || N_max <= 0) return 0;
     return gsc_merge_workspace_bytes(B, Hkv, N_max, d);
 }
+size_t sc_gsc_merge_workspace_bytes_for(int B, int Hkv, int N_max, int d, sc_dtype out_dtype) {
+    if (B <= 0 || Hkv <= 0 || N_max <= 0 || !dtype_ok(out_dtype)) return 0;
+    return gsc_merge_workspace_bytes(B, Hkv, N_max, d, (int)elem_size(out_dtype));
+}
 
 static sc_status gsc_check_and_fill(const void *K, const void *V, sc_dtype in_dtype, int64_t stride_b, int64_t stride_h,
                                     int64_t stride_n, const int32_t *seq_lens, const int32_t *offsets,
@@ -151,7 +155,7 @@ static sc_status gsc_check_and_fill(const void *K, const void *V, sc_dtype in_dt
     if (!aligned4(counts) || !aligned4(comp_lens) || !aligned4(offsets) || !aligned4(num_chunks)) return SC_ERR_INVALID_ARG;
     if (offsets_stride_b < 2) return SC_ERR_INVALID_ARG;
     if (tau != tau) return SC_ERR_INVALID_ARG;
-    const size_t need = gsc_merge_workspace_bytes(B, Hkv, N_max, d);
+    const size_t need = gsc_merge_workspace_bytes(B, Hkv, N_max, d, (int)elem_size(out_dtype));
     if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SC_ERR_WORKSPACE;
 
     a.K = K; a.V = V; a.in_dtype = static_cast<DType>(in_dtype);

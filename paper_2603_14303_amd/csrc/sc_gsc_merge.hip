@@ -377,7 +377,7 @@ __global__ __launch_bounds__(kGscThreads) void gsc_merge_kernel(GscParams p) {
 }
 
 // ------------------------------------------------------------------------------------------------
-size_t gsc_merge_workspace_bytes(int B, int Hkv, int N_max, int d) {
+size_t gsc_merge_workspace_bytes(int B, int Hkv, int N_max, int d, int out_elem_bytes) {
     const size_t bh = (size_t)B * Hkv;
     size_t bytes = 0;
     bytes += align_up(bh * (size_t)N_max * 4, 256);          // cid
@@ -385,7 +385,7 @@ size_t gsc_merge_workspace_bytes(int B, int Hkv, int N_max, int d) {
     bytes += align_up(bh * ((size_t)N_max + 1) * 4, 256);    // pcount
     bytes += align_up(bh * ((size_t)N_max + 2) * 4, 256);    // rowbase
     bytes += align_up(bh * (size_t)N_max * 4, 256);          // stmp
-    bytes += 2 * align_up(bh * (size_t)N_max * (size_t)d * 4, 256);   // ktmp, vtmp (sized for fp32 output)
+    bytes += 2 * align_up(bh * (size_t)N_max * (size_t)d * (size_t)out_elem_bytes, 256);   // ktmp, vtmp: provisional rows of the output type
     return bytes;
 }
 
@@ -439,7 +439,7 @@ hipError_t launch_gsc_merge(const GscMergeArgs &a, hipStream_t stream) {
     p.stmp = reinterpret_cast<int32_t *>(w);
     w += align_up(bh * (size_t)a.N_max * 4, 256);
     p.ktmp = w;
-    w += align_up(bh * (size_t)a.N_max * (size_t)a.d * 4, 256);
+    w += align_up(bh * (size_t)a.N_max * (size_t)a.d * (a.out_dtype == DType::BF16 ? 2 : 4), 256);
     p.vtmp = w;
     p.cid = a.cluster_id ? a.cluster_id : ws_cid;
     p.cluster_id = a.cluster_id;

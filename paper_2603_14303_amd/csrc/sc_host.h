@@ -34,7 +34,8 @@ struct GscMergeArgs {
     bool count_only = false;              // only comp_lens is produced (bf16 / d = 128 fast path; elsewhere the full merge runs)
     void *ws;
 };
-size_t gsc_merge_workspace_bytes(int B, int Hkv, int N_max, int d);
+// out_elem_bytes: element size of the merged rows the call will write (4 sizes it for either output type)
+size_t gsc_merge_workspace_bytes(int B, int Hkv, int N_max, int d, int out_elem_bytes = 4);
 hipError_t launch_gsc_merge(const GscMergeArgs &a, hipStream_t stream);
 
 // ---- sc_gsc_merge_global: the whole sequence as one chunk (a.offsets / a.num_chunks are not used)

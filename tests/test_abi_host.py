@@ -46,6 +46,11 @@ def test_workspace_queries(lib):
     b = lib.sc_gsc_merge_workspace_bytes(4, 8, 32768, 128)
     assert a > 0 and a % 256 == 0 and b >= 4 * a - 4096
     assert lib.sc_gsc_merge_workspace_bytes(0, 8, 32768, 128) == 0
+    # sized for one output type: fp32 is the general size, bf16 halves the provisional rows
+    assert lib.sc_gsc_merge_workspace_bytes_for(1, 8, 32768, 128, 0) == a
+    half = lib.sc_gsc_merge_workspace_bytes_for(1, 8, 32768, 128, 1)
+    assert half % 256 == 0 and a - half == 2 * 8 * 32768 * 128 * 2
+    assert lib.sc_gsc_merge_workspace_bytes_for(1, 8, 32768, 128, 5) == 0
     d = lib.sc_decode_attn_workspace_bytes(1, 32, 8, 32768, 128)
     assert d > 0 and d % 256 == 0
     assert lib.sc_decode_attn_workspace_bytes(1, 30, 8, 32768, 128) == 0   # Hq not a multiple of Hkv
@@ -100,6 +105,9 @@ def test_gsc_merge_rejects_bad_arguments(lib):
     assert call(K=FAKE + 4) == 1
     assert call(tau=float("nan")) == 1
     assert call(ws=None) == 4 and call(wsb=need - 1) == 4 and call(ws=FAKE + 8) == 4
+    # a workspace sized for bf16 output is too small for fp32 output (odt=0 above), and enough for bf16
+    small = lib.sc_gsc_merge_workspace_bytes_for(1, 2, 1024, 64, 1)
+    assert small < need and call(wsb=small) == 4 and call(wsb=small - 1, odt=1) == 4
 
 
 def test_decode_rejects_bad_arguments(lib):
