@@ -62,6 +62,8 @@ int sc_tune_set(const char *key, int value) {
     else if (!strcmp(key, "gsc_grid_x")) t.gsc_grid_x = value;
     else if (!strcmp(key, "gsc_fast_path")) t.gsc_fast_path = value;
     else if (!strcmp(key, "gsc_chunks_per_task")) t.gsc_chunks_per_task = value;
+    else if (!strcmp(key, "multi_block_rows")) t.multi_block_rows = value;
+    else if (!strcmp(key, "multi_target_wgs")) t.multi_target_wgs = value;
     else return -1;
     return 0;
 }
@@ -78,6 +80,8 @@ int sc_tune_get(const char *key) {
     if (!strcmp(key, "gsc_grid_x")) return t.gsc_grid_x;
     if (!strcmp(key, "gsc_fast_path")) return t.gsc_fast_path;
     if (!strcmp(key, "gsc_chunks_per_task")) return t.gsc_chunks_per_task;
+    if (!strcmp(key, "multi_block_rows")) return t.multi_block_rows;
+    if (!strcmp(key, "multi_target_wgs")) return t.multi_target_wgs;
     return -1;
 }
 

@@ -381,11 +381,19 @@ __global__ __launch_bounds__(kMqD) void multi_attn_combine_kernel(MqParams p) {
 // ------------------------------------------------------------------------------------------------
 static void mq_shape(int B, int Hq, int Hkv, int nq, int cap /* merged + tail rows */, int &row_blocks, int &max_splits, int &min_rows, int &block_rows) {
     const int G = Hq / Hkv;
-    block_rows = (nq * G <= 16) ? 16 : kMqRows;
+    // Two tiles of query rows per workgroup read the cache once for 32 rows, but such a workgroup fills a
+    // compute unit alone (registers) and a few heads with 17..32 rows do not split into enough of them
+    // to cover the chip: those take one tile per workgroup, two row blocks (32 rows, 8 heads, 5 400 cache
+    // rows: 14.5 against 17.9 us).
+    block_rows = (nq * G <= 16 || (nq * G <= kMqRows && B * Hkv <= 8)) ? 16 : kMqRows;
+    if (tuning().multi_block_rows == 16 || tuning().multi_block_rows == 32) block_rows = tuning().multi_block_rows;
     row_blocks = (nq * G + block_rows - 1) / block_rows;
     min_rows = 256;
-    // enough workgroups to cover the 256 CUs about twice, never more splits than the capacity can feed
-    const int want = (512 + B * Hkv * row_blocks - 1) / (B * Hkv * row_blocks);
+    // One workgroup per compute unit, never more splits than the capacity can feed: a second round of
+    // workgroups waits for the first (measured 15-30 % slower with twice as many), and every split
+    // adds a partial per query row that the second kernel reads back.
+    const int target = max(1, tuning().multi_target_wgs);
+    const int want = (target + B * Hkv * row_blocks - 1) / (B * Hkv * row_blocks);
     const int by_cap = (cap + min_rows - 1) / min_rows;
     max_splits = max(1, min(min(kMqMaxSplits, want), by_cap));
 }

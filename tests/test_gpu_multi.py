@@ -135,3 +135,35 @@ def test_multi_attn_tail_mask_needs_the_matrix_core_path():
                             Vt=z(B, Hkv, tcap, d) + 2.0, tail_lens=torch.full((B,), tcap, dtype=torch.int32, device=g.DEV))
     torch.cuda.synchronize()
     assert torch.allclose(O, torch.full_like(O, 2.0), atol=1e-5)
+
+
+@pytest.mark.parametrize("knobs", [
+    dict(multi_block_rows=16, multi_target_wgs=64), dict(multi_block_rows=32, multi_target_wgs=1024),
+    dict(multi_block_rows=16, multi_target_wgs=1024), dict(multi_block_rows=32, multi_target_wgs=8),
+])
+def test_multi_attn_launch_shapes(knobs):
+    # one or two tiles of query rows per workgroup, few and many splits: the workspace query and the launch
+    # follow the same knobs, the result stays within the bound of the default shape
+    rng = np.random.default_rng(641)
+    B, Hkv, G, cap, nq, d = 2, 4, 4, 3000, 7, 128          # 28 query rows per KV head
+    Hq = Hkv * G
+    Q = _round_like(rng.standard_normal((nq, B, Hq, d)), True)
+    Kc, Vc = _round_like(rng.standard_normal((B, Hkv, cap, d)), True), _round_like(rng.standard_normal((B, Hkv, cap, d)), True)
+    counts = rng.integers(1, 40, (B, Hkv, cap)).astype(np.int32)
+    lens = rng.integers(cap // 2, cap + 1, (B, Hkv)).astype(np.int32)
+    lens[0, 0] = cap
+    want_O, want_L = oracle.multi_attn(Q, Kc, Vc, counts, lens)
+    dQ, dKc, dVc = g.to_device(Q, True), g.to_device(Kc, True), g.to_device(Vc, True)
+    dcounts, dlens = torch.from_numpy(counts).to(g.DEV), torch.from_numpy(lens).to(g.DEV)
+    old = {k: sc.tune_get(k) for k in knobs}
+    try:
+        for k, v in knobs.items():
+            sc.tune_set(k, v)
+        O, lse = sc.sc_multi_attn(dQ, dKc, dVc, dcounts, dlens, want_lse=True)
+        torch.cuda.synchronize()
+    finally:
+        for k, v in old.items():
+            sc.tune_set(k, v)
+    err = np.abs(O.float().cpu().numpy().astype(np.float64) - want_O) / np.maximum(1.0, np.abs(want_O))
+    assert err.max() <= 4e-3, (knobs, err.max())
+    assert np.abs(lse.cpu().numpy().astype(np.float64) - want_L).max() <= 1e-3
