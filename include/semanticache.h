@@ -377,9 +377,12 @@ sc_status sc_stream_read_probe(const void *src, size_t bytes, void *sink, void *
  *   "decode_mfma_min_group" sc_decode_attn (bf16, d = 128): query heads per KV head from which the
  *                          kernel of sc_multi_attn is used for the single row; 9 = never (the default)
  *   "gsc_fast_path"        0 forces the generic kernels even for bf16 / d = 128
- *   "gsc_chunks_per_task"  fast path: chunks handled by one single-wave workgroup task (1..32)
+ *   "gsc_chunks_per_task"  fast path: chunks handled by one single-wave workgroup task (1..32);
+ *                          <= 0 (the default) = 2, or 1 for a call of a few thousand tokens in all
  *   "gsc_chunks_per_item"  generic path: chunks per work item
- *   "gsc_grid_x"           workgroups per (sequence, KV head); <= 0 = chosen from B*Hkv
+ *   "gsc_grid_x"           workgroups per pass and (sequence, KV head); <= 0 = chosen from N_max
+ *   "multi_block_rows"     sc_multi_attn: query rows per workgroup, 16 or 32; <= 0 = chosen from the shape
+ *   "multi_target_wgs"     sc_multi_attn: workgroups the split count aims at (default 256)
  * Return 0 / the value, or -1 for an unknown key.
  */
 int sc_tune_set(const char *key, int value);

@@ -115,7 +115,7 @@ struct Tuning {
     int decode_mfma_min_group = 9;  // query heads per KV head from which single-row decode runs on the multi-row kernel (9 = never)
     int gsc_chunks_per_item = 16;   // chunks handled by one workgroup work item
     int gsc_grid_x = 0;             // workgroups per pass and (sequence, KV head); <= 0 picks it from the sequence length
-    int gsc_chunks_per_task = 2;    // fast path: chunks handled by one single-wave workgroup
+    int gsc_chunks_per_task = 0;    // fast path: chunks handled by one single-wave workgroup; <= 0: 2, or 1 for a call of a few thousand tokens
     int gsc_fast_path = 1;          // 0 forces the generic kernels even for bf16 / d = 128
     int multi_block_rows = 0;       // query rows per workgroup of sc_multi_attn: 16 or 32; <= 0 picks it from the shape of the call
     int multi_target_wgs = 256;     // workgroups the split count of sc_multi_attn aims at (one per compute unit)
