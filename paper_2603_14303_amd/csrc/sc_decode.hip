@@ -753,7 +753,7 @@ size_t decode_workspace_state_bytes(int B, int Hkv) { return kDecStatusBytes + a
 
 static int clamp_splits() { return max(1, min(kDecMaxSplits, tuning().decode_max_splits)); }   // knob <= 0: automatic
 
-size_t decode_workspace_bytes(int B, int Hq, int Hkv, int cap, int d) {
+size_t decode_workspace_bytes(int B, int Hq, int Hkv, int /* cap: the size does not depend on it */, int d) {
     const int G = Hq / Hkv;
     // sized for the largest split count the tuning knob may take, so the knob never invalidates a workspace
     const size_t split_k = align_up((size_t)B * Hkv * kDecMaxSplits * G * (d + kPartPad) * 4, 256);

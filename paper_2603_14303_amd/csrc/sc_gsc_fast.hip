@@ -24,7 +24,6 @@
 
 namespace sc {
 
-typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2f_t;
 typedef short short4_t __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8f_t __attribute__((ext_vector_type(8)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
@@ -34,15 +33,6 @@ constexpr int kFastD = 128;
 constexpr int kWin = 64;                 // rows of a window
 constexpr float kFastBand = 1e-4f;       // fp32 cosine error for d = 128 is < 2e-5; inside the band -> fp64
 
-__device__ __forceinline__ float dot2f(uint32_t a, uint32_t b, float c) {
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2f_t, a), __builtin_bit_cast(bf16x2f_t, b), c, false);
-}
-__device__ __forceinline__ float dot8(const uint4 &a, const uint4 &b) {
-    float s = dot2f(a.x, b.x, 0.f);
-    s = dot2f(a.y, b.y, s);
-    s = dot2f(a.z, b.z, s);
-    return dot2f(a.w, b.w, s);
-}
 __device__ __forceinline__ uint64_t bits_range(int lo, int hi) {   // bits [lo, hi), 0 <= lo <= hi <= 64
     const uint64_t upto_hi = (hi >= 64) ? ~0ull : ((1ull << hi) - 1ull);
     const uint64_t upto_lo = (lo >= 64) ? ~0ull : ((1ull << lo) - 1ull);
@@ -52,9 +42,6 @@ __device__ __forceinline__ uint64_t bits_below(int x) {   // bits [0, x), 0 <= x
     const uint32_t l = (x >= 32) ? 0xFFFFFFFFu : ((1u << x) - 1u);
     const uint32_t h = (x <= 32) ? 0u : ((x >= 64) ? 0xFFFFFFFFu : ((1u << (x - 32)) - 1u));
     return ((uint64_t)h << 32) | l;
-}
-__device__ __forceinline__ uint32_t bperm_u32(uint32_t x, int src_lane) {
-    return (uint32_t)__builtin_amdgcn_ds_bpermute(src_lane << 2, (int)x);
 }
 
 // LDS layout of a wavefront
@@ -167,15 +154,6 @@ __device__ __forceinline__ void membership_mfma(const RowRegs &x, const int (&or
             Dn = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, ones, Dn, 0, 0, 0);
         }
     }
-}
-
-// output indices from row order (lane r = row r) to the operand order of membership_mfma
-__device__ __forceinline__ void orow_to_operand_order(int my_o, int lane, int (&orow_t)[16]) {
-    const int g = lane >> 4;
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) orow_t[4 * q + i] = lane_gather(my_o, 16 * q + 4 * i + g);
 }
 
 // 8 elements of an output row, moved without conversion
@@ -906,7 +884,7 @@ __global__ __launch_bounds__(kFastTaskThreads, 2) void gsc_compress_kernel(GscPa
                         if (first_fit_fixed_point(s_lds, yes_row & earlier_open, unsure_row & earlier_open, is_open, tau, lane, S, my_seed)) {
                             if (is_open) my_o = nseeds + __popcll(S & bits_below(my_seed));
                             const int k = c - nseeds;
-                            if (k >= 0 && k < __popcll(S)) new_row = nth_set_bit(S, k);
+                            if (k >= 0 && k < (int)__popcll(S)) new_row = nth_set_bit(S, k);
                             new_seeds = S;
                             nseeds += __popcll(S);
                             todo = 0ull;
