@@ -24,7 +24,6 @@
 
 namespace sc {
 
-typedef short short4_t __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8f_t __attribute__((ext_vector_type(8)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
@@ -123,58 +122,8 @@ __device__ __forceinline__ float safe_rinv(float nsq) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Membership product on the matrix cores.  For output tile `ot` (16 output rows) and the rows in
-// registers: D[j][i] += sum over rows of [orow(row) == 16*ot + 4*(lane/16) + i] * x[row][8c + j],
-// Dn[i] += the number of such rows.  v_mfma_f32_16x16x16_bf16: A[m][k] lane l holds m = l%16,
-// k = 4*(l/16)+i; B[k][n] lane l holds n = l%16, k = 4*(l/16)+i; D[m][n] lane l holds n = l%16,
-// m = 4*(l/16)+i.  The k index (l/16, i) of k-step q stands for row 16q + 4i + l/16, which is register
-// 4q + i of the lane's own group, so the B operands are built from registers alone.
-// orow_t[q*4 + i] = output index of row 16q + 4i + lane/16 (or -1).
-__device__ __forceinline__ void membership_mfma(const RowRegs &x, const int (&orow_t)[16], int ot, int q_hi, int lane,
-                                                floatx4_t (&D)[8], floatx4_t &Dn) {
-    const int want = 16 * ot + (lane & 15);
-    const short4_t ones = {0x3F80, 0x3F80, 0x3F80, 0x3F80};
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        if (q < q_hi) {
-            short4_t a;
-            a[0] = (orow_t[4 * q + 0] == want) ? (short)0x3F80 : (short)0;
-            a[1] = (orow_t[4 * q + 1] == want) ? (short)0x3F80 : (short)0;
-            a[2] = (orow_t[4 * q + 2] == want) ? (short)0x3F80 : (short)0;
-            a[3] = (orow_t[4 * q + 3] == want) ? (short)0x3F80 : (short)0;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const uint32_t d0 = dword_of(x.r[4 * q + 0], j >> 1), d1 = dword_of(x.r[4 * q + 1], j >> 1);
-                const uint32_t d2 = dword_of(x.r[4 * q + 2], j >> 1), d3 = dword_of(x.r[4 * q + 3], j >> 1);
-                const uint32_t lo = (j & 1) ? pack_hi(d0, d1) : pack_lo(d0, d1);
-                const uint32_t hi = (j & 1) ? pack_hi(d2, d3) : pack_lo(d2, d3);
-                const uint2 bb = make_uint2(lo, hi);
-                D[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, __builtin_bit_cast(short4_t, bb), D[j], 0, 0, 0);
-            }
-            Dn = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, ones, Dn, 0, 0, 0);
-        }
-    }
-}
-
-// 8 elements of an output row, moved without conversion
-template <typename TO> struct RawPiece;
-template <> struct RawPiece<bf16_t> {
-    uint4 v;
-    __device__ __forceinline__ void load(const bf16_t *p) { v = *reinterpret_cast<const uint4 *>(p); }
-    __device__ __forceinline__ void store(bf16_t *p) const { *reinterpret_cast<uint4 *>(p) = v; }
-};
-template <> struct RawPiece<float> {
-    float4 a, b;
-    __device__ __forceinline__ void load(const float *p) {
-        a = *reinterpret_cast<const float4 *>(p);
-        b = *reinterpret_cast<const float4 *>(p + 4);
-    }
-    __device__ __forceinline__ void store(float *p) const {
-        *reinterpret_cast<float4 *>(p) = a;
-        *reinterpret_cast<float4 *>(p + 4) = b;
-    }
-};
-
+// Membership products on the matrix cores (Eq. 3 as a 0/1 matrix times the rows): membership_mfma_tiles and
+// membership_mfma_kv below.
 // scale the sums of tile `ot` by 1/size and store rows [16*ot, 16*ot+16) ∩ [0, n_out) at dst_row0 + o
 template <typename TO>
 __device__ __forceinline__ void store_tile(const floatx4_t (&D)[8], const floatx4_t &Dn, int ot, int n_out, TO *dst,
