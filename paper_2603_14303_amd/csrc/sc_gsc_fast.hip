@@ -1,23 +1,25 @@
 // Fast path of sc_gsc_merge for bf16 keys/values with head dim 128 (paper Sec. 2.3 Alg. 1 / Eq. 2 and
 // Sec. 2.4 Eq. 3).
 //
-// Three launches:
-//   compress  reads K and V once.  One single-wavefront workgroup handles a few consecutive chunks.
-//           It packs whole chunks (each with its closing delimiter) into "windows" of at most 64
+// Two launches (three for sequences of more than 32k tokens):
+//   compress  reads K and V once.  One single-wavefront workgroup handles a task of one or two consecutive
+//           chunks.  It packs whole chunks (each with its closing delimiter) into "windows" of at most 64
 //           rows.  Keys and values of a window are loaded together (16 lanes per row, 16-byte
 //           pieces); the keys are parked in LDS, the values wait in registers.  All pairwise
 //           cosines of the window come from one Gram matrix on the matrix cores, are compared with
-//           tau (decisions inside +-1e-4 of tau are redone in fp64) and filed as a bit matrix, on
-//           which the seeds of Alg. 1 are taken with a few bit operations per round.  A delimiter is
+//           tau (decisions inside +-1e-4 of tau are redone in fp64 where they matter) and filed as a bit
+//           matrix, on which the seed set of Alg. 1 is found as the fixed point of the first-fit rule
+//           (a few bit operations per application; seed by seed as the fallback).  A delimiter is
 //           a one-row chunk, so the seeds in row order ARE the output rows of the window.  The
 //           cluster means are a second small matrix product: (output row x window row) 0/1
 //           membership times (window row x 128) keys or values, fp32 accumulate, with a ones column
 //           giving the sizes.  Results go to provisional rows (the window's own first rows), because
 //           the final row of a window depends on every window before it.
-//   scan      exclusive scan of (clusters + delimiter) over the chunks of a (sequence, head).
+//   scan      (beyond 32k tokens only; shorter sequences add the counts up inside relocate) exclusive scan of
+//           (clusters + delimiter) over the chunks of a (sequence, head).
 //   relocate  moves the merged rows and sizes from their provisional to their final rows.
-// A chunk longer than one window runs over several 64-row blocks with its seeds carried along
-// (their keys are re-read through L2).
+// A chunk longer than one window runs over several 64-row blocks with its seeds carried along: the first
+// sixteen in registers, further ones re-read through L2.
 #include "sc_device.h"
 #include "sc_gsc_params.h"
 #include "sc_host.h"
