@@ -201,7 +201,10 @@ __global__ __launch_bounds__(256) void gsc_scan_kernel(GscParams p) {
     const int64_t bh = (int64_t)b * p.Hkv + h;
     const int M = p.num_chunks[b];
     if (M <= 0) {
-        if (tid == 0) p.comp_lens[bh] = -1;
+        if (tid == 0) {
+            p.comp_lens[bh] = -1;
+            if (p.budget) budget_probe_arrive(p.budget, -1, (unsigned int)(p.B * p.Hkv));
+        }
         return;
     }
     const int32_t *pcount_bh = p.pcount + bh * ((int64_t)p.N_max + 1);
@@ -244,7 +247,9 @@ __global__ __launch_bounds__(256) void gsc_scan_kernel(GscParams p) {
     }
     if (tid == 0) {
         rowbase_bh[M] = running;
-        p.comp_lens[bh] = (!base_bad && running <= p.cap) ? running : -1;
+        const int rows = (!base_bad && running <= p.cap) ? running : -1;
+        p.comp_lens[bh] = rows;
+        if (p.budget) budget_probe_arrive(p.budget, rows, (unsigned int)(p.B * p.Hkv));
     }
 }
 
@@ -409,6 +414,11 @@ static hipError_t launch_typed(const GscParams &p, hipStream_t stream) {
     return hipGetLastError();
 }
 
+// (the fast path addresses a window of rows with 32-bit byte offsets: 64 rows of stride_n elements)
+bool gsc_merge_takes_fast_path(const GscMergeArgs &a) {
+    return a.in_dtype == DType::BF16 && a.d == 128 && tuning().gsc_fast_path && a.stride_n <= (int64_t(1) << 22);
+}
+
 hipError_t launch_gsc_merge(const GscMergeArgs &a, hipStream_t stream) {
     GscParams p;
     p.K = a.K; p.V = a.V;
@@ -424,6 +434,7 @@ hipError_t launch_gsc_merge(const GscMergeArgs &a, hipStream_t stream) {
     p.counts = a.counts; p.comp_lens = a.comp_lens;
     p.base_lens = a.base_lens;
     p.count_only = a.count_only ? 1 : 0;
+    p.budget = nullptr;
     p.chunks_per_item = max(1, min(kMaxChunksPerItem, tuning().gsc_chunks_per_item));
 
     const size_t bh = (size_t)a.B * a.Hkv;
@@ -444,8 +455,8 @@ hipError_t launch_gsc_merge(const GscMergeArgs &a, hipStream_t stream) {
     p.cid = a.cluster_id ? a.cluster_id : ws_cid;
     p.cluster_id = a.cluster_id;
 
-    // (the fast path addresses a window of rows with 32-bit byte offsets: 64 rows of stride_n elements)
-    if (a.in_dtype == DType::BF16 && a.d == 128 && tuning().gsc_fast_path && a.stride_n <= (int64_t(1) << 22)) {
+    if (gsc_merge_takes_fast_path(a)) {
+        if (a.count_only) p.budget = reinterpret_cast<BudgetState *>(a.budget_state);
         // Two chunks per task pack fuller windows and halve the workgroups; a call so small that every window
         // finds a free wave slot at once (a stretch of tokens appended during decoding) is faster with one,
         // because no window then waits behind another in its workgroup (256 tokens, 8 heads: 19 against 23 us).

@@ -32,11 +32,13 @@ struct GscMergeArgs {
     const int32_t *base_lens = nullptr;   // append mode: rows already in the outputs, [B, Hkv]
     const float *tau_dev = nullptr;       // threshold in device memory (overrides tau)
     bool count_only = false;              // only comp_lens is produced (bf16 / d = 128 fast path; elsewhere the full merge runs)
+    void *budget_state = nullptr;         // counting probe of the budget search: its scan kernel also moves the bracket (fast path only)
     void *ws;
 };
 // out_elem_bytes: element size of the merged rows the call will write (4 sizes it for either output type)
 size_t gsc_merge_workspace_bytes(int B, int Hkv, int N_max, int d, int out_elem_bytes = 4);
 hipError_t launch_gsc_merge(const GscMergeArgs &a, hipStream_t stream);
+bool gsc_merge_takes_fast_path(const GscMergeArgs &a);
 
 // ---- sc_gsc_merge_global: the whole sequence as one chunk (a.offsets / a.num_chunks are not used)
 size_t gsc_global_workspace_bytes(int B, int Hkv, int N_max, int d);
