@@ -4,7 +4,8 @@
 // 32 mask bytes with two 16-byte loads (both in flight together), turns them into a 64-bit "is
 // delimiter" word, a block-wide exclusive scan of the popcounts gives each thread the rank of its first
 // delimiter, and the positions are scattered to offsets[rank + 1].  A tile costs three barriers, so a
-// 32k-token sequence is one tile.  Pure integer work, HBM traffic = the mask once.
+// 32k-token sequence is one tile.  The mask bytes of the first tile are requested together with the sequence
+// length, not after it.  Pure integer work, HBM traffic = the mask once.
 #include "sc_device.h"
 #include "sc_host.h"
 
@@ -40,10 +41,15 @@ __global__ __launch_bounds__(kSegThreads) void segment_kernel(
 
     if (tid == 0) off[0] = 0;
     int running = 0;  // delimiters found in earlier tiles
-    for (int base = 0; base < n; base += kSegThreads * kSegBytesPerThread) {
+    // (the first tile always runs, so that its requests are issued before the length is known; an empty
+    // sequence finds no delimiter in it)
+    int base = 0;
+    do {
         const int i0 = base + tid * kSegBytesPerThread;
         uint64_t bits = 0;
-        if (i0 + kSegBytesPerThread <= n && aligned) {
+        // (whether the 32 bytes may be read depends on the row's capacity, not on the sequence length: the
+        // request does not wait for seq_lens[b]; bytes at and beyond the length are dropped afterwards)
+        if (i0 + kSegBytesPerThread <= n_max && aligned) {
             constexpr int kLoads = kSegBytesPerThread / 16;
             uint4 v[kLoads];
 #pragma unroll
@@ -54,6 +60,8 @@ __global__ __launch_bounds__(kSegThreads) void segment_kernel(
                                      (nonzero_bytes4(v[q].w) << 12);
                 bits |= (uint64_t)b16 << (16 * q);
             }
+            const int keep = n - i0;   // bytes of this thread inside the sequence
+            bits = (keep >= kSegBytesPerThread) ? bits : ((keep <= 0) ? 0ull : (bits & ((1ull << keep) - 1ull)));
         } else {
             for (int k = 0; k < kSegBytesPerThread; ++k)
                 if (i0 + k < n && row[i0 + k] != 0) bits |= 1ull << k;
@@ -90,7 +98,8 @@ __global__ __launch_bounds__(kSegThreads) void segment_kernel(
         }
         running += tile_total;
         __syncthreads();  // s_wave_total / s_tile_total are reused by the next tile
-    }
+        base += kSegThreads * kSegBytesPerThread;
+    } while (base < n);
     if (tid == 0) {
         const int M = running + 1;
         if (M + 1 <= offsets_cap) {
