@@ -123,7 +123,7 @@ sc_status sc_segment(const uint8_t *mask, int64_t mask_stride_b, const int32_t *
     if (offsets_cap < 2) return SC_ERR_CAPACITY;
     if (mask_stride_b < N_max || offsets_stride_b < offsets_cap) return SC_ERR_INVALID_ARG;
     if (!aligned4(offsets) || !aligned4(num_chunks) || (seq_lens && !aligned4(seq_lens))) return SC_ERR_INVALID_ARG;
-    if (B > 65535 * 32) return SC_ERR_UNSUPPORTED;
+    if (B > 65535 * 32 || (N_max + 32767) / 32768 > 65535) return SC_ERR_UNSUPPORTED;   // grid sizes
     return runtime_status(launch_segment(mask, mask_stride_b, seq_lens, B, N_max, offsets, offsets_stride_b,
                                          offsets_cap, num_chunks, static_cast<hipStream_t>(stream)));
 }

@@ -55,6 +55,15 @@ def test_segment_capacity_overflow_is_flagged():
     torch.cuda.synchronize()
     assert nch.tolist() == [-1, 6]
     assert off[1, :7].tolist() == [0, 1, 2, 3, 4, 5, 65]
+    # several tiles of mask per sequence, each filed by a workgroup of its own: none writes beyond the capacity
+    mask = torch.ones((2, 70000), dtype=torch.uint8, device=g.DEV)
+    mask[1, 40:69990] = 0
+    wide = torch.full((2, 200), -5, dtype=torch.int32, device=g.DEV)
+    _, nch = sc.sc_segment(mask, None, offsets=wide[:, :100])
+    torch.cuda.synchronize()
+    assert nch.tolist() == [-1, 51]
+    assert wide[0, :100].tolist() == list(range(100)) and (wide[:, 100:] == -5).all()
+    assert wide[1, :52].tolist() == list(range(41)) + list(range(69991, 70001)) + [70001]
 
 
 # ------------------------------------------------------------------ sc_gsc_merge + sc_decode_attn
