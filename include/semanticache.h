@@ -108,9 +108,10 @@ sc_status sc_segment(const uint8_t *mask, int64_t mask_stride_b, const int32_t *
  * Inputs are expected to be finite: the sums run on matrix cores over groups of neighbouring chunks
  * with 0/1 weights, so a NaN or Inf element can turn the same column of other rows of its group into
  * NaN.  The clustering decisions themselves treat NaN similarities as "not above tau".
- * With bf16 inputs, bf16 or fp32 outputs and d = 128 the call runs three kernels (cluster + merge
- * into provisional rows, exclusive scan of the row counts, relocation); other combinations run a
- * generic three-kernel path with the same results.
+ * With bf16 inputs, bf16 or fp32 outputs and d = 128 the call runs two kernels (cluster + merge
+ * into provisional rows; relocation to the final rows, which adds up the row counts itself), three
+ * for sequences of more than 32768 tokens (an exclusive scan of the row counts in between); other
+ * combinations run a generic three-kernel path with the same results.
  *
  *   K, V            device [B, Hkv, N_max, d] of in_dtype, addressed as
  *                   base + b*stride_b + h*stride_h + n*stride_n (+ e), strides in ELEMENTS;
