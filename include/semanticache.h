@@ -384,6 +384,8 @@ sc_status sc_stream_read_probe(const void *src, size_t bytes, void *sink, void *
  *   "gsc_grid_x"           workgroups per pass and (sequence, KV head); <= 0 = chosen from N_max
  *   "multi_block_rows"     sc_multi_attn: query rows per workgroup, 16 or 32; <= 0 = chosen from the shape
  *   "multi_target_wgs"     sc_multi_attn: workgroups the split count aims at (default 256)
+ *                          (these two enter sc_multi_attn_workspace_bytes: set them before asking for the
+ *                          size; a workspace that has become too small is refused with SC_ERR_WORKSPACE)
  * Return 0 / the value, or -1 for an unknown key.
  */
 int sc_tune_set(const char *key, int value);
