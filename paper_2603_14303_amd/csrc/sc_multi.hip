@@ -346,6 +346,11 @@ __global__ __launch_bounds__(kMqD) void multi_attn_combine_kernel(MqParams p) {
     const int rb = R / p.block_rows, row = R - rb * p.block_rows;
     const float *part = p.part + (((bh * p.row_blocks + rb) * (int64_t)p.max_splits) * p.block_rows + row) * kMqPart;
     const int64_t split_stride = (int64_t)p.block_rows * kMqPart;
+    // the first sixteen splits' values of this thread's column are requested together with the (m, l) pairs,
+    // not after the weights are known
+    float v0[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v0[k] = (k < S) ? part[k * split_stride + col] : 0.f;
     if (col < kWave) {
         const float m = (col < S) ? part[col * split_stride + kMqD] : -INFINITY;
         const float l = (col < S) ? part[col * split_stride + kMqD + 1] : 0.f;
@@ -362,7 +367,9 @@ __global__ __launch_bounds__(kMqD) void multi_attn_combine_kernel(MqParams p) {
     }
     __syncthreads();
     float acc = 0.f;
-    for (int s0 = 0; s0 < S; s0 += 16) {
+#pragma unroll
+    for (int k = 0; k < 16; ++k) acc = fmaf(v0[k], (k < S) ? s_w[k] : 0.f, acc);
+    for (int s0 = 16; s0 < S; s0 += 16) {
         float v[16];
 #pragma unroll
         for (int k = 0; k < 16; ++k) v[k] = (s0 + k < S) ? part[(s0 + k) * split_stride + col] : 0.f;
