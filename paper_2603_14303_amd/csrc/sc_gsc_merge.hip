@@ -209,7 +209,7 @@ __global__ __launch_bounds__(256) void gsc_scan_kernel(GscParams p) {
     }
     const int32_t *pcount_bh = p.pcount + bh * ((int64_t)p.N_max + 1);
     int32_t *rowbase_bh = p.rowbase + bh * ((int64_t)p.N_max + 2);
-    constexpr int kItems = 4;
+    constexpr int kItems = 8;
     bool base_bad;
     int running = gsc_base_rows(p, bh, base_bad);
     for (int base = 0; base < M; base += 256 * kItems) {
