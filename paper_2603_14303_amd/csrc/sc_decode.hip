@@ -304,7 +304,8 @@ __device__ __forceinline__ void combine_splits(const DecParams &p, const float *
 }
 
 template <int G> struct FastShape {
-    static constexpr int WAVES = 12;                  // 12 waves x 8 KB of loads in flight per CU, <= 170 VGPRs each
+    static constexpr int WAVES = 6;                   // two such workgroups per CU: 12 waves x 8 KB of loads in flight, <= 170 VGPRs each
+                                                      // (one workgroup of 12 waves per CU was 1-8 % slower on every configuration)
     static constexpr int THREADS = WAVES * kWave;
     static constexpr int U = 4;                       // wave-wide loads of K (and of V) per step: 16 rows, one MFMA tile
 };
